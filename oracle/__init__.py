@@ -1,0 +1,151 @@
+"""CPU oracle for the CFGzip hot path.  TEST INFRASTRUCTURE ONLY.
+
+Thin numpy wrappers over ``cfgzip_oracle.c`` (compiled with gcc into
+``liboracle.so`` next to it).  Only tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the HIP library and its Python
+binding never do, and this package never imports them.
+
+``oracle.displacement`` additionally holds a pure-Python implementation of the
+paper's general displacement computation (Algorithm 1 with the stack-adjacency
+relation of Appendix C) for tiny grammars; it pins the regular-grammar reading
+used by ``signatures``.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cfgzip_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC",
+                               "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_build_classes.restype = ctypes.c_int32
+        _lib.oracle_num_threads.restype = ctypes.c_int
+        _lib.oracle_splitmix64_next.restype = ctypes.c_uint64
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def words_for(n: int) -> int:
+    return (int(n) + 31) // 32
+
+
+def signatures(tok_bytes, tok_off, table) -> np.ndarray:
+    """uint16 [V, S]: sig[t][q] = state reached from q on the bytes of token t."""
+    tok_bytes = _c(tok_bytes, np.uint8)
+    tok_off = _c(tok_off, np.int64)
+    table = _c(table, np.uint16)
+    V = tok_off.shape[0] - 1
+    S = table.shape[0]
+    assert table.shape == (S, 256)
+    sig = np.empty((V, S), dtype=np.uint16)
+    _load().oracle_signatures(_p(tok_bytes), _p(tok_off), ctypes.c_int32(V), _p(table),
+                              ctypes.c_int32(S), _p(sig))
+    return sig
+
+
+def build_classes(sig, tok_off) -> Tuple[np.ndarray, np.ndarray]:
+    """(class_of_token int32 [V], rep_of_class int32 [C]) by full-signature equality."""
+    sig = _c(sig, np.uint16)
+    tok_off = _c(tok_off, np.int64)
+    V, S = sig.shape
+    c = np.empty(V, dtype=np.int32)
+    r = np.empty(max(V, 1), dtype=np.int32)
+    C = _load().oracle_build_classes(_p(sig), _p(tok_off), ctypes.c_int32(V), ctypes.c_int32(S),
+                                     _p(c), _p(r))
+    return c, r[:C].copy()
+
+
+def expand_mask(cls_bits, class_of_token, C: int) -> np.ndarray:
+    """int32 [B, W(V)] token-level bit masks from int32 [B, W(C)] class-level ones."""
+    cls_bits = _c(cls_bits, np.int32)
+    c = _c(class_of_token, np.int32)
+    B = cls_bits.shape[0]
+    V = c.shape[0]
+    assert cls_bits.shape[1] == words_for(C)
+    out = np.empty((B, words_for(V)), dtype=np.int32)
+    _load().oracle_expand_mask(_p(cls_bits), ctypes.c_int32(B), ctypes.c_int32(C), _p(c),
+                               ctypes.c_int32(V), _p(out))
+    return out
+
+
+def apply_mask(logits, tok_bits, dtype: str, V: Optional[int] = None) -> np.ndarray:
+    """Returns a masked copy of `logits`.  dtype 'f32': float32 or uint32 array;
+    dtype 'bf16': uint16 bit patterns.  Rows may be wider than V (row stride)."""
+    tok_bits = _c(tok_bits, np.int32)
+    B = tok_bits.shape[0]
+    if dtype == "f32":
+        out = np.array(logits, copy=True, order="C")
+        assert out.dtype in (np.float32, np.uint32) and out.ndim == 2 and out.shape[0] == B
+        fn = _load().oracle_apply_mask_f32
+    elif dtype == "bf16":
+        out = np.array(logits, dtype=np.uint16, copy=True, order="C")
+        assert out.ndim == 2 and out.shape[0] == B
+        fn = _load().oracle_apply_mask_bf16
+    else:
+        raise ValueError(dtype)
+    stride = out.shape[1]
+    V = stride if V is None else V
+    assert tok_bits.shape[1] == words_for(V)
+    fn(_p(out), ctypes.c_int32(B), ctypes.c_int32(V), ctypes.c_int64(stride), _p(tok_bits))
+    return out
+
+
+def map_to_rep(tok, class_of_token, rep_of_class) -> np.ndarray:
+    tok = _c(tok, np.int32)
+    c = _c(class_of_token, np.int32)
+    r = _c(rep_of_class, np.int32)
+    out = np.empty(tok.shape[0], dtype=np.int32)
+    _load().oracle_map_to_rep(_p(tok), ctypes.c_int32(tok.shape[0]), _p(c),
+                              ctypes.c_int32(c.shape[0]), _p(r), ctypes.c_int32(r.shape[0]),
+                              _p(out))
+    return out
+
+
+def signature_hash(sig, seed: int) -> np.ndarray:
+    sig = _c(sig, np.uint16)
+    V, S = sig.shape
+    out = np.empty(V, dtype=np.uint64)
+    _load().oracle_hash(_p(sig), ctypes.c_int32(V), ctypes.c_int32(S), ctypes.c_uint64(seed),
+                        _p(out))
+    return out
+
+
+def splitmix64_stream(seed: int, n: int) -> np.ndarray:
+    state = ctypes.c_uint64(seed)
+    lib = _load()
+    return np.array([lib.oracle_splitmix64_next(ctypes.byref(state)) for _ in range(n)],
+                    dtype=np.uint64)

@@ -1,0 +1,221 @@
+/*
+ * CPU oracle for the CFGzip hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, obviously-correct C.  It shares no code with the HIP library and
+ * must never be called from the product path; only the tests, the smoke check
+ * and the benchmark's CPU-baseline leg use it.
+ *
+ * What each function follows in the paper ("Accelerating Constrained Decoding
+ * with Token Space Compression"):
+ *
+ *   oracle_signatures     Displacement of a token (Section 3.2.1, Algorithm 1)
+ *                         restricted to right-linear grammars, i.e. to a
+ *                         deterministic byte automaton: the PDA stack holds one
+ *                         symbol, the stack-adjacency relation (Appendix C) is
+ *                         empty, and the displacement of token t collapses to
+ *                         the map  q -> delta*(q, bytes(t)).  Written out as
+ *                         that walk, from every state.
+ *   oracle_build_classes  Section 3.1 "Pre-Computation": group tokens with equal
+ *                         signature; representative = byte-wise shortest member
+ *                         (tie: smallest token id); vectors c (token -> class)
+ *                         and r (class -> representative).  Class ids are issued
+ *                         in order of first appearance when scanning token ids
+ *                         upwards.  No hashing: full signatures are compared.
+ *   oracle_expand_mask    Section 3.1 "Inference" / Figure 1(b): token-level mask
+ *                         bit i = class-level mask bit c[i].
+ *   oracle_apply_mask_*   Section 2.2 logit masking: a disallowed token's logit
+ *                         becomes -infinity, an allowed one is left untouched
+ *                         (bit-for-bit).
+ *   oracle_map_to_rep     Section 3.1 "Inference" / Figure 1(a): sampled token
+ *                         t(i) -> r[c[i]].
+ *   oracle_hash           The library's signature hash (not in the paper; a
+ *                         device of this implementation) written from its
+ *                         formula:  H(t) = sum_q a_q * sig[t][q]  mod 2^64 with
+ *                         a_q = (q-th output of the SplitMix64 generator seeded
+ *                         with `seed`) | 1.
+ *
+ * Bit masks: int32 words, bit (i & 31) of word (i >> 5); 1 = allowed; rows are
+ * padded to whole words; pad bits are written as 0 and ignored on input.
+ */
+
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* sig[t][q] = state reached from q after reading every byte of token t. */
+void oracle_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                       const uint16_t *table /* [S][256] */, int32_t S,
+                       uint16_t *sig /* [V][S] */) {
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int32_t t = 0; t < V; ++t) {
+        for (int32_t q = 0; q < S; ++q) {
+            uint16_t s = (uint16_t)q;
+            for (int64_t p = tok_off[t]; p < tok_off[t + 1]; ++p)
+                s = table[(size_t)s * 256 + tok_bytes[p]];
+            sig[(size_t)t * S + q] = s;
+        }
+    }
+}
+
+/* ---- grouping -------------------------------------------------------- */
+
+static const uint16_t *g_sig;
+static int32_t g_S;
+
+static int cmp_by_signature_then_id(const void *pa, const void *pb) {
+    int32_t a = *(const int32_t *)pa, b = *(const int32_t *)pb;
+    const uint16_t *ra = g_sig + (size_t)a * g_S, *rb = g_sig + (size_t)b * g_S;
+    for (int32_t q = 0; q < g_S; ++q) {
+        if (ra[q] != rb[q]) return ra[q] < rb[q] ? -1 : 1;
+    }
+    return (a > b) - (a < b);
+}
+
+static int cmp_int32(const void *pa, const void *pb) {
+    int32_t a = *(const int32_t *)pa, b = *(const int32_t *)pb;
+    return (a > b) - (a < b);
+}
+
+/*
+ * Groups tokens by equal signature.  Returns the number of classes C, fills
+ * class_of_token[V] and the first C entries of rep_of_class.
+ * Not re-entrant (the comparator reads file-scope pointers).
+ */
+int32_t oracle_build_classes(const uint16_t *sig /* [V][S] */, const int64_t *tok_off,
+                             int32_t V, int32_t S,
+                             int32_t *class_of_token /* [V] */,
+                             int32_t *rep_of_class /* [V] capacity */) {
+    if (V <= 0) return 0;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)V);
+    int32_t *first = (int32_t *)malloc(sizeof(int32_t) * (size_t)V); /* smallest member of each group */
+    int32_t *group_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)V);
+    for (int32_t t = 0; t < V; ++t) order[t] = t;
+    g_sig = sig;
+    g_S = S;
+    qsort(order, (size_t)V, sizeof(int32_t), cmp_by_signature_then_id);
+
+    /* equal signatures are now adjacent, members of a group in ascending id */
+    int32_t G = 0;
+    for (int32_t i = 0; i < V; ++i) {
+        int same = i > 0 && memcmp(sig + (size_t)order[i] * S, sig + (size_t)order[i - 1] * S,
+                                   sizeof(uint16_t) * (size_t)S) == 0;
+        if (!same) first[G++] = order[i];
+        group_of[order[i]] = G - 1;
+    }
+    /* class id = rank of the group's smallest member among all groups' smallest members */
+    int32_t *sorted_first = (int32_t *)malloc(sizeof(int32_t) * (size_t)G);
+    memcpy(sorted_first, first, sizeof(int32_t) * (size_t)G);
+    qsort(sorted_first, (size_t)G, sizeof(int32_t), cmp_int32);
+    int32_t *id_of_group = (int32_t *)malloc(sizeof(int32_t) * (size_t)G);
+    for (int32_t k = 0; k < G; ++k) class_of_token[sorted_first[k]] = k; /* temp: on the first members */
+    for (int32_t g = 0; g < G; ++g) id_of_group[g] = class_of_token[first[g]];
+    for (int32_t t = 0; t < V; ++t) class_of_token[t] = id_of_group[group_of[t]];
+
+    /* representative: shortest member, ties to the smallest token id */
+    for (int32_t k = 0; k < G; ++k) rep_of_class[k] = -1;
+    for (int32_t t = 0; t < V; ++t) {
+        int32_t k = class_of_token[t];
+        int32_t r = rep_of_class[k];
+        if (r < 0) {
+            rep_of_class[k] = t;
+        } else {
+            int64_t lt = tok_off[t + 1] - tok_off[t], lr = tok_off[r + 1] - tok_off[r];
+            if (lt < lr) rep_of_class[k] = t; /* t > r always, so ties keep r */
+        }
+    }
+    free(order);
+    free(first);
+    free(group_of);
+    free(sorted_first);
+    free(id_of_group);
+    return G;
+}
+
+/* ---- decode-step path ------------------------------------------------ */
+
+static int get_bit(const int32_t *row, int64_t i) {
+    return (int)(((uint32_t)row[i >> 5] >> (i & 31)) & 1u);
+}
+
+void oracle_expand_mask(const int32_t *cls_bits /* [B][W(C)] */, int32_t B, int32_t C,
+                        const int32_t *class_of_token /* [V] */, int32_t V,
+                        int32_t *tok_bits /* [B][W(V)] */) {
+    int64_t Wc = ((int64_t)C + 31) / 32, Wv = ((int64_t)V + 31) / 32;
+#pragma omp parallel for schedule(static)
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t *in = cls_bits + b * Wc;
+        int32_t *out = tok_bits + b * Wv;
+        for (int64_t w = 0; w < Wv; ++w) out[w] = 0;
+        for (int32_t i = 0; i < V; ++i) {
+            if (get_bit(in, class_of_token[i]))
+                out[i >> 5] = (int32_t)((uint32_t)out[i >> 5] | (1u << (i & 31)));
+        }
+    }
+}
+
+/* logits as raw 32-bit patterns (fp32); -inf = 0xFF800000 */
+void oracle_apply_mask_f32(uint32_t *logits /* [B][row_stride] */, int32_t B, int32_t V,
+                           int64_t row_stride, const int32_t *tok_bits /* [B][W(V)] */) {
+    int64_t Wv = ((int64_t)V + 31) / 32;
+#pragma omp parallel for schedule(static)
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t i = 0; i < V; ++i)
+            if (!get_bit(tok_bits + b * Wv, i)) logits[b * row_stride + i] = 0xFF800000u;
+}
+
+/* logits as raw 16-bit patterns (bf16); -inf = 0xFF80 */
+void oracle_apply_mask_bf16(uint16_t *logits, int32_t B, int32_t V, int64_t row_stride,
+                            const int32_t *tok_bits) {
+    int64_t Wv = ((int64_t)V + 31) / 32;
+#pragma omp parallel for schedule(static)
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t i = 0; i < V; ++i)
+            if (!get_bit(tok_bits + b * Wv, i)) logits[b * row_stride + i] = 0xFF80u;
+}
+
+/* out[b] = r[c[tok[b]]]; a token id outside [0, V) maps to -1 */
+void oracle_map_to_rep(const int32_t *tok, int32_t B, const int32_t *class_of_token, int32_t V,
+                       const int32_t *rep_of_class, int32_t C, int32_t *out) {
+    (void)C;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t t = tok[b];
+        out[b] = (t < 0 || t >= V) ? -1 : rep_of_class[class_of_token[t]];
+    }
+}
+
+/* ---- the library's signature hash, from its formula ------------------- */
+
+/* SplitMix64 (Steele, Lea, Flood 2014; Vigna's public-domain formulation):
+ * state += 0x9E3779B97F4A7C15; z = state; z = (z ^ z>>30) * 0xBF58476D1CE4E5B9;
+ * z = (z ^ z>>27) * 0x94D049BB133111EB; output z ^ z>>31. */
+uint64_t oracle_splitmix64_next(uint64_t *state) {
+    uint64_t z = (*state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+void oracle_hash(const uint16_t *sig /* [V][S] */, int32_t V, int32_t S, uint64_t seed,
+                 uint64_t *hash_out /* [V] */) {
+    uint64_t *a = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)S);
+    uint64_t state = seed;
+    for (int32_t q = 0; q < S; ++q) a[q] = oracle_splitmix64_next(&state) | 1ull;
+    for (int32_t t = 0; t < V; ++t) {
+        uint64_t h = 0;
+        for (int32_t q = 0; q < S; ++q) h += a[q] * (uint64_t)sig[(size_t)t * S + q];
+        hash_out[t] = h;
+    }
+    free(a);
+}
