@@ -1,0 +1,182 @@
+/*
+ * cfgzip.h - C ABI of the MI355X (gfx950) CFGzip hot-path library.
+ *
+ * CFGzip ("Accelerating Constrained Decoding with Token Space Compression")
+ * collapses a tokenizer vocabulary T into equivalence classes E of tokens that a
+ * grammar engine cannot tell apart, so that the engine works on |E| << |T|
+ * representatives.  This library holds the data-parallel part:
+ *
+ *   offline   per-token signatures, grouping into classes, representatives
+ *             (paper Section 3.1 "Pre-Computation", Section 3.2 for what a
+ *             signature is);
+ *   per step  class-level mask -> token-level mask, -inf masking of logits,
+ *             sampled token -> class representative
+ *             (paper Section 3.1 "Inference", Figure 1; Section 2.2 for what a
+ *             mask means).
+ *
+ * Signature.  The paper's relation is equality of displacement sets over the
+ * one-state pushdown automaton of a grammar in Greibach normal form (Section
+ * 3.2.1, Algorithm 1).  This library covers grammars given as a deterministic
+ * byte automaton (a right-linear grammar): the stack then holds one symbol, no
+ * stack backtrack can follow the first one, and the displacement of token t is
+ * the map  q -> delta*(q, bytes(t))  over all automaton states q.  That vector
+ * is the signature: sig[t][q], S entries of uint16.
+ *
+ * Conventions for every call
+ *   - Every pointer is a DEVICE pointer owned by the caller unless the comment
+ *     says "host".  The library allocates nothing, frees nothing and keeps no
+ *     pointer after a call returns.  Scratch memory comes in as `ws`, sized by
+ *     the matching *_workspace_bytes query (a host-only computation).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
+ *     is enqueued on it; calls do not synchronise, except cfgzip_build_classes
+ *     (it must hand the class count back to the host).
+ *   - Return value: CFGZIP_OK, or a negative CFGZIP_E* code.  On
+ *     CFGZIP_E_INVALID nothing was enqueued.  On CFGZIP_E_HIP the failing HIP
+ *     status is kept per host thread and read with cfgzip_last_hip_error().
+ *   - Ids (token ids, class ids) are int32.  Bit masks are int32 words: bit
+ *     (i & 31) of word (i >> 5) belongs to item i; 1 = allowed.  A mask row over
+ *     n items has W(n) = ceil(n / 32) words; pad bits are written as 0 and
+ *     ignored when read.
+ *   - Values the host cannot check without reading device memory (table entries
+ *     < S, class ids < C, sampled ids < V) are the caller's responsibility where
+ *     a comment says so; cfgzip_map_to_rep range-checks on the device.
+ */
+#ifndef CFGZIP_H
+#define CFGZIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CFGZIP_OK 0
+#define CFGZIP_E_INVALID (-1)   /* null pointer, non-positive size, S > 65536, bad enum, misaligned pointer */
+#define CFGZIP_E_WORKSPACE (-2) /* ws == NULL or ws_bytes smaller than the query says */
+#define CFGZIP_E_HIP (-3)       /* a HIP call failed; see cfgzip_last_hip_error() */
+#define CFGZIP_E_COLLISION (-4) /* hash collisions could not be resolved within the round limit */
+
+#define CFGZIP_DTYPE_F32 0
+#define CFGZIP_DTYPE_BF16 1
+
+#define CFGZIP_BITS_TOKEN 0 /* `bits` is a token-level mask  [B][W(V)] */
+#define CFGZIP_BITS_CLASS 1 /* `bits` is a class-level mask  [B][W(C)], gathered through class_of_token */
+
+/* hipError_t (as int) of the last failing HIP call made by this host thread; 0 if none. */
+int cfgzip_last_hip_error(void);
+
+/* Library version: major * 100 + minor. */
+int cfgzip_version(void);
+
+/*
+ * Signatures of all tokens (paper Section 3.2.1 / Algorithm 1, regular case):
+ *     sig[t][q] = state reached from q after reading bytes(t),  0 <= t < V, 0 <= q < S,
+ * and/or their 64-bit hash
+ *     hash[t] = sum_{q<S} a_q * sig[t][q]  (mod 2^64),
+ *     a_q = (q-th output of SplitMix64 seeded with hash_seed) | 1.
+ * The sum is order-free, so the hash does not depend on how states are split
+ * over lanes, waves or kernels.  The hash is a device of this library (the
+ * paper never hashes); class ids never depend on it.
+ *
+ *   tok_bytes  uint8 [tok_off[V]]   concatenated token bytes
+ *   tok_off    int64 [V + 1]        CSR offsets, tok_off[0] = 0, non-decreasing; an empty
+ *                                   token (equal offsets) has the identity signature
+ *   table      uint16 [S][256]      table[q][b] = next state; every entry must be < S
+ *                                   (caller's responsibility)
+ *   S          1 .. 65536
+ *   sig_out    uint16 [V][S] or NULL (NULL: signatures are hashed on the fly, never stored)
+ *   hash_out   uint64 [V]   or NULL (at least one of sig_out / hash_out must be given)
+ *   ws         cfgzip_signatures_workspace_bytes(V, S) bytes, 256-byte aligned
+ */
+size_t cfgzip_signatures_workspace_bytes(int32_t V, int32_t S);
+int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                      const uint16_t *table, int32_t S,
+                      uint16_t *sig_out, uint64_t *hash_out, uint64_t hash_seed,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Equivalence classes, class ids and representatives (paper Section 3.1
+ * "Pre-Computation"): tokens with equal signature form a class; the vector c
+ * maps token id -> class id, the vector r maps class id -> representative, the
+ * byte-wise shortest member (ties: smallest token id).  Class ids are issued in
+ * order of each class's smallest token id, so c[0] = 0.
+ *
+ * Method: radix sort of (hash, token id), equal-hash segments, then every
+ * member's full signature is compared with its segment head; members that differ
+ * (a hash collision) are split off in further rounds, so the result is exact for
+ * any `hash` that is a function of the signature (equal signatures must carry
+ * equal hashes).  With sig == NULL signatures are recomputed from the automaton
+ * for the comparison instead of being read.
+ *
+ *   tok_bytes, tok_off, V, table, S   as for cfgzip_signatures
+ *   sig        uint16 [V][S] from cfgzip_signatures, or NULL
+ *   hash       uint64 [V]    from cfgzip_signatures (or any function of the signature)
+ *   class_of_token   out, int32 [V]
+ *   rep_of_class     out, int32 [V] capacity; the first C entries are written
+ *   num_classes_dev  out, int32 [1] device, or NULL
+ *   num_classes_host out, int32 [1] HOST, or NULL
+ *   collisions_host  out, int32 [1] HOST, or NULL: number of tokens whose signature
+ *                    differed from their equal-hash segment head
+ *   ws         cfgzip_build_classes_workspace_bytes(V, S) bytes, 256-byte aligned
+ * Synchronises `stream` before returning.
+ */
+size_t cfgzip_build_classes_workspace_bytes(int32_t V, int32_t S);
+int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                         const uint16_t *table, int32_t S,
+                         const uint16_t *sig, const uint64_t *hash,
+                         int32_t *class_of_token, int32_t *rep_of_class,
+                         int32_t *num_classes_dev, int32_t *num_classes_host,
+                         int32_t *collisions_host,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Class-level mask -> token-level mask (paper Section 3.1 "Inference",
+ * Figure 1(b)):  tok_bits[b] bit i = cls_bits[b] bit class_of_token[i].
+ *
+ *   cls_bits        int32 [B][W(C)]
+ *   class_of_token  int32 [V], every entry in [0, C) (caller's responsibility)
+ *   tok_bits        out, int32 [B][W(V)], pad bits 0
+ */
+int cfgzip_expand_mask(const int32_t *cls_bits, int32_t B, int32_t C,
+                       const int32_t *class_of_token, int32_t V,
+                       int32_t *tok_bits, void *stream);
+
+/*
+ * Logit masking in place (paper Section 2.2: a disallowed token's logit is set
+ * to -infinity; Section 3.1 "Inference": z_i <- z_i * m_{c_i} read as a select,
+ * since a product with -inf would give +inf or NaN on log-probabilities):
+ *     logits[b][i] unchanged, bit for bit, if token i is allowed in row b,
+ *     else the dtype's -inf pattern (fp32 0xFF800000, bf16 0xFF80).
+ *
+ *   logits      [B] rows of V elements, consecutive rows row_stride ELEMENTS apart
+ *               (row_stride >= V); element size 4 (F32) or 2 (BF16) bytes; the base
+ *               pointer must be aligned to the element size
+ *   bits_kind   CFGZIP_BITS_TOKEN: bits = int32 [B][W(V)] token-level mask;
+ *               CFGZIP_BITS_CLASS: bits = int32 [B][W(C)] class-level mask, gathered through
+ *               class_of_token (expand and apply fused; no token mask round trip)
+ *   class_of_token, C   used for CFGZIP_BITS_CLASS only (else NULL / 0)
+ *   tok_bits_out        CFGZIP_BITS_CLASS only: NULL, or int32 [B][W(V)] that also receives
+ *                       the token-level mask
+ */
+int cfgzip_apply_mask(void *logits, int32_t dtype, int32_t B, int32_t V, int64_t row_stride,
+                      const int32_t *bits, int32_t bits_kind,
+                      const int32_t *class_of_token, int32_t C,
+                      int32_t *tok_bits_out, void *stream);
+
+/*
+ * Sampled token -> class representative (paper Section 3.1 "Inference",
+ * Figure 1(a)):  out[b] = rep_of_class[class_of_token[tok[b]]].
+ * A token id outside [0, V), or a class id outside [0, C), yields -1.
+ *
+ *   tok  int32 [B];  out  int32 [B]
+ */
+int cfgzip_map_to_rep(const int32_t *tok, int32_t B,
+                      const int32_t *class_of_token, int32_t V,
+                      const int32_t *rep_of_class, int32_t C,
+                      int32_t *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CFGZIP_H */

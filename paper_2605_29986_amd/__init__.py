@@ -1,0 +1,22 @@
+"""MI355X-native hot path of CFGzip (token-vocabulary compression for
+grammar-constrained decoding): a C-ABI HIP library, ``lib/libcfgzip.so``, and a
+thin ctypes binding with the same entry-point names.
+
+The binding only marshals arguments (device pointers of torch tensors, sizes,
+the current HIP stream); every step of the path runs in the library's kernels.
+There is no CPU fallback: calling anything without the built library raises.
+"""
+
+from .binding import (  # noqa: F401
+    CfgzipError,
+    DEFAULT_HASH_SEED,
+    cfgzip_apply_mask,
+    cfgzip_build_classes,
+    cfgzip_expand_mask,
+    cfgzip_map_to_rep,
+    cfgzip_signatures,
+    cfgzip_version,
+    library_path,
+    load_library,
+    words_for,
+)

@@ -1,0 +1,242 @@
+"""ctypes binding of libcfgzip.so.  Argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors; they supply device memory and the HIP
+stream.  Function names and argument order follow ``include/cfgzip.h``.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "lib", "libcfgzip.so")
+_lib: Optional[ctypes.CDLL] = None
+
+DEFAULT_HASH_SEED = 0x5EED_CF62_1234_ABCD
+
+CFGZIP_DTYPE_F32 = 0
+CFGZIP_DTYPE_BF16 = 1
+CFGZIP_BITS_TOKEN = 0
+CFGZIP_BITS_CLASS = 1
+
+_ERRORS = {
+    -1: "CFGZIP_E_INVALID (bad argument)",
+    -2: "CFGZIP_E_WORKSPACE (workspace missing, misaligned or too small)",
+    -3: "CFGZIP_E_HIP (a HIP call failed)",
+    -4: "CFGZIP_E_COLLISION (hash collisions not resolved)",
+}
+
+
+class CfgzipError(RuntimeError):
+    def __init__(self, fn: str, code: int, hip_error: int = 0):
+        self.code = code
+        self.hip_error = hip_error
+        extra = f", hipError_t={hip_error}" if code == -3 else ""
+        super().__init__(f"{fn} failed: {_ERRORS.get(code, code)}{extra}")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the built HIP library; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2605_29986_amd.build` "
+            "(hipcc, gfx950). The CFGzip path has no CPU fallback.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, u64, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64,
+                             ctypes.c_size_t)
+    lib.cfgzip_version.restype = ctypes.c_int
+    lib.cfgzip_last_hip_error.restype = ctypes.c_int
+    lib.cfgzip_signatures_workspace_bytes.restype = sz
+    lib.cfgzip_signatures_workspace_bytes.argtypes = [i32, i32]
+    lib.cfgzip_signatures.restype = ctypes.c_int
+    lib.cfgzip_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp, sz, vp]
+    lib.cfgzip_build_classes_workspace_bytes.restype = sz
+    lib.cfgzip_build_classes_workspace_bytes.argtypes = [i32, i32]
+    lib.cfgzip_build_classes.restype = ctypes.c_int
+    lib.cfgzip_build_classes.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cfgzip_expand_mask.restype = ctypes.c_int
+    lib.cfgzip_expand_mask.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+    lib.cfgzip_apply_mask.restype = ctypes.c_int
+    lib.cfgzip_apply_mask.argtypes = [vp, i32, i32, i32, i64, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_map_to_rep.restype = ctypes.c_int
+    lib.cfgzip_map_to_rep.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
+    _lib = lib
+    return lib
+
+
+def cfgzip_version() -> int:
+    return int(load_library().cfgzip_version())
+
+
+def words_for(n: int) -> int:
+    return (int(n) + 31) // 32
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != 0:
+        raise CfgzipError(fn, rc, int(load_library().cfgzip_last_hip_error()))
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a tensor in GPU memory")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def cfgzip_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: torch.Tensor, *,
+                      want_sig: bool = True, want_hash: bool = True,
+                      hash_seed: int = DEFAULT_HASH_SEED, sig_out: Optional[torch.Tensor] = None,
+                      hash_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      stream=None) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """sig[t][q] = state reached from q on bytes(t) (uint16 [V, S]) and/or its 64-bit hash
+    (int64 tensor holding the uint64 bit patterns, [V])."""
+    lib = load_library()
+    V = tok_off.numel() - 1
+    S = table.shape[0]
+    dev = tok_off.device
+    if want_sig and sig_out is None:
+        sig_out = torch.empty((V, S), dtype=torch.uint16, device=dev)
+    if want_hash and hash_out is None:
+        hash_out = torch.empty((V,), dtype=torch.int64, device=dev)
+    need = lib.cfgzip_signatures_workspace_bytes(V, S)
+    if workspace is None:
+        workspace = _workspace(need, dev)
+    rc = lib.cfgzip_signatures(
+        _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
+        _dev(tok_off, torch.int64, "tok_off"), V,
+        _dev(table, torch.uint16, "table"), S,
+        _dev(sig_out, torch.uint16, "sig_out") if sig_out is not None else None,
+        _dev(hash_out, torch.int64, "hash_out") if hash_out is not None else None,
+        ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF),
+        workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _check("cfgzip_signatures", rc)
+    return sig_out, hash_out
+
+
+def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: torch.Tensor,
+                         sig: Optional[torch.Tensor], hash: torch.Tensor, *,
+                         class_of_token: Optional[torch.Tensor] = None,
+                         rep_of_class: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None):
+    """Returns (class_of_token int32 [V], rep_of_class int32 [C] (a view of the first C
+    entries), C, collisions)."""
+    lib = load_library()
+    V = tok_off.numel() - 1
+    S = table.shape[0]
+    dev = tok_off.device
+    if class_of_token is None:
+        class_of_token = torch.empty((V,), dtype=torch.int32, device=dev)
+    if rep_of_class is None:
+        rep_of_class = torch.empty((V,), dtype=torch.int32, device=dev)
+    need = lib.cfgzip_build_classes_workspace_bytes(V, S)
+    if workspace is None:
+        workspace = _workspace(need, dev)
+    c_host = ctypes.c_int32(0)
+    coll_host = ctypes.c_int32(0)
+    rc = lib.cfgzip_build_classes(
+        _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
+        _dev(tok_off, torch.int64, "tok_off"), V,
+        _dev(table, torch.uint16, "table"), S,
+        _dev(sig, torch.uint16, "sig") if sig is not None else None,
+        _dev(hash, torch.int64, "hash"),
+        _dev(class_of_token, torch.int32, "class_of_token"),
+        _dev(rep_of_class, torch.int32, "rep_of_class"),
+        None, ctypes.addressof(c_host), ctypes.addressof(coll_host),
+        workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _check("cfgzip_build_classes", rc)
+    C = int(c_host.value)
+    return class_of_token, rep_of_class[:C], C, int(coll_host.value)
+
+
+def cfgzip_expand_mask(cls_bits: torch.Tensor, C: int, class_of_token: torch.Tensor, *,
+                       tok_bits: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """tok_bits[b] bit i = cls_bits[b] bit class_of_token[i]; int32 [B, W(V)]."""
+    lib = load_library()
+    B = cls_bits.shape[0]
+    V = class_of_token.numel()
+    if cls_bits.shape[1] != words_for(C):
+        raise ValueError("cls_bits must be [B, ceil(C/32)]")
+    if tok_bits is None:
+        tok_bits = torch.empty((B, words_for(V)), dtype=torch.int32, device=cls_bits.device)
+    rc = lib.cfgzip_expand_mask(_dev(cls_bits, torch.int32, "cls_bits"), B, int(C),
+                                _dev(class_of_token, torch.int32, "class_of_token"), V,
+                                _dev(tok_bits, torch.int32, "tok_bits"), _stream(stream))
+    _check("cfgzip_expand_mask", rc)
+    return tok_bits
+
+
+def cfgzip_apply_mask(logits: torch.Tensor, bits: torch.Tensor, *, V: Optional[int] = None,
+                      class_of_token: Optional[torch.Tensor] = None, C: int = 0,
+                      tok_bits_out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Masks `logits` ([B, row_stride >= V], float32 or bfloat16) in place.  With
+    `class_of_token` given, `bits` is a class-level mask [B, W(C)] gathered through it
+    (fused expand + apply, optionally also writing the token-level mask); otherwise
+    `bits` is a token-level mask [B, W(V)]."""
+    lib = load_library()
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [B, V] with unit column stride")
+    B = logits.shape[0]
+    V = logits.shape[1] if V is None else int(V)
+    if logits.dtype == torch.float32:
+        dt = CFGZIP_DTYPE_F32
+    elif logits.dtype == torch.bfloat16:
+        dt = CFGZIP_DTYPE_BF16
+    else:
+        raise TypeError("logits must be float32 or bfloat16")
+    if not logits.is_cuda:
+        raise TypeError("logits must be a tensor in GPU memory")
+    kind = CFGZIP_BITS_CLASS if class_of_token is not None else CFGZIP_BITS_TOKEN
+    want_words = words_for(C) if kind == CFGZIP_BITS_CLASS else words_for(V)
+    if bits.shape[0] != B or bits.shape[1] != want_words:
+        raise ValueError("bits has the wrong shape for this mask kind")
+    rc = lib.cfgzip_apply_mask(
+        logits.data_ptr(), dt, B, V, int(logits.stride(0)),
+        _dev(bits, torch.int32, "bits"), kind,
+        _dev(class_of_token, torch.int32, "class_of_token") if class_of_token is not None else None,
+        int(C),
+        _dev(tok_bits_out, torch.int32, "tok_bits_out") if tok_bits_out is not None else None,
+        _stream(stream))
+    _check("cfgzip_apply_mask", rc)
+    return logits
+
+
+def cfgzip_map_to_rep(tok: torch.Tensor, class_of_token: torch.Tensor, rep_of_class: torch.Tensor,
+                      *, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """out[b] = rep_of_class[class_of_token[tok[b]]] (-1 for an id out of range)."""
+    lib = load_library()
+    B = tok.numel()
+    if out is None:
+        out = torch.empty((B,), dtype=torch.int32, device=tok.device)
+    rc = lib.cfgzip_map_to_rep(_dev(tok, torch.int32, "tok"), B,
+                               _dev(class_of_token, torch.int32, "class_of_token"),
+                               class_of_token.numel(),
+                               _dev(rep_of_class, torch.int32, "rep_of_class"),
+                               rep_of_class.numel(), _dev(out, torch.int32, "out"), _stream(stream))
+    _check("cfgzip_map_to_rep", rc)
+    return out

@@ -1,0 +1,189 @@
+"""GPU parity, offline path: cfgzip_signatures and cfgzip_build_classes against
+the CPU oracle, bit for bit, on the four class-build configurations and on edge
+cases (tiny and odd state counts, empty / long / duplicate tokens, forced hash
+collisions, hash seeds)."""
+
+import numpy as np
+import pytest
+
+import oracle
+import synthetic_inputs as si
+from synthetic_inputs.vocab import vocab_from_tokens
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_29986_amd as p
+    p.load_library()
+    return p
+
+
+def _random_vocab(rng, V, max_len, n_bytes=256, empties=True):
+    toks = []
+    for _ in range(V):
+        k = int(rng.integers(0 if empties else 1, max_len + 1))
+        toks.append(rng.integers(0, n_bytes, size=k, dtype=np.uint8).tobytes())
+    return vocab_from_tokens(toks)
+
+
+def _check_signatures(lib, vocab, table, seed=None):
+    from gpu_util import vocab_dev, hash_np
+    seed = lib.DEFAULT_HASH_SEED if seed is None else seed
+    tb, to, tt = vocab_dev(vocab, table)
+    want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+    want_hash = oracle.signature_hash(want_sig, seed)
+    sig, h = lib.cfgzip_signatures(tb, to, tt, hash_seed=seed)
+    torch.cuda.synchronize()
+    assert (sig.cpu().numpy() == want_sig).all(), "signatures"
+    assert (hash_np(h) == want_hash).all(), "hash (with signatures stored)"
+    _, h2 = lib.cfgzip_signatures(tb, to, tt, want_sig=False, hash_seed=seed)
+    assert (hash_np(h2) == want_hash).all(), "hash (on the fly)"
+    sig3, _ = lib.cfgzip_signatures(tb, to, tt, want_hash=False, hash_seed=seed)
+    assert (sig3.cpu().numpy() == want_sig).all(), "signatures (no hash)"
+    return want_sig, sig, h
+
+
+def _check_build(lib, vocab, table, stored=True, hash_override=None):
+    from gpu_util import vocab_dev, dev
+    tb, to, tt = vocab_dev(vocab, table)
+    want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+    want_c, want_r = oracle.build_classes(want_sig, vocab.tok_off)
+    sig, h = lib.cfgzip_signatures(tb, to, tt, want_sig=stored)
+    if hash_override is not None:
+        h = hash_override(h)
+    c, r, C, coll = lib.cfgzip_build_classes(tb, to, tt, sig if stored else None, h)
+    assert C == len(want_r), (C, len(want_r))
+    assert (c.cpu().numpy() == want_c).all(), "class_of_token"
+    assert (r.cpu().numpy() == want_r).all(), "rep_of_class"
+    return C, coll
+
+
+@pytest.mark.parametrize("S", [1, 2, 3, 24, 33, 63, 64, 65, 100, 128, 129, 200, 256, 257, 288, 289,
+                               300, 513, 1000])
+def test_signatures_state_counts(lib, S):
+    print(f"case S={S}", flush=True)
+    rng = np.random.default_rng(S)
+    table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+    vocab = _random_vocab(rng, 257, 9)
+    _check_signatures(lib, vocab, table)
+
+
+def test_signatures_long_and_empty_tokens(lib):
+    rng = np.random.default_rng(0)
+    for S in (24, 256, 700):
+        print(f"case long tokens S={S}", flush=True)
+        table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+        toks = [b"", b"a", rng.integers(0, 256, size=64, dtype=np.uint8).tobytes(),
+                rng.integers(0, 256, size=65, dtype=np.uint8).tobytes(), b"",
+                rng.integers(0, 256, size=200, dtype=np.uint8).tobytes(),
+                rng.integers(0, 256, size=129, dtype=np.uint8).tobytes(), b"zz", b""]
+        _check_signatures(lib, vocab_from_tokens(toks), table)
+
+
+def test_signatures_all_tokens_empty(lib):
+    table = np.random.default_rng(1).integers(0, 70, size=(70, 256)).astype(np.uint16)
+    _check_signatures(lib, vocab_from_tokens([b"", b"", b""]), table)
+
+
+def test_signatures_hash_seeds(lib, cfg1):
+    for seed in (0, 1, 0xFFFFFFFFFFFFFFFF, 1234567):
+        _check_signatures(lib, cfg1["vocab"], cfg1["table"], seed=seed)
+
+
+def test_config1_build(lib, cfg1):
+    _check_signatures(lib, cfg1["vocab"], cfg1["table"])
+    C, coll = _check_build(lib, cfg1["vocab"], cfg1["table"])
+    assert coll == 0
+    _check_build(lib, cfg1["vocab"], cfg1["table"], stored=False)
+
+
+def test_config2_build(lib):
+    cfg = si.make_config(2)
+    _check_signatures(lib, cfg["vocab"], cfg["table"])
+    C, coll = _check_build(lib, cfg["vocab"], cfg["table"])
+    print("config 2: C =", C, "V/C =", cfg["vocab"].V / C, flush=True)
+    assert coll == 0
+    _check_build(lib, cfg["vocab"], cfg["table"], stored=False)
+
+
+def test_config3_build(lib):
+    cfg = si.make_config(3)
+    _check_signatures(lib, cfg["vocab"], cfg["table"])
+    C, coll = _check_build(lib, cfg["vocab"], cfg["table"])
+    print("config 3: C =", C, "V/C =", cfg["vocab"].V / C, flush=True)
+    assert coll == 0
+
+
+def test_config4_build_hash_on_the_fly(lib):
+    """Signatures are never stored: hashed on the fly, verified by re-walking."""
+    from gpu_util import vocab_dev, hash_np
+    cfg = si.make_config(4)
+    vocab, table = cfg["vocab"], cfg["table"]
+    tb, to, tt = vocab_dev(vocab, table)
+    want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+    want_c, want_r = oracle.build_classes(want_sig, vocab.tok_off)
+    _, h = lib.cfgzip_signatures(tb, to, tt, want_sig=False)
+    assert (hash_np(h) == oracle.signature_hash(want_sig, lib.DEFAULT_HASH_SEED)).all()
+    c, r, C, coll = lib.cfgzip_build_classes(tb, to, tt, None, h)
+    print("config 4: C =", C, "V/C =", vocab.V / C, "collisions =", coll, flush=True)
+    assert C == len(want_r) and coll == 0
+    assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+
+
+@pytest.mark.parametrize("stored", [True, False])
+@pytest.mark.parametrize("bits", [0, 3, 8])
+def test_forced_hash_collisions(lib, cfg2_small, stored, bits):
+    """A hash cut down to a few bits (still a function of the signature) forces
+    thousands of collisions; classes and representatives must not change."""
+    print(f"case stored={stored} bits={bits}", flush=True)
+    mask = (1 << bits) - 1
+    C, coll = _check_build(lib, cfg2_small["vocab"], cfg2_small["table"], stored=stored,
+                           hash_override=lambda h: h & mask)
+    assert coll > 0
+
+
+def test_classes_do_not_depend_on_hash_seed(lib, cfg1):
+    from gpu_util import vocab_dev
+    tb, to, tt = vocab_dev(cfg1["vocab"], cfg1["table"])
+    outs = []
+    for seed in (1, 2, 3):
+        sig, h = lib.cfgzip_signatures(tb, to, tt, hash_seed=seed)
+        c, r, C, _ = lib.cfgzip_build_classes(tb, to, tt, sig, h)
+        outs.append((c.cpu().numpy().copy(), r.cpu().numpy().copy(), C))
+    for o in outs[1:]:
+        assert o[2] == outs[0][2] and (o[0] == outs[0][0]).all() and (o[1] == outs[0][1]).all()
+
+
+def test_build_edge_vocabularies(lib, cfg1):
+    table = cfg1["table"]
+    for toks in ([b"a"], [b"", b""], [b"ab", b"", b"ab", b"{", b"", b"ab"],
+                 [bytes([97 + (i % 3)]) * (1 + i % 5) for i in range(2049)]):
+        print("case vocabulary of", len(toks), flush=True)
+        _check_build(lib, vocab_from_tokens(toks), table)
+        _check_build(lib, vocab_from_tokens(toks), table, stored=False)
+
+
+def test_build_random_automaton_every_token_its_own_class(lib):
+    rng = np.random.default_rng(5)
+    S = 300
+    table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+    vocab = _random_vocab(rng, 5000, 6, empties=False)
+    _check_build(lib, vocab, table)
+    _check_build(lib, vocab, table, stored=False)
+
+
+def test_workspace_and_argument_errors(lib):
+    raw = lib.load_library()
+    assert raw.cfgzip_signatures_workspace_bytes(100, 0) == 0
+    assert raw.cfgzip_signatures_workspace_bytes(100, 65537) == 0
+    t = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    # no output requested
+    assert raw.cfgzip_signatures(t.data_ptr(), t.data_ptr(), 4, t.data_ptr(), 2, None, None, 0,
+                                 t.data_ptr(), 1024, None) == -1
+    # workspace too small
+    assert raw.cfgzip_signatures(t.data_ptr(), t.data_ptr(), 4, t.data_ptr(), 2, t.data_ptr(), None,
+                                 0, t.data_ptr(), 16, None) == -2
