@@ -393,20 +393,40 @@ __global__ void mark_heads_kernel(int n, const int32_t *__restrict__ head_pos,
     if (i < n && head_pos[i] == i) is_head_token[vals[i]] = 1;
 }
 
-__global__ void assign_classes_kernel(int n, const int32_t *__restrict__ head_pos,
-                                      const int32_t *__restrict__ vals,
-                                      const int32_t *__restrict__ id_of_head_token,
-                                      const int64_t *__restrict__ tok_off, int32_t *class_of_token,
-                                      uint64_t *rep_key) {
+// Sorted neighbours mostly share a class, so a wave first reduces (length, id) over its lanes
+// of equal class and issues one atomic per distinct class instead of one per token.
+__global__ __launch_bounds__(kThreads) void assign_classes_kernel(
+    int n, const int32_t *__restrict__ head_pos, const int32_t *__restrict__ vals,
+    const int32_t *__restrict__ id_of_head_token, const int64_t *__restrict__ tok_off,
+    int32_t *class_of_token, uint64_t *rep_key) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int32_t tok = vals[i];
-    const int32_t k = id_of_head_token[vals[head_pos[i]]];
-    class_of_token[tok] = k;
-    int64_t len = tok_off[tok + 1] - tok_off[tok];
-    if (len > 0x7FFFFFFF) len = 0x7FFFFFFF;
-    const uint64_t packed = ((uint64_t)len << 32) | (uint32_t)tok;
-    atomicMin(reinterpret_cast<unsigned long long *>(rep_key + k), (unsigned long long)packed);
+    const bool valid = i < n;
+    int32_t k = -1;
+    uint64_t packed = ~0ull;
+    if (valid) {
+        const int32_t tok = vals[i];
+        k = id_of_head_token[vals[head_pos[i]]];
+        class_of_token[tok] = k;
+        int64_t len = tok_off[tok + 1] - tok_off[tok];
+        if (len > 0x7FFFFFFF) len = 0x7FFFFFFF;
+        packed = ((uint64_t)len << 32) | (uint32_t)tok;
+    }
+    uint64_t todo = __ballot(valid);
+    const int lane = threadIdx.x & 63;
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const int32_t k0 = __shfl(k, leader, 64);
+        const bool mine = valid && k == k0;
+        uint64_t m = mine ? packed : ~0ull;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint64_t o = __shfl_xor(m, off, 64);
+            m = o < m ? o : m;
+        }
+        if (lane == leader)
+            atomicMin(reinterpret_cast<unsigned long long *>(rep_key + k0), (unsigned long long)m);
+        todo &= ~__ballot(mine);
+    }
 }
 
 __global__ void write_reps_kernel(int n, const uint64_t *__restrict__ rep_key, const Counters *ctr,
