@@ -21,10 +21,6 @@
 
 namespace cfgzip {
 
-int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, void *ws,
-                   const uint16_t **Tt_out, const uint64_t **mult_out, hipStream_t stream);
-size_t sig_workspace_bytes(int32_t S);
-
 namespace {
 
 constexpr int kThreads = 256;
@@ -312,43 +308,82 @@ __global__ __launch_bounds__(kThreads) void verify_stored_kernel(
     }
 }
 
-// Work item = (sorted position, block of 64*K start states): walks the member
-// and its candidate head from the automaton and compares the end states.
-template <int K>
+// A workgroup takes 32 consecutive sorted positions at a time.  Every unresolved member and
+// its candidate head are walked with the image walk (walk_device.hpp); the pair is then
+// compared without materialising either signature: directly on w when both byte strings
+// start with the same byte (idx[row] is onto, so sig equal <=> w equal), else through
+// sig[q] = w[idx[row][q]] for every q.
+constexpr int kMaxLdsWalkEntries = 72 * 1024;  // 144 KB of uint16; beyond that w lives in global memory
+constexpr int kGlobalWalkGrid = 256;
+
+template <bool W_GLOBAL>
 __global__ __launch_bounds__(kThreads) void verify_rewalk_kernel(
-    const uint16_t *__restrict__ Tt, int S, const uint8_t *__restrict__ tok_bytes,
+    Tables T, int S, int wcap, uint16_t *w_global, const uint8_t *__restrict__ tok_bytes,
     const int64_t *__restrict__ tok_off, const int32_t *__restrict__ vals,
     const int32_t *__restrict__ head_pos, const int32_t *__restrict__ resolved, int n,
     int32_t *mismatch) {
-    const int lane = threadIdx.x & 63;
-    const int64_t gw = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    const int64_t total = (int64_t)gridDim.x * (kThreads / 64);
-    constexpr int SB = 64 * K;
-    const int nsb = (S + SB - 1) / SB;
-    const int64_t n_items = (int64_t)n * nsb;
-    for (int64_t it = gw; it < n_items; it += total) {
-        const int i = (int)(it / nsb);
-        const int sb = (int)(it % nsb);
-        if (resolved[i]) continue;
-        const int32_t tok[2] = {vals[i], vals[head_pos[i]]};
-        int64_t beg[2];
-        int len[2];
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            beg[m] = tok_off[tok[m]];
-            len[m] = __builtin_amdgcn_readfirstlane((int)(tok_off[tok[m] + 1] - beg[m]));
+    extern __shared__ __align__(16) uint16_t dyn_lds[];
+    __shared__ Batch B;
+    __shared__ uint8_t ldsb[kByteCap];
+    uint16_t *w = W_GLOBAL ? w_global + (size_t)blockIdx.x * wcap : dyn_lds;
+    constexpr int kPairs = kBatchTokens / 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool vec = (S % 8) == 0;
+    const int n_chunks = (n + kPairs - 1) / kPairs;
+    for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+        const int i_end = min(n, (chunk + 1) * kPairs);
+        int icur = chunk * kPairs;
+        while (icur < i_end) {  // workgroup-uniform
+            __syncthreads();
+            if (threadIdx.x < 64) {
+                // lanes 2p, 2p+1: member and head of sorted position icur + p
+                const int i = icur + (lane >> 1);
+                int64_t beg = 0, len = -1;
+                if (i < i_end && !resolved[i]) {
+                    const int32_t tok = (lane & 1) ? vals[head_pos[i]] : vals[i];
+                    beg = tok_off[tok];
+                    len = tok_off[tok + 1] - beg;
+                    if (len < 0) len = 0;
+                }
+                const int k = batch_fill(B, T, tok_bytes, beg, len, wcap, 2, 2);
+                if (lane < k) B.aux[lane] = len >= 0 ? 1 : 0;
+            }
+            __syncthreads();
+            const int pairs = min(B.k / 2, i_end - icur);
+            batch_stage_bytes(B, tok_bytes, ldsb);
+            __syncthreads();
+            batch_walk<4, false>(T, T.Tt, S, tok_bytes, B, ldsb, w);
+            __syncthreads();
+            for (int p = wave; p < pairs; p += kThreads / 64) {
+                if (!B.aux[2 * p]) continue;  // wave-uniform
+                const int rm = B.row[2 * p], rh = B.row[2 * p + 1];
+                const uint16_t *wm = w + B.wstart[2 * p], *wh = w + B.wstart[2 * p + 1];
+                bool diff = false;
+                if (rm == rh) {
+                    const int cnt = B.wstart[2 * p + 1] - B.wstart[2 * p];
+                    for (int j = lane; j < cnt; j += 64) diff |= wm[j] != wh[j];
+                } else if (vec) {
+                    const uint4 *im = reinterpret_cast<const uint4 *>(T.idx + (size_t)rm * S);
+                    const uint4 *ih = reinterpret_cast<const uint4 *>(T.idx + (size_t)rh * S);
+                    for (int v = lane; v < S / 8; v += 64) {
+                        const uint4 x = im[v], y = ih[v];
+                        diff |= wm[x.x & 0xFFFFu] != wh[y.x & 0xFFFFu];
+                        diff |= wm[x.x >> 16] != wh[y.x >> 16];
+                        diff |= wm[x.y & 0xFFFFu] != wh[y.y & 0xFFFFu];
+                        diff |= wm[x.y >> 16] != wh[y.y >> 16];
+                        diff |= wm[x.z & 0xFFFFu] != wh[y.z & 0xFFFFu];
+                        diff |= wm[x.z >> 16] != wh[y.z >> 16];
+                        diff |= wm[x.w & 0xFFFFu] != wh[y.w & 0xFFFFu];
+                        diff |= wm[x.w >> 16] != wh[y.w >> 16];
+                    }
+                } else {
+                    const uint16_t *im = T.idx + (size_t)rm * S, *ih = T.idx + (size_t)rh * S;
+                    for (int q = lane; q < S; q += 64) diff |= wm[im[q]] != wh[ih[q]];
+                }
+                if (__ballot(diff) != 0ull && lane == 0) mismatch[icur + p] = 1;
+            }
+            icur += pairs;
         }
-        uint32_t cur[2][K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int q = sb * SB + k * 64 + lane;
-            cur[0][k] = cur[1][k] = q < S ? (uint32_t)q : 0u;
-        }
-        walk_uniform<K, 2>(Tt, S, tok_bytes, beg, len, cur);
-        bool diff = false;
-#pragma unroll
-        for (int k = 0; k < K; ++k) diff |= cur[0][k] != cur[1][k];
-        if (__ballot(diff) != 0ull && lane == 0) mismatch[i] = 1;
     }
 }
 
@@ -445,6 +480,7 @@ struct BuildWorkspace {
     int32_t *seg_head, *head_pos, *resolved, *mismatch, *next_head, *cand;
     int32_t *is_head_token, *id_of_head_token, *tile_tmp;
     uint64_t *rep_key;
+    uint16_t *verify_w;  // walk vectors of the re-walk verification when they do not fit in LDS
     Counters *ctr;
     size_t bytes;
 };
@@ -470,6 +506,9 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
     w.id_of_head_token = c.take<int32_t>(n);
     w.tile_tmp = c.take<int32_t>(nt);
     w.rep_key = c.take<uint64_t>(n);
+    w.verify_w = walk_cap_for(S) > kMaxLdsWalkEntries
+                     ? c.take<uint16_t>((size_t)kGlobalWalkGrid * walk_cap_for(S))
+                     : nullptr;
     w.ctr = c.take<Counters>(1);
     w.bytes = c.used;
     return w;
@@ -535,11 +574,8 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
                        w.head_pos, w.resolved, w.ctr);
     CFGZIP_TRY(check_launch());
 
-    const uint16_t *Tt = nullptr;
-    if (!sig) {
-        const uint64_t *mult_unused = nullptr;
-        CFGZIP_TRY(prepare_tables(table, S, 0, w.sig_ws, &Tt, &mult_unused, stream));
-    }
+    Tables T{};
+    if (!sig) CFGZIP_TRY(prepare_tables(table, S, 0, false, w.sig_ws, &T, stream));
     int n_cu = 256;
     {
         int dev = 0;
@@ -555,16 +591,24 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
                                dim3(kThreads), 0, stream, sig, S, vals, w.head_pos, w.resolved, n,
                                w.mismatch);
         } else {
-            const dim3 grid((unsigned)(n_cu * 8));
-            if (S <= 64)
-                hipLaunchKernelGGL(verify_rewalk_kernel<1>, grid, dim3(kThreads), 0, stream, Tt, S,
-                                   tok_bytes, tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
-            else if (S <= 128)
-                hipLaunchKernelGGL(verify_rewalk_kernel<2>, grid, dim3(kThreads), 0, stream, Tt, S,
-                                   tok_bytes, tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
-            else
-                hipLaunchKernelGGL(verify_rewalk_kernel<4>, grid, dim3(kThreads), 0, stream, Tt, S,
-                                   tok_bytes, tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
+            const int wcap = walk_cap_for(S);
+            const int n_chunks = (int)ceil_div(n, kBatchTokens / 2);
+            if (wcap > kMaxLdsWalkEntries) {
+                hipLaunchKernelGGL(verify_rewalk_kernel<true>,
+                                   dim3((unsigned)std::min(n_chunks, kGlobalWalkGrid)),
+                                   dim3(kThreads), 0, stream, T, S, wcap, w.verify_w, tok_bytes,
+                                   tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
+            } else {
+                const size_t dyn = (size_t)wcap * 2;
+                auto kern = verify_rewalk_kernel<false>;
+                if (dyn > 48 * 1024)
+                    CFGZIP_TRY(check_hip(hipFuncSetAttribute(
+                        reinterpret_cast<const void *>(kern),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn)));
+                hipLaunchKernelGGL(kern, dim3((unsigned)std::min(n_chunks, n_cu * 8)),
+                                   dim3(kThreads), dyn, stream, T, S, wcap, nullptr, tok_bytes,
+                                   tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
+            }
         }
         CFGZIP_TRY(check_launch());
         hipLaunchKernelGGL(settle_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.resolved,

@@ -1,11 +1,15 @@
 // cfgzip_signatures: byte-walk signatures of all tokens and their hash
-// (paper Section 3.2.1 / Algorithm 1, regular case; see walk_device.hpp).
+// (paper Section 3.2.1 / Algorithm 1, regular case; see walk_device.hpp for the
+// image walk that keeps the work per token proportional to the number of
+// distinct states its first byte leaves, not to S).
 //
-// Work item = (group of M tokens, block of 64*K start states), one wavefront
-// each; lanes are start states, so every table read of a step goes to one
-// column Tt[byte][*].  Automata whose whole transposed table fits in LDS are
-// walked from LDS; larger ones are walked from the L2-resident copy in the
-// workspace.  Automata with fewer than 64 states pack several tokens per wave.
+// Per call:  transpose the table, build the per-first-byte image tables, then
+// one kernel in which a workgroup takes 64 consecutive tokens at a time, stages
+// their bytes in LDS, walks all (token, image state) pairs as one flat list of
+// independent lanes, reduces the hash in LDS and expands w through idx into the
+// stored signature rows with 16-byte stores.  Automata whose transposed table
+// fits next to that in LDS are walked from LDS, larger ones from the
+// L2-resident copy in the workspace.
 
 #include <algorithm>
 
@@ -20,10 +24,10 @@ struct WalkArgs {
     const int64_t *tok_off;
     int32_t V;
     int32_t S;
-    const uint16_t *Tt;   // [256][S] (+ pad), workspace
-    const uint64_t *mult; // [S] hash multipliers a_q, workspace
-    uint16_t *sig_out;    // [V][S] or null
-    uint64_t *hash_out;   // [V] or null
+    int32_t wcap;  // entries of w in LDS
+    Tables T;
+    uint16_t *sig_out;   // [V][S] or null
+    uint64_t *hash_out;  // [V] or null
 };
 
 // Tt[b][q] = table[q][b]
@@ -43,139 +47,155 @@ __global__ __launch_bounds__(256) void transpose_table_kernel(const uint16_t *__
     }
 }
 
-__global__ void fill_pad_and_multipliers_kernel(uint16_t *Tt_pad, int n_pad, uint64_t *mult, int S,
-                                                uint64_t seed) {
+__global__ void fill_pad_kernel(uint16_t *Tt_pad, int n_pad) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_pad) Tt_pad[i] = 0;
-    if (i < S) mult[i] = splitmix64_at(seed, (uint32_t)i) | 1ull;
 }
 
-__global__ void zero_u64_kernel(uint64_t *p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
+constexpr int kStateWords = 65536 / 32;  // presence bitmap over every uint16 value
+constexpr int kAccCap = 4096;            // ranks whose multiplier sums are reduced in LDS
 
-// S >= 64 (or any S when no narrow variant applies): lanes = start states.
-template <int K, int M, bool LDS_TABLE>
-__global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void walk_wide_kernel(WalkArgs a) {
-    extern __shared__ uint16_t t_lds[];
-    if (LDS_TABLE) {
-        const int n16 = a.S * 32;  // S*512 bytes / 16
-        const uint4 *src = reinterpret_cast<const uint4 *>(a.Tt);
-        uint4 *dst = reinterpret_cast<uint4 *>(t_lds);
-        for (int i = threadIdx.x; i < n16; i += blockDim.x) dst[i] = src[i];
-        __syncthreads();
+// One workgroup per image row b: distinct states of column b (row 256: the identity map),
+// their ranks, and the multiplier sum of every rank.
+__global__ __launch_bounds__(1024) void image_tables_kernel(const uint16_t *__restrict__ Tt, int S,
+                                                            uint64_t seed, int32_t *nimg,
+                                                            uint16_t *img, uint16_t *idx,
+                                                            uint64_t *wsum) {
+    __shared__ uint32_t present[kStateWords];
+    __shared__ uint32_t wprefix[kStateWords];
+    __shared__ uint32_t wave_tot[16];
+    __shared__ unsigned long long acc[kAccCap];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const uint16_t *col = Tt + (size_t)b * S;
+    auto state_of = [&](int q) -> uint32_t { return b < 256 ? (uint32_t)col[q] : (uint32_t)q; };
+
+    for (int i = tid; i < kStateWords; i += 1024) present[i] = 0;
+    for (int i = tid; i < kAccCap; i += 1024) acc[i] = 0ull;
+    __syncthreads();
+    for (int q = tid; q < S; q += 1024) {
+        const uint32_t s = state_of(q);
+        atomicOr(&present[s >> 5], 1u << (s & 31));
     }
-    const uint16_t *tab = LDS_TABLE ? t_lds : a.Tt;
-
-    const int lane = threadIdx.x & 63;
-    const int waves_per_block = blockDim.x >> 6;
-    const int64_t gw = (int64_t)blockIdx.x * waves_per_block + (threadIdx.x >> 6);
-    const int64_t total_waves = (int64_t)gridDim.x * waves_per_block;
-    constexpr int SB = 64 * K;
-    const int S = a.S;
-    const int nsb = (S + SB - 1) / SB;
-    const int64_t n_items = ((int64_t)a.V + M - 1) / M * nsb;
-
-    for (int64_t i = gw; i < n_items; i += total_waves) {
-        const int sb = (int)(i % nsb);
-        const int64_t t0 = (i / nsb) * M;
-        int64_t beg[M];
-        int len[M];
+    __syncthreads();
+    // exclusive prefix of the per-word population counts; thread i owns words 2i, 2i+1
+    const uint32_t c0 = __popc(present[2 * tid]), c1 = __popc(present[2 * tid + 1]);
+    int incl = wave_inclusive_sum((int)(c0 + c1));
+    if (lane == 63) wave_tot[wave] = (uint32_t)incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int wv = 0; wv < wave; ++wv) before += wave_tot[wv];
+    const uint32_t excl = before + (uint32_t)incl - (c0 + c1);
+    wprefix[2 * tid] = excl;
+    wprefix[2 * tid + 1] = excl + c0;
+    uint32_t n = 0;
+    for (int wv = 0; wv < 16; ++wv) n += wave_tot[wv];  // distinct states, <= S
+    if (tid == 0) nimg[b] = (int32_t)n;
+    // img: the set bits in ascending order
+    {
+        uint32_t r = excl;
 #pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const bool tv = t0 + m < a.V;
-            const int64_t o0 = tv ? a.tok_off[t0 + m] : 0;
-            const int64_t o1 = tv ? a.tok_off[t0 + m + 1] : 0;
-            beg[m] = o0;
-            len[m] = __builtin_amdgcn_readfirstlane((int)(o1 - o0));
-        }
-        int q[K];
-        uint32_t cur[M][K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            q[k] = sb * SB + k * 64 + lane;
-#pragma unroll
-            for (int m = 0; m < M; ++m) cur[m][k] = q[k] < S ? (uint32_t)q[k] : 0u;
-        }
-        walk_uniform<K, M>(tab, S, a.tok_bytes, beg, len, cur);
-
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            if (t0 + m >= a.V) continue;
-            if (a.sig_out) {
-#pragma unroll
-                for (int k = 0; k < K; ++k)
-                    if (q[k] < S) a.sig_out[(size_t)(t0 + m) * S + q[k]] = (uint16_t)cur[m][k];
+        for (int h = 0; h < 2; ++h) {
+            uint32_t bits = present[2 * tid + h];
+            while (bits) {
+                const int bit = __ffs(bits) - 1;
+                bits &= bits - 1;
+                img[(size_t)b * S + r++] = (uint16_t)((2 * tid + h) * 32 + bit);
             }
-            if (a.hash_out) {
-                uint64_t h = 0;
-#pragma unroll
-                for (int k = 0; k < K; ++k)
-                    if (q[k] < S) h += a.mult[q[k]] * (uint64_t)cur[m][k];
-                h = wave_sum_u64(h);
-                if (lane == 0) {
-                    if (nsb == 1) a.hash_out[t0 + m] = h;
-                    else atomicAdd(reinterpret_cast<unsigned long long *>(a.hash_out + t0 + m),
-                                   (unsigned long long)h);
+        }
+    }
+    if (wsum)
+        for (uint32_t r = kAccCap + tid; r < n; r += 1024) wsum[(size_t)b * S + r] = 0ull;
+    __syncthreads();
+    for (int q = tid; q < S; q += 1024) {
+        const uint32_t s = state_of(q);
+        const uint32_t r = wprefix[s >> 5] + __popc(present[s >> 5] & ((1u << (s & 31)) - 1u));
+        idx[(size_t)b * S + q] = (uint16_t)r;
+        if (wsum) {
+            const unsigned long long a = splitmix64_at(seed, (uint32_t)q) | 1ull;
+            if (r < kAccCap) atomicAdd(&acc[r], a);
+            else atomicAdd(reinterpret_cast<unsigned long long *>(wsum + (size_t)b * S + r), a);
+        }
+    }
+    __syncthreads();
+    if (wsum)
+        for (uint32_t r = tid; r < n && r < kAccCap; r += 1024) wsum[(size_t)b * S + r] = acc[r];
+}
+
+template <bool LDS_TABLE>
+__global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(WalkArgs a) {
+    extern __shared__ __align__(16) uint16_t dyn_lds[];  // [table S*256 if LDS_TABLE][w wcap]
+    __shared__ Batch B;
+    __shared__ uint8_t ldsb[kByteCap];
+    const int S = a.S;
+    if (LDS_TABLE) {
+        const int n16 = S * 32;  // S*512 bytes / 16
+        const uint4 *src = reinterpret_cast<const uint4 *>(a.T.Tt);
+        uint4 *dst = reinterpret_cast<uint4 *>(dyn_lds);
+        for (int i = threadIdx.x; i < n16; i += blockDim.x) dst[i] = src[i];
+    }
+    const uint16_t *tab = LDS_TABLE ? dyn_lds : a.T.Tt;
+    uint16_t *w = dyn_lds + (LDS_TABLE ? (size_t)S * 256 : 0);
+    const int lane = threadIdx.x & 63;
+    const bool first_wave = threadIdx.x < 64;
+    const bool vec = (S % 8) == 0 && (reinterpret_cast<uintptr_t>(a.sig_out) % 16) == 0;
+
+    const int64_t n_chunks = ((int64_t)a.V + kBatchTokens - 1) / kBatchTokens;
+    for (int64_t chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+        const int64_t t_end = min((int64_t)a.V, (chunk + 1) * kBatchTokens);
+        int64_t tcur = chunk * kBatchTokens;
+        while (tcur < t_end) {  // workgroup-uniform
+            __syncthreads();    // previous batch fully consumed (and the table loaded)
+            if (first_wave) {
+                const int64_t t = tcur + lane;
+                int64_t beg = 0, len = -1;
+                if (t < t_end) {
+                    beg = a.tok_off[t];
+                    len = a.tok_off[t + 1] - beg;
+                    if (len < 0) len = 0;  // offsets must not decrease; stay in bounds if they do
+                }
+                batch_fill(B, a.T, a.tok_bytes, beg, len, a.wcap, 1, 1);
+            }
+            __syncthreads();
+            const int k = (int)min((int64_t)B.k, t_end - tcur);
+            batch_stage_bytes(B, a.tok_bytes, ldsb);
+            __syncthreads();
+            if (a.hash_out) batch_walk<4, true>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
+            else batch_walk<4, false>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
+            __syncthreads();
+            if (a.hash_out && (int)threadIdx.x < k) a.hash_out[tcur + threadIdx.x] = B.hash[threadIdx.x];
+            if (a.sig_out) {
+                // sig[t][q] = w[idx[row][q]]
+                if (vec) {
+                    const uint32_t s8 = (uint32_t)S / 8;
+                    const uint32_t items = (uint32_t)k * s8;
+                    for (uint32_t x = threadIdx.x; x < items; x += blockDim.x) {
+                        const uint32_t m = x / s8, q0 = (x - m * s8) * 8;
+                        const uint4 id = *reinterpret_cast<const uint4 *>(
+                            a.T.idx + (size_t)B.row[m] * S + q0);
+                        const uint16_t *wm = w + B.wstart[m];
+                        uint4 o;
+                        o.x = (uint32_t)wm[id.x & 0xFFFFu] | ((uint32_t)wm[id.x >> 16] << 16);
+                        o.y = (uint32_t)wm[id.y & 0xFFFFu] | ((uint32_t)wm[id.y >> 16] << 16);
+                        o.z = (uint32_t)wm[id.z & 0xFFFFu] | ((uint32_t)wm[id.z >> 16] << 16);
+                        o.w = (uint32_t)wm[id.w & 0xFFFFu] | ((uint32_t)wm[id.w >> 16] << 16);
+                        *reinterpret_cast<uint4 *>(a.sig_out + (size_t)(tcur + m) * S + q0) = o;
+                    }
+                } else {
+                    const uint32_t items = (uint32_t)k * (uint32_t)S;
+                    for (uint32_t x = threadIdx.x; x < items; x += blockDim.x) {
+                        const uint32_t m = x / (uint32_t)S, q = x - m * (uint32_t)S;
+                        a.sig_out[(size_t)(tcur + m) * S + q] =
+                            w[B.wstart[m] + a.T.idx[(size_t)B.row[m] * S + q]];
+                    }
                 }
             }
+            tcur += k;
         }
     }
 }
 
-// S < 64: a wave holds 64 / SP tokens, SP = smallest power of two >= S; table in LDS.
-__global__ __launch_bounds__(256) void walk_narrow_kernel(WalkArgs a, int SP) {
-    extern __shared__ uint16_t t_lds[];
-    {
-        const int n16 = a.S * 32;
-        const uint4 *src = reinterpret_cast<const uint4 *>(a.Tt);
-        uint4 *dst = reinterpret_cast<uint4 *>(t_lds);
-        for (int i = threadIdx.x; i < n16; i += blockDim.x) dst[i] = src[i];
-        __syncthreads();
-    }
-    const int S = a.S;
-    const int per_thread_block = blockDim.x / SP;  // tokens per workgroup pass
-    const int slot = threadIdx.x / SP;
-    const int q = threadIdx.x % SP;
-    for (int64_t t = (int64_t)blockIdx.x * per_thread_block + slot; t < a.V;
-         t += (int64_t)gridDim.x * per_thread_block) {
-        // lanes of one token slot that lie beyond S idle through the walk
-        const int64_t beg = a.tok_off[t];
-        const int len = (int)(a.tok_off[t + 1] - beg);
-        uint32_t cur = q < S ? (uint32_t)q : 0u;
-        for (int p = 0; p < len; ++p) {
-            const uint32_t b = a.tok_bytes[beg + p];
-            cur = t_lds[b * S + cur];
-        }
-        if (q < S && a.sig_out) a.sig_out[(size_t)t * S + q] = (uint16_t)cur;
-        if (a.hash_out) {
-            uint64_t h = q < S ? a.mult[q] * (uint64_t)cur : 0ull;
-            h = wave_sum_u64(h, SP);
-            if (q == 0) a.hash_out[t] = h;
-        }
-    }
-}
-
-constexpr size_t kLdsTableLimit = 144 * 1024;
-
-template <int K, int M>
-int launch_wide(const WalkArgs &a, bool lds, int n_cu, hipStream_t stream) {
-    if (lds) {
-        auto kern = walk_wide_kernel<K, M, true>;
-        const size_t bytes = (size_t)a.S * 512;
-        if (bytes > 64 * 1024)
-            CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                     (int)bytes)));
-        const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(2, (160 * 1024) / bytes));
-        hipLaunchKernelGGL(kern, dim3(n_cu * per_cu), dim3(1024), bytes, stream, a);
-    } else {
-        auto kern = walk_wide_kernel<K, M, false>;
-        hipLaunchKernelGGL(kern, dim3(n_cu * 8), dim3(256), 0, stream, a);
-    }
-    return check_launch();
-}
+constexpr size_t kLdsTableLimit = 128 * 1024;  // S <= 256
 
 int device_cu_count(int *out) {
     int dev = 0;
@@ -186,37 +206,46 @@ int device_cu_count(int *out) {
     return CFGZIP_OK;
 }
 
-}  // namespace
-
-// Layout of the signature workspace: Tt (+pad), then the hash multipliers.
+// Layout of the signature workspace.
 struct SigWorkspace {
     uint16_t *Tt;
-    uint64_t *mult;
+    int32_t *nimg;
+    uint16_t *img, *idx;
+    uint64_t *wsum;
     size_t bytes;
 };
 
-static SigWorkspace carve_sig_ws(void *ws, int32_t S) {
+SigWorkspace carve_sig_ws(void *ws, int32_t S) {
     Carver c(ws);
     SigWorkspace w;
     w.Tt = c.take<uint16_t>((size_t)256 * S + kTablePad);
-    w.mult = c.take<uint64_t>((size_t)S);
+    w.nimg = c.take<int32_t>(kImageRows);
+    w.img = c.take<uint16_t>((size_t)kImageRows * S);
+    w.idx = c.take<uint16_t>((size_t)kImageRows * S);
+    w.wsum = c.take<uint64_t>((size_t)kImageRows * S);
     w.bytes = c.used;
     return w;
 }
 
-// Builds Tt and the multipliers in the workspace.  Shared with the class builder.
-int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, void *ws,
-                   const uint16_t **Tt_out, const uint64_t **mult_out, hipStream_t stream) {
+}  // namespace
+
+int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, void *ws,
+                   Tables *out, hipStream_t stream) {
     SigWorkspace w = carve_sig_ws(ws, S);
     hipLaunchKernelGGL(transpose_table_kernel, dim3((S + 63) / 64, 4), dim3(256), 0, stream, table,
                        w.Tt, S);
     CFGZIP_TRY(check_launch());
-    const int n = std::max(kTablePad, S);
-    hipLaunchKernelGGL(fill_pad_and_multipliers_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
-                       w.Tt + (size_t)256 * S, kTablePad, w.mult, S, hash_seed);
+    hipLaunchKernelGGL(fill_pad_kernel, dim3((kTablePad + 255) / 256), dim3(256), 0, stream,
+                       w.Tt + (size_t)256 * S, kTablePad);
     CFGZIP_TRY(check_launch());
-    *Tt_out = w.Tt;
-    *mult_out = w.mult;
+    hipLaunchKernelGGL(image_tables_kernel, dim3(kImageRows), dim3(1024), 0, stream, w.Tt, S,
+                       hash_seed, w.nimg, w.img, w.idx, want_wsum ? w.wsum : nullptr);
+    CFGZIP_TRY(check_launch());
+    out->Tt = w.Tt;
+    out->nimg = w.nimg;
+    out->img = w.img;
+    out->idx = w.idx;
+    out->wsum = want_wsum ? w.wsum : nullptr;
     return CFGZIP_OK;
 }
 
@@ -251,30 +280,34 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
     a.S = S;
     a.sig_out = sig_out;
     a.hash_out = hash_out;
-    CFGZIP_TRY(prepare_tables(table, S, hash_seed, ws, &a.Tt, &a.mult, stream));
+    CFGZIP_TRY(prepare_tables(table, S, hash_seed, hash_out != nullptr, ws, &a.T, stream));
 
     int n_cu = 256;
     CFGZIP_TRY(device_cu_count(&n_cu));
-    const bool lds = (size_t)S * 512 <= kLdsTableLimit;
-
-    if (S < 64) {
-        int SP = 1;
-        while (SP < S) SP <<= 1;
-        const int tokens_per_block = 256 / SP;
-        int64_t blocks = ceil_div(V, tokens_per_block);
-        blocks = std::min<int64_t>(blocks, (int64_t)n_cu * 8);
-        hipLaunchKernelGGL(walk_narrow_kernel, dim3((int)blocks), dim3(256), (size_t)S * 512, stream,
-                           a, SP);
-        return check_launch();
+    const int64_t n_chunks = ceil_div(V, kBatchTokens);
+    const bool lds_table = (size_t)S * 512 <= kLdsTableLimit;
+    // the signatures kernel walks one token at a time in the worst case: S entries suffice
+    a.wcap = std::max(kMinWalkCap, S);
+    if (lds_table) {
+        const size_t dyn = (size_t)S * 512 + (size_t)a.wcap * 2;
+        auto kern = signatures_kernel<true>;
+        if (dyn > 48 * 1024)
+            CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)dyn)));
+        // loading the table costs a workgroup about as much as walking a few batches
+        const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(2, (150 * 1024) / (dyn + 8192)));
+        const int64_t grid = std::min<int64_t>(ceil_div(n_chunks, 2), (int64_t)n_cu * per_cu);
+        hipLaunchKernelGGL(kern, dim3((unsigned)std::max<int64_t>(1, grid)), dim3(1024), dyn, stream, a);
+    } else {
+        const size_t dyn = (size_t)a.wcap * 2;
+        auto kern = signatures_kernel<false>;
+        if (dyn > 48 * 1024)
+            CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)dyn)));
+        const int64_t grid = std::min<int64_t>(n_chunks, (int64_t)n_cu * 8);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), dyn, stream, a);
     }
-    const int nsb4 = (S + 255) / 256;
-    if (hash_out && S > 256) {
-        hipLaunchKernelGGL(zero_u64_kernel, dim3((V + 255) / 256), dim3(256), 0, stream, hash_out,
-                           (int64_t)V);
-        CFGZIP_TRY(check_launch());
-    }
-    (void)nsb4;
-    if (S <= 64) return launch_wide<1, 4>(a, lds, n_cu, stream);
-    if (S <= 128) return launch_wide<2, 4>(a, lds, n_cu, stream);
-    return launch_wide<4, 2>(a, lds, n_cu, stream);
+    return check_launch();
 }

@@ -1,10 +1,27 @@
-// Device-side byte walk shared by the signature kernels and by the class
-// builder's re-walk verification (paper Section 3.2.1 / Algorithm 1 restricted to
-// a deterministic byte automaton:  sig[t][q] = delta*(q, bytes(t))).
+// Device-side pieces of the byte walk shared by cfgzip_signatures and by the
+// class builder's re-walk verification (paper Section 3.2.1 / Algorithm 1
+// restricted to a deterministic byte automaton:  sig[t][q] = delta*(q, bytes(t))).
 //
-// Table layout used on the device: the caller's table[q][b] is transposed once
-// into Tt[b][q] so that one token byte selects one contiguous column of S
-// uint16 entries; a wavefront's lanes are start states, the byte is uniform.
+// Image walk.  After its first byte b a token can only be in one of the
+// distinct states of column b of the automaton, whatever state it started in.
+// So a token is not walked from all S states: only the nimg[b] distinct states
+// of its first byte's column are walked through the remaining bytes, giving a
+// short vector w, and
+//     sig[t][q] = w[idx[b][q]],
+//     H(t)      = sum_j wsum[b][j] * w[j]      (the hash is linear, so this is
+//                                               bit-identical to the sum over q).
+// Lexer-like automata send most (state, byte) pairs to the reject state, so
+// nimg[b] is typically a few percent of S; a random automaton gives no gain
+// (nimg[b] ~ 0.63 S) and costs one extra indirection.
+//
+// Tables kept in the signature workspace (built per call by prepare_tables):
+//   Tt[b][q]   = table[q][b]            one byte selects one contiguous column
+//   per image row b (0..255 = first byte; 256 = "no byte", the identity map of
+//   the empty token):
+//   nimg[b]    = number of distinct states in column b
+//   img[b][j]  = j-th distinct state of column b, ascending           (j < nimg[b])
+//   idx[b][q]  = position of Tt[b][q] in img[b]
+//   wsum[b][j] = sum of the hash multipliers a_q over all q with idx[b][q] == j
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -15,6 +32,26 @@ namespace cfgzip {
 // Tt is over-allocated by this many entries so that a table entry >= S (a
 // caller error) still indexes inside the workspace.
 constexpr int kTablePad = 65536;
+constexpr int kImageRows = 257;     // 256 first bytes + the "empty token" row
+constexpr int kBatchTokens = 64;    // tokens a workgroup walks together (one per lane of a wave)
+constexpr int kByteCap = 4096;      // token bytes staged in LDS per batch
+constexpr int kMinWalkCap = 8192;   // walks (entries of w) held in LDS per batch, at least
+
+struct Tables {
+    const uint16_t *Tt;
+    const int32_t *nimg;
+    const uint16_t *img;
+    const uint16_t *idx;
+    const uint64_t *wsum;  // null when no hash is wanted
+};
+
+// Builds all tables in the signature workspace.  Host functions, defined in walk.hip.
+int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, void *ws,
+                   Tables *out, hipStream_t stream);
+size_t sig_workspace_bytes(int32_t S);
+// Entries of w a batch may hold for an automaton of S states (>= 2 S, so that
+// any two tokens fit together).
+inline int walk_cap_for(int32_t S) { return 2 * S > kMinWalkCap ? 2 * S : kMinWalkCap; }
 
 __device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint32_t index) {
     // index-th output (0-based) of the SplitMix64 generator seeded with `seed`
@@ -24,46 +61,156 @@ __device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint32_t index)
     return z ^ (z >> 31);
 }
 
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v, int width = 64) {
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ int wave_inclusive_sum(int v) {
+    const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
-        if (off < width) v += __shfl_xor(v, off, 64);
+        const int o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
     }
     return v;
 }
 
-// Walks M tokens at once from K start states per lane.  `tab` points at Tt
-// (global or LDS).  beg/len are wave-uniform.  cur[m][k] must hold the start
-// states on entry and holds the end states on return.
-template <int K, int M>
-__device__ __forceinline__ void walk_uniform(const uint16_t *tab, int S,
-                                             const uint8_t *__restrict__ tok_bytes,
-                                             const int64_t (&beg)[M], const int (&len)[M],
-                                             uint32_t (&cur)[M][K]) {
+// A batch of up to kBatchTokens byte strings that a workgroup walks together.
+// Slot m owns walks [wstart[m], wstart[m+1]) and staged bytes [boff[m], boff[m+1]).
+// A slot with no walks (an unused lane) has wstart[m] == wstart[m+1].
+struct Batch {
+    int32_t k;             // slots in use
+    int32_t wtotal;        // walks of the batch
+    int32_t btotal;        // staged bytes of the batch
+    int32_t bytes_in_lds;  // 0: a single over-long token, its bytes are read from global memory
+    int32_t wstart[kBatchTokens + 1];
+    int32_t boff[kBatchTokens + 1];
+    int32_t len[kBatchTokens];
+    int32_t row[kBatchTokens];  // image row: first byte, or 256 for an empty byte string
+    int32_t aux[kBatchTokens];  // free for the kernel that fills the batch
+    int64_t beg[kBatchTokens];  // offset of the first byte in tok_bytes
+    unsigned long long hash[kBatchTokens];
+};
+
+// Largest m < k with starts[m] <= i (starts non-decreasing, starts[0] <= i).
+__device__ __forceinline__ int batch_find(const int32_t *starts, int k, int i) {
+    int lo = 0;
+#pragma unroll
+    for (int step = kBatchTokens / 2; step >= 1; step >>= 1) {
+        const int c = lo + step;
+        if (c < k && starts[c] <= i) lo = c;
+    }
+    return lo;
+}
+
+// Filled by the 64 lanes of one wave: lane l proposes byte string (beg, len) (len < 0: lane
+// unused).  Slots are accepted in lane order while the walks fit in `wcap` entries and the
+// bytes in kByteCap; at least `min_lanes` lanes are accepted (their walks always fit, see
+// walk_cap_for; if their bytes do not, the batch reads bytes from global memory).  Returns
+// the number of accepted lanes, rounded down to a multiple of `group` (wave-uniform).
+__device__ __forceinline__ int batch_fill(Batch &B, const Tables &T, const uint8_t *tok_bytes,
+                                          int64_t beg, int64_t len64, int wcap, int min_lanes,
+                                          int group) {
     const int lane = threadIdx.x & 63;
-    int maxlen = 0;
+    const bool used = len64 >= 0;
+    const int len = !used ? 0 : (len64 > 0x7FFFFFFF ? 0x7FFFFFFF : (int)len64);
+    const int row = len > 0 ? (int)tok_bytes[beg] : 256;
+    const int n = used ? T.nimg[row] : 0;
+    const int lenc = len > kByteCap ? kByteCap + 1 : len;
+    const int incl_n = wave_inclusive_sum(n);
+    const int incl_b = wave_inclusive_sum(lenc);
+    const bool fits = lane < min_lanes || (incl_n <= wcap && incl_b <= kByteCap);
+    const uint64_t mask = __ballot(fits);
+    // accepted lanes form a prefix: both sums are non-decreasing
+    int k = mask == ~0ull ? 64 : __ffsll((unsigned long long)~mask) - 1;
+    k -= k % group;
+    if (lane < k) {
+        B.wstart[lane] = incl_n - n;
+        B.boff[lane] = incl_b - lenc;
+        B.len[lane] = len;
+        B.row[lane] = row;
+        B.beg[lane] = beg;
+        B.hash[lane] = 0ull;
+    }
+    if (lane == k - 1) {
+        B.wstart[k] = incl_n;
+        B.boff[k] = incl_b;
+        B.k = k;
+        B.wtotal = incl_n;
+        B.btotal = incl_b;
+        B.bytes_in_lds = incl_b <= kByteCap ? 1 : 0;
+    }
+    return k;
+}
+
+// Copies the batch's bytes into LDS (all threads of the workgroup).
+__device__ __forceinline__ void batch_stage_bytes(const Batch &B, const uint8_t *__restrict__ tok_bytes,
+                                                  uint8_t *ldsb) {
+    if (!B.bytes_in_lds) return;
+    const int total = B.btotal, k = B.k;
+    for (int x = threadIdx.x; x < total; x += blockDim.x) {
+        const int m = batch_find(B.boff, k, x);
+        ldsb[x] = tok_bytes[B.beg[m] + (x - B.boff[m])];
+    }
+}
+
+// Walks every (slot, image state) pair of the batch: w[wstart[m] + j] = state reached from
+// img[row][j] on bytes 1.. of slot m.  U walks are in flight per thread.  With HASH, also
+// accumulates B.hash[m] += wsum[row][j] * w (order-free).
+template <int U, bool LDS_BYTES, bool HASH>
+__device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t *tab, int S,
+                                                const uint8_t *__restrict__ tok_bytes, Batch &B,
+                                                const uint8_t *ldsb, uint16_t *w) {
+    const int nt = blockDim.x, k = B.k, wtotal = B.wtotal;
+    for (int i0 = threadIdx.x; i0 < wtotal; i0 += nt * U) {
+        uint32_t cur[U];
+        int rem[U], slot[U], j[U];
+        int64_t src[U];  // index of byte 1 in ldsb or tok_bytes
+        int maxrem = 0;
 #pragma unroll
-    for (int m = 0; m < M; ++m) maxlen = max(maxlen, len[m]);
-    for (int base = 0; base < maxlen; base += 64) {
-        uint32_t mybyte[M];
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const int idx = base + lane;
-            mybyte[m] = idx < len[m] ? (uint32_t)tok_bytes[beg[m] + idx] : 0u;
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * nt;
+            rem[u] = 0;
+            cur[u] = 0;
+            slot[u] = 0;
+            j[u] = 0;
+            src[u] = 0;
+            if (i < wtotal) {
+                const int m = batch_find(B.wstart, k, i);
+                slot[u] = m;
+                j[u] = i - B.wstart[m];
+                cur[u] = T.img[(size_t)B.row[m] * S + j[u]];
+                rem[u] = B.len[m] > 0 ? B.len[m] - 1 : 0;
+                src[u] = (LDS_BYTES ? (int64_t)B.boff[m] : B.beg[m]) + 1;
+                maxrem = max(maxrem, rem[u]);
+            }
         }
-        const int steps = min(64, maxlen - base);
-        for (int p = 0; p < steps; ++p) {
+        for (int p = 0; p < maxrem; ++p) {
 #pragma unroll
-            for (int m = 0; m < M; ++m) {
-                if (base + p < len[m]) {  // wave-uniform
-                    const uint32_t b = __builtin_amdgcn_readlane(mybyte[m], p);
-                    const uint16_t *col = tab + (size_t)b * S;
-#pragma unroll
-                    for (int k = 0; k < K; ++k) cur[m][k] = col[cur[m][k]];
+            for (int u = 0; u < U; ++u) {
+                if (p < rem[u]) {
+                    const uint32_t b = LDS_BYTES ? ldsb[(int)src[u] + p] : tok_bytes[src[u] + p];
+                    cur[u] = tab[(size_t)b * S + cur[u]];
                 }
             }
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * nt;
+            if (i < wtotal) {
+                w[i] = (uint16_t)cur[u];
+                if (HASH)
+                    atomicAdd(&B.hash[slot[u]],
+                              (unsigned long long)(T.wsum[(size_t)B.row[slot[u]] * S + j[u]] *
+                                                   (uint64_t)cur[u]));
+            }
+        }
     }
+}
+
+template <int U, bool HASH>
+__device__ __forceinline__ void batch_walk(const Tables &T, const uint16_t *tab, int S,
+                                           const uint8_t *__restrict__ tok_bytes, Batch &B,
+                                           const uint8_t *ldsb, uint16_t *w) {
+    if (B.bytes_in_lds) batch_walk_impl<U, true, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
+    else batch_walk_impl<U, false, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
 }
 
 }  // namespace cfgzip

@@ -72,16 +72,37 @@ def test_signatures_state_counts(lib, S):
     _check_signatures(lib, vocab, table)
 
 
+@pytest.mark.parametrize("S", [9000, 40000, 65536])
+def test_large_state_counts(lib, S):
+    """State counts whose walk vectors need more than the minimum LDS buffer (S > 8192)
+    and, for the re-walk verification, more than LDS holds (2 S entries > 144 KB)."""
+    print(f"case S={S}", flush=True)
+    rng = np.random.default_rng(S)
+    table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+    table[:, 65:91] = (np.arange(S)[:, None] % 7).astype(np.uint16)  # a few narrow columns
+    toks = [b"", b"A", b"AB", b"Ab", b"ab", b"abc", b"ab", b"zzzz", b"B", b"A"] * 3
+    toks += [rng.integers(0, 256, size=int(rng.integers(1, 6)), dtype=np.uint8).tobytes()
+             for _ in range(40)]
+    vocab = vocab_from_tokens(toks)
+    _check_signatures(lib, vocab, table)
+    _check_build(lib, vocab, table, stored=False)
+    _check_build(lib, vocab, table, stored=True)
+
+
 def test_signatures_long_and_empty_tokens(lib):
     rng = np.random.default_rng(0)
     for S in (24, 256, 700):
         print(f"case long tokens S={S}", flush=True)
         table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
-        toks = [b"", b"a", rng.integers(0, 256, size=64, dtype=np.uint8).tobytes(),
+        toks = [b"", b"a", rng.integers(0, 256, size=5000, dtype=np.uint8).tobytes(),
+                rng.integers(0, 256, size=64, dtype=np.uint8).tobytes(),
                 rng.integers(0, 256, size=65, dtype=np.uint8).tobytes(), b"",
                 rng.integers(0, 256, size=200, dtype=np.uint8).tobytes(),
                 rng.integers(0, 256, size=129, dtype=np.uint8).tobytes(), b"zz", b""]
+        toks += [toks[2], toks[5], b"zz", toks[2]]  # duplicates: members to verify against a head
         _check_signatures(lib, vocab_from_tokens(toks), table)
+        _check_build(lib, vocab_from_tokens(toks), table, stored=False)
+        _check_build(lib, vocab_from_tokens(toks), table, stored=True)
 
 
 def test_signatures_all_tokens_empty(lib):
