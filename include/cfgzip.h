@@ -102,12 +102,14 @@ int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t 
  * byte-wise shortest member (ties: smallest token id).  Class ids are issued in
  * order of each class's smallest token id, so c[0] = 0.
  *
- * Method: radix sort of (hash, token id), equal-hash segments, then every
- * member's full signature is compared with its segment head; members that differ
- * (a hash collision) are split off in further rounds, so the result is exact for
- * any `hash` that is a function of the signature (equal signatures must carry
- * equal hashes).  With sig == NULL signatures are recomputed from the automaton
- * for the comparison instead of being read.
+ * Method: radix sort by (hash, first byte) with the token id as value, equal-hash
+ * segments, then every member's full signature is compared with its left
+ * neighbour's in the segment (equality is transitive); members that differ (a
+ * hash collision) start a chain of their own and the chains of a segment are
+ * matched against each other in further rounds, so the result is exact for any
+ * `hash` that is a function of the signature (equal signatures must carry equal
+ * hashes).  With sig == NULL signatures are recomputed from the automaton for
+ * the comparison instead of being read.
  *
  *   tok_bytes, tok_off, V, table, S   as for cfgzip_signatures
  *   sig        uint16 [V][S] from cfgzip_signatures, or NULL
@@ -117,7 +119,8 @@ int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t 
  *   num_classes_dev  out, int32 [1] device, or NULL
  *   num_classes_host out, int32 [1] HOST, or NULL
  *   collisions_host  out, int32 [1] HOST, or NULL: number of tokens whose signature
- *                    differed from their equal-hash segment head
+ *                    differed from that of their left neighbour in an equal-hash
+ *                    segment (0 unless hashes collide)
  *   ws         cfgzip_build_classes_workspace_bytes(V, S) bytes, 256-byte aligned
  * Synchronises `stream` before returning.
  */

@@ -2,17 +2,25 @@
 // and pick representatives (paper Section 3.1 "Pre-Computation").
 //
 // Pipeline (all on the device):
-//   1. stable LSD radix sort of (hash, token id), 8 bits per pass;
-//   2. equal-hash segments; every member's signature is compared with its
-//      segment head's (read from sig, or re-walked when sig is not stored);
-//   3. members that differ from their head (hash collisions) are split off in
-//      rounds: the first unresolved member of a segment becomes a new head and
-//      the rest are compared with it, until nothing is unresolved - exact for
-//      any hash that is a function of the signature;
-//   4. class id = rank of the class head's token id among all heads (heads are
-//      the smallest ids of their classes because the sort is stable), by a
+//   1. stable LSD radix sort of the 48-bit key (low 40 bits of the hash, first
+//      byte of the token) with the token id as value, 8 bits per pass, two
+//      kernels per pass: per-tile digit counts, then a scatter that ranks its
+//      tile and adds over the counts of the earlier tiles itself;
+//   2. equal-hash segments; inside a segment tokens with the same first byte are
+//      neighbours.  Every member is compared with its left neighbour (a chain:
+//      equality is transitive).  Stored signatures are compared row by row;
+//      without stored signatures both are re-walked with the image walk and
+//      compared on the short vector w when they share the first byte, through
+//      the index tables otherwise (walk_device.hpp);
+//   3. if no link differs (no hash collision - the overwhelmingly common case),
+//      the segments are the classes.  Otherwise every differing member starts a
+//      new chain and the chain starts of a segment are matched against each
+//      other in rounds (the first unmatched one becomes a class, the rest are
+//      compared with it) - exact for any hash that is a function of the signature;
+//   4. class id = rank of the class's smallest token id among all classes, by a
 //      prefix sum over token ids;
 //   5. representative = min over members of (byte length, token id).
+// The host waits once, for the class count and the number of differing links.
 
 #include <algorithm>
 
@@ -20,7 +28,6 @@
 #include "walk_device.hpp"
 
 namespace cfgzip {
-
 namespace {
 
 constexpr int kThreads = 256;
@@ -28,12 +35,37 @@ constexpr int kItems = 8;
 constexpr int kTile = kThreads * kItems;  // keys per workgroup in sort and scan kernels
 constexpr int kRadixBits = 8;
 constexpr int kBins = 1 << kRadixBits;
+constexpr int kHashBits = 40;                   // hash bits that take part in the sort
+constexpr int kKeyBits = kHashBits + 8;         // + first byte
+constexpr int kPasses = kKeyBits / kRadixBits;  // 6
+constexpr uint64_t kHashMask = (1ull << kHashBits) - 1ull;
+static_assert(kThreads == kBins, "one thread per bin in the sort kernels");
+
+struct Counters {
+    int32_t unresolved;
+    int32_t num_classes;
+    int32_t pad[6];
+};
 
 // ---------------------------------------------------------------- radix sort
 
-__global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint64_t *__restrict__ keys,
-                                                              int n, int shift, uint32_t *hist,
-                                                              int nb) {
+// key of token t: hash bits above its first byte (0 for the empty token; a clash
+// of that 0 with a real first byte only costs a slower comparison)
+__device__ __forceinline__ uint64_t sort_key(const uint64_t *__restrict__ hash,
+                                             const int64_t *__restrict__ tok_off,
+                                             const uint8_t *__restrict__ tok_bytes, int t) {
+    const int64_t beg = tok_off[t];
+    const uint32_t fb = tok_off[t + 1] > beg ? (uint32_t)tok_bytes[beg] : 0u;
+    return ((hash[t] & kHashMask) << 8) | fb;
+}
+
+// Digit counts of one pass per tile: hist[tile][digit].  The first pass forms its keys from
+// the hash and the first bytes; later passes read the keys the previous pass wrote.
+template <bool FIRST>
+__global__ __launch_bounds__(kThreads) void radix_hist_kernel(
+    const uint64_t *__restrict__ hash, const int64_t *__restrict__ tok_off,
+    const uint8_t *__restrict__ tok_bytes, const uint64_t *__restrict__ keys, int n, int shift,
+    uint32_t *hist) {
     __shared__ uint32_t bins[kBins];
     bins[threadIdx.x] = 0;
     __syncthreads();
@@ -41,51 +73,62 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(const uint64_t *__
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
         const int idx = base + j * kThreads + threadIdx.x;
-        if (idx < n) atomicAdd(&bins[(uint32_t)(keys[idx] >> shift) & (kBins - 1)], 1u);
-    }
-    __syncthreads();
-    hist[(size_t)threadIdx.x * nb + blockIdx.x] = bins[threadIdx.x];
-}
-
-// In-place exclusive sum scan of `n` uint32 by one workgroup of 1024 threads.
-__global__ __launch_bounds__(1024) void scan_u32_single_block_kernel(uint32_t *data, int n) {
-    __shared__ uint32_t wave_tot[16];
-    __shared__ uint32_t carry_s;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) carry_s = 0;
-    __syncthreads();
-    for (int base = 0; base < n; base += 1024) {
-        const int idx = base + threadIdx.x;
-        const uint32_t v = idx < n ? data[idx] : 0u;
-        uint32_t inc = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            uint32_t o = __shfl_up(inc, off, 64);
-            if (lane >= off) inc += o;
+        if (idx < n) {
+            const uint64_t key = FIRST ? sort_key(hash, tok_off, tok_bytes, idx) : keys[idx];
+            atomicAdd(&bins[(uint32_t)(key >> shift) & (kBins - 1)], 1u);
         }
-        if (lane == 63) wave_tot[wave] = inc;
-        __syncthreads();
-        uint32_t wave_prefix = 0;
-        for (int w = 0; w < wave; ++w) wave_prefix += wave_tot[w];
-        const uint32_t carry = carry_s;
-        if (idx < n) data[idx] = carry + wave_prefix + inc - v;
-        __syncthreads();
-        if (threadIdx.x == 1023) carry_s = carry + wave_prefix + inc;
-        __syncthreads();
     }
+    __syncthreads();
+    hist[(size_t)blockIdx.x * kBins + threadIdx.x] = bins[threadIdx.x];
 }
 
-// Stable scatter of one pass.  A wave owns a contiguous chunk of the tile and
-// visits it 64 keys at a time, so (wave, visit, lane) order is index order.
-__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
-    const uint64_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in,
-    uint64_t *__restrict__ keys_out, int32_t *__restrict__ vals_out, int n, int shift,
-    const uint32_t *__restrict__ hist_scanned, int nb) {
+struct ScatterArgs {
+    const uint64_t *hash;  // first pass: keys are formed from the hash and the first bytes
+    const int64_t *tok_off;
+    const uint8_t *tok_bytes;
+    const uint64_t *keys_in;  // later passes
+    const int32_t *vals_in;
+    uint64_t *keys_out;
+    int32_t *vals_out;
+    const uint32_t *hist;  // [nb][256] digit counts of this pass per input tile
+    int n, nb, shift;
+};
+
+// One stable pass.  A wave owns a contiguous chunk of the tile and visits it 64 keys at a
+// time, so (wave, visit, lane) order is index order.
+template <bool FIRST>
+__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(ScatterArgs a) {
     __shared__ uint32_t wave_count[kThreads / 64][kBins];
+    __shared__ uint32_t wave_tot[kThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < (kThreads / 64) * kBins; i += kThreads)
         (&wave_count[0][0])[i] = 0;
-    __syncthreads();
+
+    // first output position of this tile's keys with digit d:
+    //   keys with a smaller digit anywhere + keys with digit d in earlier tiles
+    uint32_t bin_base;
+    {
+        const int d = threadIdx.x;
+        uint32_t tot = 0, before = 0;
+        constexpr int kAhead = 16;  // independent loads in flight: the loop is latency-bound
+        for (int t0 = 0; t0 < a.nb; t0 += kAhead) {
+            uint32_t c[kAhead];
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u)
+                c[u] = t0 + u < a.nb ? a.hist[(size_t)(t0 + u) * kBins + d] : 0u;
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                tot += c[u];
+                if (t0 + u < (int)blockIdx.x) before += c[u];
+            }
+        }
+        const int incl = wave_inclusive_sum((int)tot);
+        if (lane == 63) wave_tot[wave] = (uint32_t)incl;
+        __syncthreads();  // also orders the clearing of wave_count before its use
+        uint32_t prefix = 0;
+        for (int w = 0; w < wave; ++w) prefix += wave_tot[w];
+        bin_base = prefix + (uint32_t)incl - tot + before;
+    }
 
     volatile uint32_t *my_count = wave_count[wave];
     const int chunk = blockIdx.x * kTile + wave * (64 * kItems);
@@ -95,9 +138,11 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
         const int idx = chunk + j * 64 + lane;
-        const bool valid = idx < n;
-        key[j] = valid ? keys_in[idx] : 0ull;
-        const uint32_t d = (uint32_t)(key[j] >> shift) & (kBins - 1);
+        const bool valid = idx < a.n;
+        key[j] = !valid ? 0ull
+                 : FIRST ? sort_key(a.hash, a.tok_off, a.tok_bytes, idx)
+                         : a.keys_in[idx];
+        const uint32_t d = (uint32_t)(key[j] >> a.shift) & (kBins - 1);
         uint64_t peers = __ballot(valid);
 #pragma unroll
         for (int bit = 0; bit < kRadixBits; ++bit) {
@@ -115,8 +160,8 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
     }
     __syncthreads();
     {
-        const int d = threadIdx.x;  // kThreads == kBins
-        uint32_t run = hist_scanned[(size_t)d * nb + blockIdx.x];
+        const int d = threadIdx.x;
+        uint32_t run = bin_base;
 #pragma unroll
         for (int w = 0; w < kThreads / 64; ++w) {
             const uint32_t c = wave_count[w][d];
@@ -128,24 +173,24 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(
 #pragma unroll
     for (int j = 0; j < kItems; ++j) {
         const int idx = chunk + j * 64 + lane;
-        if (idx < n) {
-            const uint32_t d = (uint32_t)(key[j] >> shift) & (kBins - 1);
+        if (idx < a.n) {
+            const uint32_t d = (uint32_t)(key[j] >> a.shift) & (kBins - 1);
             const uint32_t pos = wave_count[wave][d] + rank[j];
-            keys_out[pos] = key[j];
-            vals_out[pos] = vals_in ? vals_in[idx] : idx;
+            if (pos >= (uint32_t)a.n) continue;  // cannot happen with consistent counts; stay in bounds
+            a.keys_out[pos] = key[j];
+            a.vals_out[pos] = FIRST ? idx : a.vals_in[idx];
         }
     }
 }
-static_assert(kThreads == kBins, "one thread per bin in the scatter kernel");
 
-// ---------------------------------------------------------------- generic scans over int32
+// ---------------------------------------------------------------- scans over int32
 
 template <bool MAX>
 __device__ __forceinline__ int32_t scan_op(int32_t a, int32_t b) {
     return MAX ? max(a, b) : a + b;
 }
 
-// Phase 1: per-tile totals.
+// Per-tile totals.
 template <bool MAX>
 __global__ __launch_bounds__(kThreads) void scan_reduce_kernel(const int32_t *__restrict__ in, int n,
                                                                int32_t *tile_tot) {
@@ -166,46 +211,23 @@ __global__ __launch_bounds__(kThreads) void scan_reduce_kernel(const int32_t *__
     }
 }
 
-// Phase 2: exclusive scan of the tile totals by one workgroup (values >= 0, identity 0).
-template <bool MAX>
-__global__ __launch_bounds__(1024) void scan_tiles_kernel(int32_t *tile_tot, int nt,
-                                                          int32_t *grand_total) {
-    __shared__ int32_t wave_tot[16];
-    __shared__ int32_t carry_s;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) carry_s = 0;
-    __syncthreads();
-    for (int base = 0; base < nt; base += 1024) {
-        const int idx = base + threadIdx.x;
-        const int32_t v = idx < nt ? tile_tot[idx] : 0;
-        int32_t inc = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int32_t o = __shfl_up(inc, off, 64);
-            if (lane >= off) inc = scan_op<MAX>(inc, o);
-        }
-        if (lane == 63) wave_tot[wave] = inc;
-        __syncthreads();
-        int32_t prefix = carry_s;
-        for (int w = 0; w < wave; ++w) prefix = scan_op<MAX>(prefix, wave_tot[w]);
-        // exclusive value: everything before this element
-        int32_t before = __shfl_up(inc, 1, 64);
-        if (lane == 0) before = 0;
-        if (idx < nt) tile_tot[idx] = scan_op<MAX>(prefix, before);
-        __syncthreads();
-        if (threadIdx.x == 1023) carry_s = scan_op<MAX>(prefix, inc);
-        __syncthreads();
-    }
-    if (threadIdx.x == 0 && grand_total) *grand_total = carry_s;
-}
-
-// Phase 3: scan inside each tile, seeded with the tile's exclusive prefix.
+// Scan inside each tile (values >= 0, identity 0), seeded with the combination of the totals
+// of all earlier tiles, which every workgroup folds for itself.  The last tile also writes
+// the grand total.
 template <bool MAX, bool INCLUSIVE>
 __global__ __launch_bounds__(kThreads) void scan_final_kernel(const int32_t *__restrict__ in, int n,
-                                                              const int32_t *__restrict__ tile_prefix,
-                                                              int32_t *__restrict__ out) {
+                                                              const int32_t *__restrict__ tile_tot,
+                                                              int32_t *__restrict__ out,
+                                                              int32_t *grand_total) {
     __shared__ int32_t wave_tot[kThreads / 64];
+    __shared__ int32_t wave_pre[kThreads / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t tp = 0;
+    for (int t = threadIdx.x; t < (int)blockIdx.x; t += kThreads) tp = scan_op<MAX>(tp, tile_tot[t]);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) tp = scan_op<MAX>(tp, __shfl_xor(tp, off, 64));
+    if (lane == 0) wave_pre[wave] = tp;
+
     const int base = blockIdx.x * kTile + threadIdx.x * kItems;
     int32_t v[kItems];
     int32_t acc = 0;
@@ -222,7 +244,8 @@ __global__ __launch_bounds__(kThreads) void scan_final_kernel(const int32_t *__r
     }
     if (lane == 63) wave_tot[wave] = inc;
     __syncthreads();
-    int32_t prefix = tile_prefix[blockIdx.x];
+    int32_t prefix = 0;
+    for (int w = 0; w < kThreads / 64; ++w) prefix = scan_op<MAX>(prefix, wave_pre[w]);
     for (int w = 0; w < wave; ++w) prefix = scan_op<MAX>(prefix, wave_tot[w]);
     int32_t before = __shfl_up(inc, 1, 64);
     if (lane == 0) before = 0;
@@ -233,6 +256,7 @@ __global__ __launch_bounds__(kThreads) void scan_final_kernel(const int32_t *__r
         if (base + j < n) out[base + j] = INCLUSIVE ? next : run;
         run = next;
     }
+    if (grand_total && blockIdx.x == gridDim.x - 1 && threadIdx.x == kThreads - 1) *grand_total = run;
 }
 
 template <bool MAX, bool INCLUSIVE>
@@ -241,50 +265,113 @@ int device_scan(const int32_t *in, int32_t *out, int n, int32_t *tile_tmp, int32
     const int nt = (int)ceil_div(n, kTile);
     hipLaunchKernelGGL(scan_reduce_kernel<MAX>, dim3(nt), dim3(kThreads), 0, stream, in, n, tile_tmp);
     CFGZIP_TRY(check_launch());
-    hipLaunchKernelGGL(scan_tiles_kernel<MAX>, dim3(1), dim3(1024), 0, stream, tile_tmp, nt,
-                       grand_total);
-    CFGZIP_TRY(check_launch());
     hipLaunchKernelGGL((scan_final_kernel<MAX, INCLUSIVE>), dim3(nt), dim3(kThreads), 0, stream, in,
-                       n, tile_tmp, out);
+                       n, tile_tmp, out, grand_total);
     return check_launch();
 }
 
-// ---------------------------------------------------------------- segments, verification, rounds
+// ---------------------------------------------------------------- segments
 
-struct Counters {
-    int32_t unresolved;
-    int32_t num_classes;
-    int32_t pad[6];
-};
+__device__ __forceinline__ uint64_t hash_part(uint64_t key) { return key >> 8; }
 
-// cand[i] = i if sorted position i starts an equal-hash segment, else 0 (max-scan input);
-// also clears the per-token arrays used later.
-__global__ void segment_start_kernel(const uint64_t *__restrict__ keys, int n, int32_t *cand,
-                                     int32_t *is_head_token, uint64_t *rep_key, int32_t *mismatch) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    cand[i] = (i == 0 || keys[i] != keys[i - 1]) ? i : 0;
-    is_head_token[i] = 0;
-    rep_key[i] = ~0ull;
-    mismatch[i] = 0;
+// seg_head[i] = first sorted position with the same hash bits as position i.  Chain set-up:
+// a segment start is its own head and settled; every other position is compared with its
+// left neighbour.  Also clears the per-position and per-token arrays used later.
+__global__ __launch_bounds__(kThreads) void segments_kernel(
+    const uint64_t *__restrict__ keys, int n, int32_t *seg_head, int32_t *head_pos,
+    int32_t *resolved, int32_t *mismatch, int32_t *min_id, uint64_t *rep_key,
+    int32_t *is_head_token, Counters *ctr) {
+    __shared__ int32_t wave_tot[kThreads / 64];
+    __shared__ int32_t carry_s;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tile0 = blockIdx.x * kTile;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ctr->unresolved = 0;
+        ctr->num_classes = 0;
+    }
+    // where the segment that reaches into this tile starts (64-ary search by the first wave)
+    if (wave == 0) {
+        int lo = tile0;
+        if (tile0 > 0 && hash_part(keys[tile0]) == hash_part(keys[tile0 - 1])) {
+            const uint64_t target = hash_part(keys[tile0]);
+            lo = 0;
+            int hi = tile0 - 1;  // the first position with hash bits >= target lies in [lo, hi]
+            while (hi > lo) {
+                const int step = (hi - lo + 63) / 64;
+                const int x = lo + lane * step;
+                const bool p = x >= hi || hash_part(keys[x]) >= target;
+                const uint64_t m = __ballot(p);
+                if (m == 0ull) {
+                    lo = lo + 63 * step + 1;
+                } else {
+                    const int f = __ffsll((unsigned long long)m) - 1;
+                    const int new_hi = min(hi, lo + f * step);
+                    if (f > 0) lo = lo + (f - 1) * step + 1;
+                    hi = new_hi;
+                }
+            }
+        }
+        if (lane == 0) carry_s = lo;
+    }
+    const int base = tile0 + threadIdx.x * kItems;
+    int32_t v[kItems];
+    int32_t acc = -1;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const int i = base + j;
+        v[j] = -1;
+        if (i < n && (i == 0 || hash_part(keys[i]) != hash_part(keys[i - 1]))) v[j] = i;
+        acc = max(acc, v[j]);
+    }
+    int32_t inc = acc;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int32_t o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc = max(inc, o);
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int32_t run = carry_s;
+    for (int w = 0; w < wave; ++w) run = max(run, wave_tot[w]);
+    int32_t before = __shfl_up(inc, 1, 64);
+    if (lane == 0) before = -1;
+    run = max(run, before);
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+        const int i = base + j;
+        run = max(run, v[j]);
+        if (i < n) {
+            const bool start = v[j] == i;
+            seg_head[i] = run;
+            head_pos[i] = start ? i : i - 1;
+            resolved[i] = start ? 1 : 0;
+            mismatch[i] = 0;
+            min_id[i] = 0x7FFFFFFF;
+            rep_key[i] = ~0ull;
+            is_head_token[i] = 0;
+        }
+    }
 }
 
-// resolved[i] = 1 for segment heads; head_pos starts as the segment head.
-__global__ void init_round0_kernel(const int32_t *__restrict__ seg_head, int n, int32_t *head_pos,
-                                   int32_t *resolved, Counters *ctr) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) ctr->unresolved = 0;
-    if (i >= n) return;
-    head_pos[i] = seg_head[i];
-    resolved[i] = seg_head[i] == i ? 1 : 0;
+// ---------------------------------------------------------------- verification
+
+__device__ __forceinline__ void settle(bool differs, int i, int32_t *resolved, int32_t *mismatch,
+                                       Counters *ctr) {
+    if ((threadIdx.x & 63) != 0) return;
+    if (differs) {
+        mismatch[i] = 1;
+        atomicAdd(&ctr->unresolved, 1);
+    } else {
+        resolved[i] = 1;
+    }
 }
 
-// One wave per sorted position: compares the stored signature rows of the
-// member and of its candidate head.
+// One wave per sorted position: compares the stored signature rows of position i and of
+// position head_pos[i].  Equal: the position is settled; different: it is flagged and counted.
 __global__ __launch_bounds__(kThreads) void verify_stored_kernel(
     const uint16_t *__restrict__ sig, int S, const int32_t *__restrict__ vals,
-    const int32_t *__restrict__ head_pos, const int32_t *__restrict__ resolved, int n,
-    int32_t *mismatch) {
+    const int32_t *__restrict__ head_pos, int32_t *resolved, int n, int32_t *mismatch,
+    Counters *ctr) {
     const int lane = threadIdx.x & 63;
     const int64_t gw = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     const int64_t total = (int64_t)gridDim.x * (kThreads / 64);
@@ -304,31 +391,122 @@ __global__ __launch_bounds__(kThreads) void verify_stored_kernel(
         } else {
             for (int j = lane; j < S; j += 64) diff |= a[j] != b[j];
         }
-        if (__ballot(diff) != 0ull && lane == 0) mismatch[i] = 1;
+        settle(__ballot(diff) != 0ull, (int)i, resolved, mismatch, ctr);
     }
 }
 
-// A workgroup takes 32 consecutive sorted positions at a time.  Every unresolved member and
-// its candidate head are walked with the image walk (walk_device.hpp); the pair is then
-// compared without materialising either signature: directly on w when both byte strings
-// start with the same byte (idx[row] is onto, so sig equal <=> w equal), else through
-// sig[q] = w[idx[row][q]] for every q.
+// Signatures of two walked batch slots, compared without materialising either: directly on w
+// when both byte strings start with the same byte (idx[row] is onto, so sig equal <=> w
+// equal), else through sig[q] = w[idx[row][q]] for every q.  One wave; returns whether any
+// entry differs (wave-uniform).
+__device__ __forceinline__ bool slots_differ(const Batch &B, const Tables &T, int S,
+                                             const uint16_t *w, int sm, int sh) {
+    const int lane = threadIdx.x & 63;
+    const int rm = B.row[sm], rh = B.row[sh];
+    const uint16_t *wm = w + B.wstart[sm], *wh = w + B.wstart[sh];
+    bool diff = false;
+    if (rm == rh) {
+        const int cnt = B.wstart[sm + 1] - B.wstart[sm];
+        for (int j = lane; j < cnt; j += 64) diff |= wm[j] != wh[j];
+    } else if ((S % 8) == 0) {
+        const uint4 *im = reinterpret_cast<const uint4 *>(T.idx + (size_t)rm * S);
+        const uint4 *ih = reinterpret_cast<const uint4 *>(T.idx + (size_t)rh * S);
+        for (int v = lane; v < S / 8; v += 64) {
+            const uint4 x = im[v], y = ih[v];
+            diff |= wm[x.x & 0xFFFFu] != wh[y.x & 0xFFFFu];
+            diff |= wm[x.x >> 16] != wh[y.x >> 16];
+            diff |= wm[x.y & 0xFFFFu] != wh[y.y & 0xFFFFu];
+            diff |= wm[x.y >> 16] != wh[y.y >> 16];
+            diff |= wm[x.z & 0xFFFFu] != wh[y.z & 0xFFFFu];
+            diff |= wm[x.z >> 16] != wh[y.z >> 16];
+            diff |= wm[x.w & 0xFFFFu] != wh[y.w & 0xFFFFu];
+            diff |= wm[x.w >> 16] != wh[y.w >> 16];
+        }
+    } else {
+        const uint16_t *im = T.idx + (size_t)rm * S, *ih = T.idx + (size_t)rh * S;
+        for (int q = lane; q < S; q += 64) diff |= wm[im[q]] != wh[ih[q]];
+    }
+    return __ballot(diff) != 0ull;
+}
+
 constexpr int kMaxLdsWalkEntries = 72 * 1024;  // 144 KB of uint16; beyond that w lives in global memory
 constexpr int kGlobalWalkGrid = 256;
 
+struct RewalkArgs {
+    Tables T;
+    int32_t S, wcap, n;
+    uint16_t *w_global;
+    const uint8_t *tok_bytes;
+    const int64_t *tok_off;
+    const int32_t *vals;
+    const int32_t *head_pos;
+    int32_t *resolved;
+    int32_t *mismatch;
+    Counters *ctr;
+};
+
+// Chain links without stored signatures: a workgroup takes 63 consecutive sorted positions
+// (plus the left neighbour of the first) at a time, walks every token that takes part in a
+// link once, and compares neighbours.  Requires head_pos[i] == i - 1 for every unsettled i.
 template <bool W_GLOBAL>
-__global__ __launch_bounds__(kThreads) void verify_rewalk_kernel(
-    Tables T, int S, int wcap, uint16_t *w_global, const uint8_t *__restrict__ tok_bytes,
-    const int64_t *__restrict__ tok_off, const int32_t *__restrict__ vals,
-    const int32_t *__restrict__ head_pos, const int32_t *__restrict__ resolved, int n,
-    int32_t *mismatch) {
+__global__ __launch_bounds__(kThreads) void verify_chain_rewalk_kernel(RewalkArgs a) {
     extern __shared__ __align__(16) uint16_t dyn_lds[];
     __shared__ Batch B;
     __shared__ uint8_t ldsb[kByteCap];
-    uint16_t *w = W_GLOBAL ? w_global + (size_t)blockIdx.x * wcap : dyn_lds;
+    uint16_t *w = W_GLOBAL ? a.w_global + (size_t)blockIdx.x * a.wcap : dyn_lds;
+    constexpr int kPositions = kBatchTokens - 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = a.n;
+    const int n_chunks = (n + kPositions - 1) / kPositions;
+    for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+        const int i_end = min(n, (chunk + 1) * kPositions);
+        int icur = chunk * kPositions;
+        while (icur < i_end) {  // workgroup-uniform
+            __syncthreads();
+            if (threadIdx.x < 64) {
+                // lane l holds sorted position icur - 1 + l
+                const int i = icur - 1 + lane;
+                const bool in_range = i >= 0 && i < i_end;
+                const bool member = in_range && lane >= 1 && !a.resolved[i];
+                const bool pred = in_range && i + 1 < i_end && lane < 63 && !a.resolved[i + 1];
+                int64_t beg = 0, len = -1;
+                if (member || pred) {
+                    const int32_t tok = a.vals[i];
+                    beg = a.tok_off[tok];
+                    len = a.tok_off[tok + 1] - beg;
+                    if (len < 0) len = 0;
+                }
+                const int k = batch_fill(B, a.T, a.tok_bytes, beg, len, a.wcap, 2, 1);
+                if (lane < k) B.aux[lane] = member ? 1 : 0;
+            }
+            __syncthreads();
+            const int links = min(B.k - 1, i_end - icur);
+            batch_stage_bytes(B, a.tok_bytes, ldsb);
+            __syncthreads();
+            batch_walk<4, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
+            __syncthreads();
+            for (int l = 1 + wave; l <= links; l += kThreads / 64) {
+                if (!B.aux[l]) continue;  // wave-uniform
+                settle(slots_differ(B, a.T, a.S, w, l, l - 1), icur + l - 1, a.resolved, a.mismatch,
+                       a.ctr);
+            }
+            icur += links;
+        }
+    }
+}
+
+// Arbitrary pairs without stored signatures (collision rounds): a workgroup takes 32 sorted
+// positions at a time; every unsettled position i and position head_pos[i] are walked and
+// compared.
+template <bool W_GLOBAL>
+__global__ __launch_bounds__(kThreads) void verify_pairs_rewalk_kernel(RewalkArgs a) {
+    extern __shared__ __align__(16) uint16_t dyn_lds[];
+    __shared__ Batch B;
+    __shared__ uint8_t ldsb[kByteCap];
+    uint16_t *w = W_GLOBAL ? a.w_global + (size_t)blockIdx.x * a.wcap : dyn_lds;
     constexpr int kPairs = kBatchTokens / 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const bool vec = (S % 8) == 0;
+    const int n = a.n;
     const int n_chunks = (n + kPairs - 1) / kPairs;
     for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
         const int i_end = min(n, (chunk + 1) * kPairs);
@@ -336,66 +514,58 @@ __global__ __launch_bounds__(kThreads) void verify_rewalk_kernel(
         while (icur < i_end) {  // workgroup-uniform
             __syncthreads();
             if (threadIdx.x < 64) {
-                // lanes 2p, 2p+1: member and head of sorted position icur + p
+                // lanes 2p, 2p+1: sorted position icur + p and its candidate head
                 const int i = icur + (lane >> 1);
                 int64_t beg = 0, len = -1;
-                if (i < i_end && !resolved[i]) {
-                    const int32_t tok = (lane & 1) ? vals[head_pos[i]] : vals[i];
-                    beg = tok_off[tok];
-                    len = tok_off[tok + 1] - beg;
+                if (i < i_end && !a.resolved[i]) {
+                    const int32_t tok = (lane & 1) ? a.vals[a.head_pos[i]] : a.vals[i];
+                    beg = a.tok_off[tok];
+                    len = a.tok_off[tok + 1] - beg;
                     if (len < 0) len = 0;
                 }
-                const int k = batch_fill(B, T, tok_bytes, beg, len, wcap, 2, 2);
+                const int k = batch_fill(B, a.T, a.tok_bytes, beg, len, a.wcap, 2, 2);
                 if (lane < k) B.aux[lane] = len >= 0 ? 1 : 0;
             }
             __syncthreads();
             const int pairs = min(B.k / 2, i_end - icur);
-            batch_stage_bytes(B, tok_bytes, ldsb);
+            batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            batch_walk<4, false>(T, T.Tt, S, tok_bytes, B, ldsb, w);
+            batch_walk<4, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
             __syncthreads();
             for (int p = wave; p < pairs; p += kThreads / 64) {
                 if (!B.aux[2 * p]) continue;  // wave-uniform
-                const int rm = B.row[2 * p], rh = B.row[2 * p + 1];
-                const uint16_t *wm = w + B.wstart[2 * p], *wh = w + B.wstart[2 * p + 1];
-                bool diff = false;
-                if (rm == rh) {
-                    const int cnt = B.wstart[2 * p + 1] - B.wstart[2 * p];
-                    for (int j = lane; j < cnt; j += 64) diff |= wm[j] != wh[j];
-                } else if (vec) {
-                    const uint4 *im = reinterpret_cast<const uint4 *>(T.idx + (size_t)rm * S);
-                    const uint4 *ih = reinterpret_cast<const uint4 *>(T.idx + (size_t)rh * S);
-                    for (int v = lane; v < S / 8; v += 64) {
-                        const uint4 x = im[v], y = ih[v];
-                        diff |= wm[x.x & 0xFFFFu] != wh[y.x & 0xFFFFu];
-                        diff |= wm[x.x >> 16] != wh[y.x >> 16];
-                        diff |= wm[x.y & 0xFFFFu] != wh[y.y & 0xFFFFu];
-                        diff |= wm[x.y >> 16] != wh[y.y >> 16];
-                        diff |= wm[x.z & 0xFFFFu] != wh[y.z & 0xFFFFu];
-                        diff |= wm[x.z >> 16] != wh[y.z >> 16];
-                        diff |= wm[x.w & 0xFFFFu] != wh[y.w & 0xFFFFu];
-                        diff |= wm[x.w >> 16] != wh[y.w >> 16];
-                    }
-                } else {
-                    const uint16_t *im = T.idx + (size_t)rm * S, *ih = T.idx + (size_t)rh * S;
-                    for (int q = lane; q < S; q += 64) diff |= wm[im[q]] != wh[ih[q]];
-                }
-                if (__ballot(diff) != 0ull && lane == 0) mismatch[icur + p] = 1;
+                settle(slots_differ(B, a.T, a.S, w, 2 * p, 2 * p + 1), icur + p, a.resolved,
+                       a.mismatch, a.ctr);
             }
             icur += pairs;
         }
     }
 }
 
-// Unresolved members whose comparison found no difference join their head's class.
-__global__ void settle_kernel(int n, int32_t *resolved, int32_t *mismatch, Counters *ctr) {
+// ---------------------------------------------------------------- collision rounds (rare)
+
+// cand[i] = i if position i starts a chain (a segment start or a member that differs from
+// its left neighbour), else 0 (max-scan input).
+__global__ void chain_start_kernel(int n, const int32_t *__restrict__ seg_head,
+                                   const int32_t *__restrict__ mismatch, int32_t *cand) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n || resolved[i]) return;
+    if (i < n) cand[i] = (seg_head[i] == i || mismatch[i]) ? i : 0;
+}
+
+// Only chain starts take part in the rounds: the ones that are not segment starts are
+// unsettled and first compared with their segment's start.
+__global__ void rounds_init_kernel(int n, const int32_t *__restrict__ seg_head,
+                                   const int32_t *__restrict__ mismatch, int32_t *head_pos,
+                                   int32_t *resolved, Counters *ctr) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) ctr->unresolved = 0;
+    if (i >= n) return;
     if (mismatch[i]) {
-        mismatch[i] = 0;
-        atomicAdd(&ctr->unresolved, 1);
+        resolved[i] = 0;
+        head_pos[i] = seg_head[i];
     } else {
         resolved[i] = 1;
+        if (seg_head[i] == i) head_pos[i] = i;
     }
 }
 
@@ -417,59 +587,84 @@ __global__ void round_assign_kernel(int n, int32_t *resolved, const int32_t *__r
     if (i >= n || resolved[i]) return;
     const int32_t h = next_head[seg_head[i]];
     head_pos[i] = h;
-    if (h == i) resolved[i] = 1;  // first unresolved member of its segment: a new class head
+    if (h == i) resolved[i] = 1;  // first unsettled chain start of its segment: a new class
+}
+
+// anchor[i] = sorted position that stands for the class of position i: the class of its
+// chain start.  Also clears what the numbering kernels accumulate into.
+__global__ void anchors_kernel(int n, const int32_t *__restrict__ chain_start,
+                               const int32_t *__restrict__ head_pos, int32_t *anchor,
+                               int32_t *min_id, uint64_t *rep_key, int32_t *is_head_token) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    anchor[i] = head_pos[chain_start[i]];
+    min_id[i] = 0x7FFFFFFF;
+    rep_key[i] = ~0ull;
+    is_head_token[i] = 0;
 }
 
 // ---------------------------------------------------------------- numbering and representatives
 
-__global__ void mark_heads_kernel(int n, const int32_t *__restrict__ head_pos,
-                                  const int32_t *__restrict__ vals, int32_t *is_head_token) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n && head_pos[i] == i) is_head_token[vals[i]] = 1;
-}
-
-// Sorted neighbours mostly share a class, so a wave first reduces (length, id) over its lanes
-// of equal class and issues one atomic per distinct class instead of one per token.
-__global__ __launch_bounds__(kThreads) void assign_classes_kernel(
-    int n, const int32_t *__restrict__ head_pos, const int32_t *__restrict__ vals,
-    const int32_t *__restrict__ id_of_head_token, const int64_t *__restrict__ tok_off,
-    int32_t *class_of_token, uint64_t *rep_key) {
+// Per class (keyed by its anchor position): smallest token id and smallest (length, id).
+// Sorted neighbours mostly share a class, so a wave first reduces over its lanes of equal
+// anchor and issues one pair of atomics per distinct anchor.
+__global__ __launch_bounds__(kThreads) void class_minima_kernel(
+    int n, const int32_t *__restrict__ anchor, const int32_t *__restrict__ vals,
+    const int64_t *__restrict__ tok_off, int32_t *min_id, uint64_t *rep_key) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const bool valid = i < n;
-    int32_t k = -1;
+    int32_t a = -1;
     uint64_t packed = ~0ull;
     if (valid) {
         const int32_t tok = vals[i];
-        k = id_of_head_token[vals[head_pos[i]]];
-        class_of_token[tok] = k;
+        a = anchor[i];
         int64_t len = tok_off[tok + 1] - tok_off[tok];
         if (len > 0x7FFFFFFF) len = 0x7FFFFFFF;
+        if (len < 0) len = 0;
         packed = ((uint64_t)len << 32) | (uint32_t)tok;
     }
     uint64_t todo = __ballot(valid);
     const int lane = threadIdx.x & 63;
     while (todo) {
         const int leader = __ffsll((unsigned long long)todo) - 1;
-        const int32_t k0 = __shfl(k, leader, 64);
-        const bool mine = valid && k == k0;
+        const int32_t a0 = __shfl(a, leader, 64);
+        const bool mine = valid && a == a0;
         uint64_t m = mine ? packed : ~0ull;
+        int32_t id = mine ? (int32_t)(packed & 0x7FFFFFFFull) : 0x7FFFFFFF;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const uint64_t o = __shfl_xor(m, off, 64);
             m = o < m ? o : m;
+            id = min(id, __shfl_xor(id, off, 64));
         }
-        if (lane == leader)
-            atomicMin(reinterpret_cast<unsigned long long *>(rep_key + k0), (unsigned long long)m);
+        if (lane == leader) {
+            atomicMin(reinterpret_cast<unsigned long long *>(rep_key + a0), (unsigned long long)m);
+            atomicMin(min_id + a0, id);
+        }
         todo &= ~__ballot(mine);
     }
 }
 
-__global__ void write_reps_kernel(int n, const uint64_t *__restrict__ rep_key, const Counters *ctr,
-                                  int32_t *rep_of_class, int32_t *num_classes_dev) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    const int C = ctr->num_classes;
-    if (k == 0 && num_classes_dev) *num_classes_dev = C;
-    if (k < n && k < C) rep_of_class[k] = (int32_t)(rep_key[k] & 0xFFFFFFFFull);
+__global__ void mark_heads_kernel(int n, const int32_t *__restrict__ anchor,
+                                  const int32_t *__restrict__ min_id, int32_t *is_head_token) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && anchor[i] == i) is_head_token[min_id[i]] = 1;
+}
+
+__global__ void assign_classes_kernel(int n, const int32_t *__restrict__ anchor,
+                                      const int32_t *__restrict__ vals,
+                                      const int32_t *__restrict__ min_id,
+                                      const int32_t *__restrict__ id_of_head_token,
+                                      const uint64_t *__restrict__ rep_key, const Counters *ctr,
+                                      int32_t *class_of_token, int32_t *rep_of_class,
+                                      int32_t *num_classes_dev) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0 && num_classes_dev) *num_classes_dev = ctr->num_classes;
+    if (i >= n) return;
+    const int32_t a = anchor[i];
+    const int32_t k = id_of_head_token[min_id[a]];
+    class_of_token[vals[i]] = k;
+    if (a == i) rep_of_class[k] = (int32_t)(rep_key[i] & 0xFFFFFFFFull);
 }
 
 struct BuildWorkspace {
@@ -477,8 +672,8 @@ struct BuildWorkspace {
     uint64_t *keys[2];
     int32_t *vals[2];
     uint32_t *hist;
-    int32_t *seg_head, *head_pos, *resolved, *mismatch, *next_head, *cand;
-    int32_t *is_head_token, *id_of_head_token, *tile_tmp;
+    int32_t *seg_head, *head_pos, *resolved, *mismatch, *next_head, *cand, *chain_start, *anchor;
+    int32_t *min_id, *is_head_token, *id_of_head_token, *tile_tmp;
     uint64_t *rep_key;
     uint16_t *verify_w;  // walk vectors of the re-walk verification when they do not fit in LDS
     Counters *ctr;
@@ -502,6 +697,9 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
     w.mismatch = c.take<int32_t>(n);
     w.next_head = c.take<int32_t>(n);
     w.cand = c.take<int32_t>(n);
+    w.chain_start = c.take<int32_t>(n);
+    w.anchor = c.take<int32_t>(n);
+    w.min_id = c.take<int32_t>(n);
     w.is_head_token = c.take<int32_t>(n);
     w.id_of_head_token = c.take<int32_t>(n);
     w.tile_tmp = c.take<int32_t>(nt);
@@ -515,6 +713,24 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
 }
 
 inline dim3 grid_for(int n) { return dim3((unsigned)ceil_div(n, kThreads)); }
+
+template <typename Kern>
+int launch_rewalk(Kern kern_lds, Kern kern_global, const RewalkArgs &a, int n_chunks, int n_cu,
+                  hipStream_t stream) {
+    if (a.wcap > kMaxLdsWalkEntries) {
+        hipLaunchKernelGGL(kern_global, dim3((unsigned)std::min(n_chunks, kGlobalWalkGrid)),
+                           dim3(kThreads), 0, stream, a);
+    } else {
+        const size_t dyn = (size_t)a.wcap * 2;
+        if (dyn > 48 * 1024)
+            CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern_lds),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)dyn)));
+        hipLaunchKernelGGL(kern_lds, dim3((unsigned)std::min(n_chunks, n_cu * 8)), dim3(kThreads),
+                           dyn, stream, a);
+    }
+    return check_launch();
+}
 
 }  // namespace
 }  // namespace cfgzip
@@ -543,39 +759,6 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int n = V;
     const int nb = (int)ceil_div(n, kTile);
-
-    // 1. sort (hash, token id)
-    const uint64_t *kin = hash;
-    const int32_t *vin = nullptr;
-    int cur = 0;
-    for (int shift = 0; shift < 64; shift += kRadixBits) {
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(nb), dim3(kThreads), 0, stream, kin, n, shift,
-                           w.hist, nb);
-        CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(scan_u32_single_block_kernel, dim3(1), dim3(1024), 0, stream, w.hist,
-                           nb * kBins);
-        CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nb), dim3(kThreads), 0, stream, kin, vin,
-                           w.keys[cur], w.vals[cur], n, shift, w.hist, nb);
-        CFGZIP_TRY(check_launch());
-        kin = w.keys[cur];
-        vin = w.vals[cur];
-        cur ^= 1;
-    }
-    const uint64_t *keys = kin;
-    const int32_t *vals = vin;
-
-    // 2. equal-hash segments
-    hipLaunchKernelGGL(segment_start_kernel, grid_for(n), dim3(kThreads), 0, stream, keys, n, w.cand,
-                       w.is_head_token, w.rep_key, w.mismatch);
-    CFGZIP_TRY(check_launch());
-    CFGZIP_TRY((device_scan<true, true>(w.cand, w.seg_head, n, w.tile_tmp, nullptr, stream)));
-    hipLaunchKernelGGL(init_round0_kernel, grid_for(n), dim3(kThreads), 0, stream, w.seg_head, n,
-                       w.head_pos, w.resolved, w.ctr);
-    CFGZIP_TRY(check_launch());
-
-    Tables T{};
-    if (!sig) CFGZIP_TRY(prepare_tables(table, S, 0, false, w.sig_ws, &T, stream));
     int n_cu = 256;
     {
         int dev = 0;
@@ -584,81 +767,138 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
             hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)));
         if (n_cu <= 0) n_cu = 256;
     }
-    auto verify = [&]() -> int {
+
+    // without stored signatures the comparisons re-walk: tables first (independent of the sort)
+    RewalkArgs ra{};
+    if (!sig) {
+        CFGZIP_TRY(prepare_tables(table, S, 0, false, w.sig_ws, &ra.T, stream));
+        ra.S = S;
+        ra.wcap = walk_cap_for(S);
+        ra.n = n;
+        ra.w_global = w.verify_w;
+        ra.tok_bytes = tok_bytes;
+        ra.tok_off = tok_off;
+        ra.resolved = w.resolved;
+        ra.mismatch = w.mismatch;
+        ra.ctr = w.ctr;
+    }
+
+    // 1. sort (hash bits, first byte) with the token id as value
+    int cur = 0;
+    for (int pass = 0; pass < kPasses; ++pass) {
+        ScatterArgs sa{};
+        sa.hash = hash;
+        sa.tok_off = tok_off;
+        sa.tok_bytes = tok_bytes;
+        sa.keys_in = pass ? w.keys[cur ^ 1] : nullptr;
+        sa.vals_in = pass ? w.vals[cur ^ 1] : nullptr;
+        sa.keys_out = w.keys[cur];
+        sa.vals_out = w.vals[cur];
+        sa.hist = w.hist;
+        sa.n = n;
+        sa.nb = nb;
+        sa.shift = pass * kRadixBits;
+        if (pass == 0) {
+            hipLaunchKernelGGL(radix_hist_kernel<true>, dim3(nb), dim3(kThreads), 0, stream, hash,
+                               tok_off, tok_bytes, nullptr, n, sa.shift, w.hist);
+            CFGZIP_TRY(check_launch());
+            hipLaunchKernelGGL(radix_scatter_kernel<true>, dim3(nb), dim3(kThreads), 0, stream, sa);
+        } else {
+            hipLaunchKernelGGL(radix_hist_kernel<false>, dim3(nb), dim3(kThreads), 0, stream, hash,
+                               tok_off, tok_bytes, sa.keys_in, n, sa.shift, w.hist);
+            CFGZIP_TRY(check_launch());
+            hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(nb), dim3(kThreads), 0, stream, sa);
+        }
+        CFGZIP_TRY(check_launch());
+        cur ^= 1;
+    }
+    const uint64_t *keys = w.keys[cur ^ 1];
+    const int32_t *vals = w.vals[cur ^ 1];
+    ra.vals = vals;
+    ra.head_pos = w.head_pos;
+
+    // 2. equal-hash segments, chain set-up
+    hipLaunchKernelGGL(segments_kernel, dim3(nb), dim3(kThreads), 0, stream, keys, n, w.seg_head,
+                       w.head_pos, w.resolved, w.mismatch, w.min_id, w.rep_key, w.is_head_token,
+                       w.ctr);
+    CFGZIP_TRY(check_launch());
+
+    auto verify_pairs = [&]() -> int {
         if (sig) {
             const int64_t waves = std::min<int64_t>(n, (int64_t)n_cu * 32);
             hipLaunchKernelGGL(verify_stored_kernel, dim3((unsigned)ceil_div(waves, kThreads / 64)),
                                dim3(kThreads), 0, stream, sig, S, vals, w.head_pos, w.resolved, n,
-                               w.mismatch);
-        } else {
-            const int wcap = walk_cap_for(S);
-            const int n_chunks = (int)ceil_div(n, kBatchTokens / 2);
-            if (wcap > kMaxLdsWalkEntries) {
-                hipLaunchKernelGGL(verify_rewalk_kernel<true>,
-                                   dim3((unsigned)std::min(n_chunks, kGlobalWalkGrid)),
-                                   dim3(kThreads), 0, stream, T, S, wcap, w.verify_w, tok_bytes,
-                                   tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
-            } else {
-                const size_t dyn = (size_t)wcap * 2;
-                auto kern = verify_rewalk_kernel<false>;
-                if (dyn > 48 * 1024)
-                    CFGZIP_TRY(check_hip(hipFuncSetAttribute(
-                        reinterpret_cast<const void *>(kern),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn)));
-                hipLaunchKernelGGL(kern, dim3((unsigned)std::min(n_chunks, n_cu * 8)),
-                                   dim3(kThreads), dyn, stream, T, S, wcap, nullptr, tok_bytes,
-                                   tok_off, vals, w.head_pos, w.resolved, n, w.mismatch);
-            }
+                               w.mismatch, w.ctr);
+            return check_launch();
         }
+        return launch_rewalk(verify_pairs_rewalk_kernel<false>, verify_pairs_rewalk_kernel<true>, ra,
+                             (int)ceil_div(n, kBatchTokens / 2), n_cu, stream);
+    };
+    // 4./5. class ids by ascending smallest member id, representatives
+    auto number_classes = [&](const int32_t *anchor) -> int {
+        hipLaunchKernelGGL(class_minima_kernel, grid_for(n), dim3(kThreads), 0, stream, n, anchor,
+                           vals, tok_off, w.min_id, w.rep_key);
         CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(settle_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.resolved,
-                           w.mismatch, w.ctr);
+        hipLaunchKernelGGL(mark_heads_kernel, grid_for(n), dim3(kThreads), 0, stream, n, anchor,
+                           w.min_id, w.is_head_token);
+        CFGZIP_TRY(check_launch());
+        CFGZIP_TRY((device_scan<false, false>(w.is_head_token, w.id_of_head_token, n, w.tile_tmp,
+                                              &w.ctr->num_classes, stream)));
+        hipLaunchKernelGGL(assign_classes_kernel, grid_for(n), dim3(kThreads), 0, stream, n, anchor,
+                           vals, w.min_id, w.id_of_head_token, w.rep_key, w.ctr, class_of_token,
+                           rep_of_class, num_classes_dev);
         return check_launch();
     };
-    auto read_unresolved = [&](int32_t *out) -> int {
-        CFGZIP_TRY(check_hip(hipMemcpyAsync(out, &w.ctr->unresolved, sizeof(int32_t),
+    Counters host_ctr{};
+    auto read_counters = [&]() -> int {
+        CFGZIP_TRY(check_hip(hipMemcpyAsync(&host_ctr, w.ctr, sizeof(Counters),
                                             hipMemcpyDeviceToHost, stream)));
         return check_hip(hipStreamSynchronize(stream));
     };
 
-    // 3. compare with segment heads; split off colliding members in rounds
-    CFGZIP_TRY(verify());
-    int32_t unresolved = 0;
-    CFGZIP_TRY(read_unresolved(&unresolved));
-    const int32_t collisions = unresolved;
-    int64_t rounds = 0;
-    while (unresolved > 0) {
-        if (++rounds > (int64_t)V) return CFGZIP_E_COLLISION;  // cannot happen: a round settles >= 1
-        hipLaunchKernelGGL(round_reset_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.next_head,
-                           w.ctr);
-        CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(round_propose_kernel, grid_for(n), dim3(kThreads), 0, stream, n,
-                           w.resolved, w.seg_head, w.next_head);
-        CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(round_assign_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.resolved,
-                           w.seg_head, w.next_head, w.head_pos);
-        CFGZIP_TRY(check_launch());
-        CFGZIP_TRY(verify());
-        CFGZIP_TRY(read_unresolved(&unresolved));
-    }
+    // 3. chain links; the numbering is enqueued right behind them on the assumption that no
+    //    link differs (then the segments are the classes), and redone in the rare other case
+    if (sig)
+        CFGZIP_TRY(verify_pairs());  // head_pos[i] == i - 1: neighbouring rows
+    else
+        CFGZIP_TRY(launch_rewalk(verify_chain_rewalk_kernel<false>, verify_chain_rewalk_kernel<true>,
+                                 ra, (int)ceil_div(n, kBatchTokens - 1), n_cu, stream));
+    CFGZIP_TRY(number_classes(w.seg_head));
+    CFGZIP_TRY(read_counters());
+    const int32_t collisions = host_ctr.unresolved;
 
-    // 4. class ids by ascending head token id; 5. representatives
-    hipLaunchKernelGGL(mark_heads_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.head_pos, vals,
-                       w.is_head_token);
-    CFGZIP_TRY(check_launch());
-    CFGZIP_TRY((device_scan<false, false>(w.is_head_token, w.id_of_head_token, n, w.tile_tmp,
-                                          &w.ctr->num_classes, stream)));
-    hipLaunchKernelGGL(assign_classes_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.head_pos,
-                       vals, w.id_of_head_token, tok_off, class_of_token, w.rep_key);
-    CFGZIP_TRY(check_launch());
-    hipLaunchKernelGGL(write_reps_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.rep_key, w.ctr,
-                       rep_of_class, num_classes_dev);
-    CFGZIP_TRY(check_launch());
-    int32_t C = 0;
-    CFGZIP_TRY(check_hip(hipMemcpyAsync(&C, &w.ctr->num_classes, sizeof(int32_t),
-                                        hipMemcpyDeviceToHost, stream)));
-    CFGZIP_TRY(check_hip(hipStreamSynchronize(stream)));
-    if (num_classes_host) *num_classes_host = C;
+    if (collisions > 0) {
+        hipLaunchKernelGGL(chain_start_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.seg_head,
+                           w.mismatch, w.cand);
+        CFGZIP_TRY(check_launch());
+        CFGZIP_TRY((device_scan<true, true>(w.cand, w.chain_start, n, w.tile_tmp, nullptr, stream)));
+        hipLaunchKernelGGL(rounds_init_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.seg_head,
+                           w.mismatch, w.head_pos, w.resolved, w.ctr);
+        CFGZIP_TRY(check_launch());
+        CFGZIP_TRY(verify_pairs());
+        CFGZIP_TRY(read_counters());
+        int64_t rounds = 0;
+        while (host_ctr.unresolved > 0) {
+            if (++rounds > (int64_t)V) return CFGZIP_E_COLLISION;  // cannot happen: a round settles >= 1
+            hipLaunchKernelGGL(round_reset_kernel, grid_for(n), dim3(kThreads), 0, stream, n,
+                               w.next_head, w.ctr);
+            CFGZIP_TRY(check_launch());
+            hipLaunchKernelGGL(round_propose_kernel, grid_for(n), dim3(kThreads), 0, stream, n,
+                               w.resolved, w.seg_head, w.next_head);
+            CFGZIP_TRY(check_launch());
+            hipLaunchKernelGGL(round_assign_kernel, grid_for(n), dim3(kThreads), 0, stream, n,
+                               w.resolved, w.seg_head, w.next_head, w.head_pos);
+            CFGZIP_TRY(check_launch());
+            CFGZIP_TRY(verify_pairs());
+            CFGZIP_TRY(read_counters());
+        }
+        hipLaunchKernelGGL(anchors_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.chain_start,
+                           w.head_pos, w.anchor, w.min_id, w.rep_key, w.is_head_token);
+        CFGZIP_TRY(check_launch());
+        CFGZIP_TRY(number_classes(w.anchor));
+        CFGZIP_TRY(read_counters());
+    }
+    if (num_classes_host) *num_classes_host = host_ctr.num_classes;
     if (collisions_host) *collisions_host = collisions;
     return CFGZIP_OK;
 }
