@@ -2,7 +2,7 @@
 // and pick representatives (paper Section 3.1 "Pre-Computation").
 //
 // Pipeline (all on the device):
-//   1. stable LSD radix sort of the 48-bit key (low 40 bits of the hash, first
+//   1. stable LSD radix sort of the 40-bit key (low 32 bits of the hash, first
 //      byte of the token) with the token id as value, 8 bits per pass, two
 //      kernels per pass: per-tile digit counts, then a scatter that ranks its
 //      tile and adds over the counts of the earlier tiles itself;
@@ -35,9 +35,9 @@ constexpr int kItems = 8;
 constexpr int kTile = kThreads * kItems;  // keys per workgroup in sort and scan kernels
 constexpr int kRadixBits = 8;
 constexpr int kBins = 1 << kRadixBits;
-constexpr int kHashBits = 40;                   // hash bits that take part in the sort
+constexpr int kHashBits = 32;                   // hash bits that take part in the sort
 constexpr int kKeyBits = kHashBits + 8;         // + first byte
-constexpr int kPasses = kKeyBits / kRadixBits;  // 6
+constexpr int kPasses = kKeyBits / kRadixBits;  // 5
 constexpr uint64_t kHashMask = (1ull << kHashBits) - 1ull;
 static_assert(kThreads == kBins, "one thread per bin in the sort kernels");
 
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(kThreads) void verify_chain_rewalk_kernel(RewalkArg
             const int links = min(B.k - 1, i_end - icur);
             batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            batch_walk<4, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
+            batch_walk<2, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
             __syncthreads();
             for (int l = 1 + wave; l <= links; l += kThreads / 64) {
                 if (!B.aux[l]) continue;  // wave-uniform
@@ -530,7 +530,7 @@ __global__ __launch_bounds__(kThreads) void verify_pairs_rewalk_kernel(RewalkArg
             const int pairs = min(B.k / 2, i_end - icur);
             batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            batch_walk<4, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
+            batch_walk<2, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
             __syncthreads();
             for (int p = wave; p < pairs; p += kThreads / 64) {
                 if (!B.aux[2 * p]) continue;  // wave-uniform
@@ -726,8 +726,7 @@ int launch_rewalk(Kern kern_lds, Kern kern_global, const RewalkArgs &a, int n_ch
             CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern_lds),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      (int)dyn)));
-        hipLaunchKernelGGL(kern_lds, dim3((unsigned)std::min(n_chunks, n_cu * 8)), dim3(kThreads),
-                           dyn, stream, a);
+        hipLaunchKernelGGL(kern_lds, dim3((unsigned)n_chunks), dim3(kThreads), dyn, stream, a);
     }
     return check_launch();
 }

@@ -30,10 +30,15 @@ struct WalkArgs {
     uint64_t *hash_out;  // [V] or null
 };
 
-// Tt[b][q] = table[q][b]
+// Tt[b][q] = table[q][b]; the workgroups of the last grid row clear the padding behind Tt.
 __global__ __launch_bounds__(256) void transpose_table_kernel(const uint16_t *__restrict__ table,
                                                               uint16_t *__restrict__ Tt, int S) {
     __shared__ uint16_t tile[64][65];
+    if (blockIdx.y == 4) {
+        uint16_t *pad = Tt + (size_t)256 * S;
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < kTablePad; i += gridDim.x * 256) pad[i] = 0;
+        return;
+    }
     const int q0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 x 4
     for (int r = ty; r < 64; r += 4) {
@@ -45,11 +50,6 @@ __global__ __launch_bounds__(256) void transpose_table_kernel(const uint16_t *__
         const int q = q0 + tx;
         if (q < S) Tt[(size_t)(b0 + r) * S + q] = tile[tx][r];
     }
-}
-
-__global__ void fill_pad_kernel(uint16_t *Tt_pad, int n_pad) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_pad) Tt_pad[i] = 0;
 }
 
 constexpr int kStateWords = 65536 / 32;  // presence bitmap over every uint16 value
@@ -160,8 +160,8 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
             const int k = (int)min((int64_t)B.k, t_end - tcur);
             batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            if (a.hash_out) batch_walk<4, true>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
-            else batch_walk<4, false>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
+            if (a.hash_out) batch_walk<2, true>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
+            else batch_walk<2, false>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
             __syncthreads();
             if (a.hash_out && (int)threadIdx.x < k) a.hash_out[tcur + threadIdx.x] = B.hash[threadIdx.x];
             if (a.sig_out) {
@@ -232,11 +232,8 @@ SigWorkspace carve_sig_ws(void *ws, int32_t S) {
 int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, void *ws,
                    Tables *out, hipStream_t stream) {
     SigWorkspace w = carve_sig_ws(ws, S);
-    hipLaunchKernelGGL(transpose_table_kernel, dim3((S + 63) / 64, 4), dim3(256), 0, stream, table,
+    hipLaunchKernelGGL(transpose_table_kernel, dim3((S + 63) / 64, 5), dim3(256), 0, stream, table,
                        w.Tt, S);
-    CFGZIP_TRY(check_launch());
-    hipLaunchKernelGGL(fill_pad_kernel, dim3((kTablePad + 255) / 256), dim3(256), 0, stream,
-                       w.Tt + (size_t)256 * S, kTablePad);
     CFGZIP_TRY(check_launch());
     hipLaunchKernelGGL(image_tables_kernel, dim3(kImageRows), dim3(1024), 0, stream, w.Tt, S,
                        hash_seed, w.nimg, w.img, w.idx, want_wsum ? w.wsum : nullptr);
@@ -306,7 +303,9 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
             CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      (int)dyn)));
-        const int64_t grid = std::min<int64_t>(n_chunks, (int64_t)n_cu * 8);
+        // one workgroup per chunk: the hardware hands out chunks as workgroups retire, which
+        // balances chunks of very different cost
+        const int64_t grid = std::min<int64_t>(n_chunks, 0x7FFFFFFF);
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), dyn, stream, a);
     }
     return check_launch();

@@ -152,54 +152,62 @@ __device__ __forceinline__ void batch_stage_bytes(const Batch &B, const uint8_t 
 }
 
 // Walks every (slot, image state) pair of the batch: w[wstart[m] + j] = state reached from
-// img[row][j] on bytes 1.. of slot m.  U walks are in flight per thread.  With HASH, also
+// img[row][j] on bytes 1.. of slot m.  The walk is a chain of dependent table reads, so a
+// thread keeps U independent walks in flight, fetches the next byte while the current table
+// read is outstanding, and loads the hash weight before the walk starts.  With HASH, also
 // accumulates B.hash[m] += wsum[row][j] * w (order-free).
 template <int U, bool LDS_BYTES, bool HASH>
 __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t *tab, int S,
                                                 const uint8_t *__restrict__ tok_bytes, Batch &B,
                                                 const uint8_t *ldsb, uint16_t *w) {
-    const int nt = blockDim.x, k = B.k, wtotal = B.wtotal;
-    for (int i0 = threadIdx.x; i0 < wtotal; i0 += nt * U) {
-        uint32_t cur[U];
-        int rem[U], slot[U], j[U];
-        int64_t src[U];  // index of byte 1 in ldsb or tok_bytes
-        int maxrem = 0;
+    // every table index fits 32 bits: 257 rows of at most 65536 entries
+    const uint32_t nt = blockDim.x, k = B.k, wtotal = B.wtotal, Su = (uint32_t)S;
+    for (uint32_t i0 = threadIdx.x; i0 < wtotal; i0 += nt * U) {
+        uint32_t cur[U], nextb[U], rem[U], slot[U], src[U];
+        uint64_t weight[U];
+        const uint8_t *gbytes[U];  // !LDS_BYTES (over-long tokens, walked one at a time)
+        uint32_t maxrem = 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * nt;
+            const uint32_t i = i0 + u * nt;
             rem[u] = 0;
             cur[u] = 0;
             slot[u] = 0;
-            j[u] = 0;
             src[u] = 0;
+            nextb[u] = 0;
+            weight[u] = 0;
+            gbytes[u] = tok_bytes;
             if (i < wtotal) {
-                const int m = batch_find(B.wstart, k, i);
+                const uint32_t m = (uint32_t)batch_find(B.wstart, (int)k, (int)i);
+                const uint32_t e = (uint32_t)B.row[m] * Su + (i - (uint32_t)B.wstart[m]);
                 slot[u] = m;
-                j[u] = i - B.wstart[m];
-                cur[u] = T.img[(size_t)B.row[m] * S + j[u]];
-                rem[u] = B.len[m] > 0 ? B.len[m] - 1 : 0;
-                src[u] = (LDS_BYTES ? (int64_t)B.boff[m] : B.beg[m]) + 1;
+                cur[u] = T.img[e];
+                if (HASH) weight[u] = T.wsum[e];
+                rem[u] = B.len[m] > 0 ? (uint32_t)B.len[m] - 1u : 0u;
+                src[u] = (LDS_BYTES ? (uint32_t)B.boff[m] : 0u) + 1u;  // index of byte 1
+                if (!LDS_BYTES) gbytes[u] = tok_bytes + B.beg[m];
+                if (rem[u] > 0) nextb[u] = LDS_BYTES ? ldsb[src[u]] : gbytes[u][src[u]];
                 maxrem = max(maxrem, rem[u]);
             }
         }
-        for (int p = 0; p < maxrem; ++p) {
+        for (uint32_t p = 0; p < maxrem; ++p) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (p < rem[u]) {
-                    const uint32_t b = LDS_BYTES ? ldsb[(int)src[u] + p] : tok_bytes[src[u] + p];
-                    cur[u] = tab[(size_t)b * S + cur[u]];
+                    const uint32_t b = nextb[u];
+                    if (p + 1 < rem[u])
+                        nextb[u] = LDS_BYTES ? ldsb[src[u] + p + 1] : gbytes[u][(size_t)src[u] + p + 1];
+                    cur[u] = tab[b * Su + cur[u]];
                 }
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * nt;
+            const uint32_t i = i0 + u * nt;
             if (i < wtotal) {
                 w[i] = (uint16_t)cur[u];
                 if (HASH)
-                    atomicAdd(&B.hash[slot[u]],
-                              (unsigned long long)(T.wsum[(size_t)B.row[slot[u]] * S + j[u]] *
-                                                   (uint64_t)cur[u]));
+                    atomicAdd(&B.hash[slot[u]], (unsigned long long)(weight[u] * (uint64_t)cur[u]));
             }
         }
     }
@@ -210,7 +218,7 @@ __device__ __forceinline__ void batch_walk(const Tables &T, const uint16_t *tab,
                                            const uint8_t *__restrict__ tok_bytes, Batch &B,
                                            const uint8_t *ldsb, uint16_t *w) {
     if (B.bytes_in_lds) batch_walk_impl<U, true, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
-    else batch_walk_impl<U, false, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
+    else batch_walk_impl<1, false, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
 }
 
 }  // namespace cfgzip
