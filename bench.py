@@ -30,6 +30,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E peak
 N_LOGIT_BUFFERS = 8    # 8 x 65.7 MB = 525 MB > 256 MB memory-side cache
+# HBM bytes per launch of the mask kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE scaled by a plain copy of known size (profiles/mask_kernel_config5_hbm_counters.md);
+# set to None whenever mask.hip changes until the counters are taken again
+MASK_KERNEL_TRAFFIC_BYTES = 141_630_000
 
 
 def log(msg: str) -> None:
@@ -100,12 +104,21 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
         C = res["out"][2]
         sum_len = int(vocab.tok_off[-1])
         ms_sig, ms_all = min(t_sig), min(t_all)
+        # table reads: a plain walk from every state does S reads per token byte; the image walk
+        # does one read per distinct state of the first byte's column and remaining byte
+        # (input statistics only, computed here for the report)
+        nimg = np.array([np.unique(table[:, b]).size for b in range(256)] + [S], dtype=np.int64)
+        lens = np.diff(vocab.tok_off)
+        first = np.where(lens > 0, vocab.tok_bytes[np.minimum(vocab.tok_off[:-1], max(sum_len - 1, 0))], 256)
+        reads_done = int((nimg[first] * np.maximum(lens - 1, 0)).sum())
         out[f"config{idx}"] = {
             "V": V, "S": S, "C": C, "V_over_C": round(V / C, 2), "sig_stored": stored,
             "ms_signatures": round(ms_sig, 4), "ms_build_total": round(ms_all, 4),
             "walks_per_s": V * S / (ms_all * 1e-3),
             "walks_per_s_signatures_only": V * S / (ms_sig * 1e-3),
-            "lookups_per_s_signatures_only": S * sum_len / (ms_sig * 1e-3),
+            "table_reads_plain_walk": S * sum_len,
+            "table_reads_image_walk": reads_done,
+            "sig_store_GBps": round(2 * V * S / (ms_sig * 1e-3) / 1e9, 1) if stored else None,
         }
         log(f"class build config {idx}: V={V} S={S} C={C} signatures {ms_sig:.3f} ms, "
             f"total {ms_all:.3f} ms, {V * S / (ms_all * 1e-3):.3e} walks/s")
@@ -284,7 +297,7 @@ def main() -> int:
                                % (args.p_allowed, N_LOGIT_BUFFERS),
                    "B": B, "V": V, "C": C, "bytes_per_step": nbytes["step"]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MASK_KERNEL_TRAFFIC_BYTES,
                      "kernel": "mask_kernel<bf16, class bits, token bits out, 16-byte accesses>",
                      "bytes_per_launch": nbytes["mask_kernel"],
                      "us_per_launch": round(mask_ms * 1e3, 3),
