@@ -94,7 +94,8 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
 
         def run_build():
             res["out"] = lib_mod.cfgzip_build_classes(tb, to, tt, sig, h, class_of_token=c,
-                                                      rep_of_class=r, workspace=ws_bld)
+                                                      rep_of_class=r, workspace=ws_bld,
+                                                      signatures_workspace=ws_sig)
 
         run_sig(); run_build(); torch.cuda.synchronize()  # warm-up
         t_sig, t_all = [], []

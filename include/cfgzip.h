@@ -87,7 +87,11 @@ int cfgzip_version(void);
  *   S          1 .. 65536
  *   sig_out    uint16 [V][S] or NULL (NULL: signatures are hashed on the fly, never stored)
  *   hash_out   uint64 [V]   or NULL (at least one of sig_out / hash_out must be given)
- *   ws         cfgzip_signatures_workspace_bytes(V, S) bytes, 256-byte aligned
+ *   ws         cfgzip_signatures_workspace_bytes(V, S) bytes, 256-byte aligned.  After the call
+ *              it holds, besides tables, the compressed form in which the signatures were
+ *              computed (per token the states reached from the distinct states its first
+ *              byte leaves; up to 512 bytes per token).  Handing the untouched workspace
+ *              to cfgzip_build_classes lets it compare those instead of walking again.
  */
 size_t cfgzip_signatures_workspace_bytes(int32_t V, int32_t S);
 int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
@@ -108,12 +112,17 @@ int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t 
  * hash collision) start a chain of their own and the chains of a segment are
  * matched against each other in further rounds, so the result is exact for any
  * `hash` that is a function of the signature (equal signatures must carry equal
- * hashes).  With sig == NULL signatures are recomputed from the automaton for
- * the comparison instead of being read.
+ * hashes).  The comparison reads, in order of preference: the compressed
+ * signatures in `signatures_ws`; the rows of `sig`; or, with neither, signatures
+ * recomputed from the automaton.
  *
  *   tok_bytes, tok_off, V, table, S   as for cfgzip_signatures
  *   sig        uint16 [V][S] from cfgzip_signatures, or NULL
  *   hash       uint64 [V]    from cfgzip_signatures (or any function of the signature)
+ *   signatures_ws  the workspace of a finished cfgzip_signatures call with the same
+ *              vocabulary, table, V and S, not written to since, or NULL.  It is only read.
+ *              If it turns out not to hold that call's data (other V or S, or its
+ *              compressed signatures did not fit) the next source is used.
  *   class_of_token   out, int32 [V]
  *   rep_of_class     out, int32 [V] capacity; the first C entries are written
  *   num_classes_dev  out, int32 [1] device, or NULL
@@ -127,7 +136,7 @@ int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t 
 size_t cfgzip_build_classes_workspace_bytes(int32_t V, int32_t S);
 int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                          const uint16_t *table, int32_t S,
-                         const uint16_t *sig, const uint64_t *hash,
+                         const uint16_t *sig, const uint64_t *hash, void *signatures_ws,
                          int32_t *class_of_token, int32_t *rep_of_class,
                          int32_t *num_classes_dev, int32_t *num_classes_host,
                          int32_t *collisions_host,

@@ -64,7 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_build_classes_workspace_bytes.restype = sz
     lib.cfgzip_build_classes_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_build_classes.restype = ctypes.c_int
-    lib.cfgzip_build_classes.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cfgzip_build_classes.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cfgzip_expand_mask.restype = ctypes.c_int
     lib.cfgzip_expand_mask.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.cfgzip_apply_mask.restype = ctypes.c_int
@@ -143,9 +143,12 @@ def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: 
                          sig: Optional[torch.Tensor], hash: torch.Tensor, *,
                          class_of_token: Optional[torch.Tensor] = None,
                          rep_of_class: Optional[torch.Tensor] = None,
-                         workspace: Optional[torch.Tensor] = None, stream=None):
+                         workspace: Optional[torch.Tensor] = None,
+                         signatures_workspace: Optional[torch.Tensor] = None, stream=None):
     """Returns (class_of_token int32 [V], rep_of_class int32 [C] (a view of the first C
-    entries), C, collisions)."""
+    entries), C, collisions).  `signatures_workspace` is the untouched workspace tensor of the
+    cfgzip_signatures call that produced `hash` (its compressed signatures are compared
+    instead of `sig` rows or a second walk)."""
     lib = load_library()
     V = tok_off.numel() - 1
     S = table.shape[0]
@@ -165,6 +168,8 @@ def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: 
         _dev(table, torch.uint16, "table"), S,
         _dev(sig, torch.uint16, "sig") if sig is not None else None,
         _dev(hash, torch.int64, "hash"),
+        _dev(signatures_workspace, torch.uint8, "signatures_workspace")
+        if signatures_workspace is not None else None,
         _dev(class_of_token, torch.int32, "class_of_token"),
         _dev(rep_of_class, torch.int32, "rep_of_class"),
         None, ctypes.addressof(c_host), ctypes.addressof(coll_host),

@@ -8,10 +8,11 @@
 //      tile and adds over the counts of the earlier tiles itself;
 //   2. equal-hash segments; inside a segment tokens with the same first byte are
 //      neighbours.  Every member is compared with its left neighbour (a chain:
-//      equality is transitive).  Stored signatures are compared row by row;
-//      without stored signatures both are re-walked with the image walk and
-//      compared on the short vector w when they share the first byte, through
-//      the index tables otherwise (walk_device.hpp);
+//      equality is transitive).  Three sources, in order of preference: the walk
+//      vectors a preceding cfgzip_signatures call left in its workspace (compared
+//      on the short vector w when both tokens share the first byte, through the
+//      index tables otherwise - walk_device.hpp); stored signature rows; or, with
+//      neither, both tokens are re-walked with the image walk;
 //   3. if no link differs (no hash collision - the overwhelmingly common case),
 //      the segments are the classes.  Otherwise every differing member starts a
 //      new chain and the chain starts of a segment are matched against each
@@ -44,7 +45,8 @@ static_assert(kThreads == kBins, "one thread per bin in the sort kernels");
 struct Counters {
     int32_t unresolved;
     int32_t num_classes;
-    int32_t pad[6];
+    int32_t store_unusable;  // the walk store did not match this call or had overflowed
+    int32_t pad[5];
 };
 
 // ---------------------------------------------------------------- radix sort
@@ -288,6 +290,7 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         ctr->unresolved = 0;
         ctr->num_classes = 0;
+        ctr->store_unusable = 0;
     }
     // where the segment that reaches into this tile starts (64-ary search by the first wave)
     if (wave == 0) {
@@ -392,6 +395,127 @@ __global__ __launch_bounds__(kThreads) void verify_stored_kernel(
             for (int j = lane; j < S; j += 64) diff |= a[j] != b[j];
         }
         settle(__ballot(diff) != 0ull, (int)i, resolved, mismatch, ctr);
+    }
+}
+
+// Compares the walk vectors that cfgzip_signatures kept for position i and for position
+// head_pos[i], for the pairs whose tokens have the same image row: idx[row] is onto, so sig
+// equal <=> w equal.  One thread per position, 16 bytes at a time (the padding behind a
+// vector is zero on both sides).  A store that does not belong to this (V, S) or has
+// overflowed is reported and nothing is compared.
+struct StoreVerifyArgs {
+    Tables T;
+    WalkStoreView store;
+    int32_t V, S, n;
+    const int32_t *vals;
+    const int32_t *head_pos;
+    int32_t *resolved;
+    int32_t *mismatch;
+    Counters *ctr;
+};
+
+__device__ __forceinline__ bool walk_store_usable(const StoreVerifyArgs &a, uint32_t stride) {
+    const WalkStore hdr = *a.store.header;
+    return hdr.magic == kWalkStoreMagic && hdr.V == a.V && hdr.S == a.S && hdr.stride == stride &&
+           !hdr.overflow;
+}
+
+__global__ __launch_bounds__(kThreads) void verify_store_same_row_kernel(StoreVerifyArgs a) {
+    const uint32_t stride = walk_store_stride(a.S);
+    if (!walk_store_usable(a, stride)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->store_unusable = 1;
+        return;
+    }
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= a.n || a.resolved[i]) return;
+    const int32_t ta = a.vals[i], tb = a.vals[a.head_pos[i]];
+    const uint32_t ra = min((uint32_t)a.store.wrow[ta], 256u), rb = min((uint32_t)a.store.wrow[tb], 256u);
+    if (ra != rb) return;  // left to verify_store_other_row_kernel
+    const uint32_t cnt = min((uint32_t)a.T.nimg[ra], stride);
+    const uint4 *wa = reinterpret_cast<const uint4 *>(a.store.wvec + (size_t)ta * stride);
+    const uint4 *wb = reinterpret_cast<const uint4 *>(a.store.wvec + (size_t)tb * stride);
+    const uint32_t n16 = (cnt + 7u) / 8u;
+    bool diff = false;
+    constexpr int kAhead = 4;  // independent 16-byte loads in flight per side
+    for (uint32_t k0 = 0; k0 < n16; k0 += kAhead) {
+        uint4 x[kAhead], y[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const uint32_t k = min(k0 + u, n16 - 1);  // repeats the last one past the end
+            x[u] = wa[k];
+            y[u] = wb[k];
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+            diff |= (x[u].x != y[u].x) | (x[u].y != y[u].y) | (x[u].z != y[u].z) | (x[u].w != y[u].w);
+    }
+    if (diff) {
+        a.mismatch[i] = 1;
+        atomicAdd(&a.ctr->unresolved, 1);
+    } else {
+        a.resolved[i] = 1;
+    }
+}
+
+// The pairs whose tokens have different image rows (neighbours at the border between two
+// first bytes inside a segment): sig[q] = w[idx[row][q]] has to be compared for every q.  A
+// workgroup of 16 waves looks at 64 consecutive positions; every wave finds the same list of
+// such pairs and takes every 16th of it, staging the two vectors in LDS.
+constexpr int kOtherRowThreads = 1024;
+__global__ __launch_bounds__(kOtherRowThreads) void verify_store_other_row_kernel(StoreVerifyArgs a) {
+    __shared__ uint16_t staged[kOtherRowThreads / 64][2][kWalkStoreMaxStride];
+    const uint32_t stride = walk_store_stride(a.S);
+    if (!walk_store_usable(a, stride)) return;  // reported by the same-row kernel
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int S = a.S;
+    const int i = blockIdx.x * 64 + lane;
+    const bool todo = i < a.n && !a.resolved[i];
+    int32_t ta = 0, tb = 0;
+    uint32_t ra = 256, rb = 256;
+    if (todo) {
+        ta = a.vals[i];
+        tb = a.vals[a.head_pos[i]];
+        ra = min((uint32_t)a.store.wrow[ta], 256u);
+        rb = min((uint32_t)a.store.wrow[tb], 256u);
+    }
+    uint64_t list = __ballot(todo && ra != rb);  // same-row pairs settle in the other kernel
+    uint16_t *la = staged[wave][0], *lb = staged[wave][1];
+    for (int ordinal = 0; list; ++ordinal) {
+        const int l = __ffsll((unsigned long long)list) - 1;
+        list &= list - 1;
+        if (ordinal % (kOtherRowThreads / 64) != wave) continue;  // wave-uniform
+        const int32_t sa = __shfl(ta, l, 64), sb = __shfl(tb, l, 64);
+        const uint32_t qa = __shfl(ra, l, 64), qb = __shfl(rb, l, 64);
+        const uint32_t na = min((uint32_t)a.T.nimg[qa], stride), nb = min((uint32_t)a.T.nimg[qb], stride);
+        {
+            // lanes 0..31 copy vector a, lanes 32..63 vector b, 16 bytes each (stride <= 256 entries)
+            const uint32_t half = lane & 31;
+            const uint16_t *src = a.store.wvec + (size_t)(lane < 32 ? sa : sb) * stride;
+            if (half * 8 < stride)
+                reinterpret_cast<uint4 *>(lane < 32 ? la : lb)[half] =
+                    reinterpret_cast<const uint4 *>(src)[half];
+        }
+        const uint16_t *ia = a.T.idx + (size_t)qa * S, *ib = a.T.idx + (size_t)qb * S;
+        bool d = false;
+        if ((S % 8) == 0) {
+            for (int q0 = lane * 8; q0 < S; q0 += 512) {
+                const uint4 xa = *reinterpret_cast<const uint4 *>(ia + q0);
+                const uint4 xb = *reinterpret_cast<const uint4 *>(ib + q0);
+                const uint32_t ja[8] = {xa.x & 0xFFFFu, xa.x >> 16, xa.y & 0xFFFFu, xa.y >> 16,
+                                        xa.z & 0xFFFFu, xa.z >> 16, xa.w & 0xFFFFu, xa.w >> 16};
+                const uint32_t jb[8] = {xb.x & 0xFFFFu, xb.x >> 16, xb.y & 0xFFFFu, xb.y >> 16,
+                                        xb.z & 0xFFFFu, xb.z >> 16, xb.w & 0xFFFFu, xb.w >> 16};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    d |= (ja[e] < na ? la[ja[e]] : 0xFFFFu) != (jb[e] < nb ? lb[jb[e]] : 0xFFFFu);
+            }
+        } else {
+            for (int q = lane; q < S; q += 64) {
+                const uint32_t ja = ia[q], jb = ib[q];
+                d |= (ja < na ? la[ja] : 0xFFFFu) != (jb < nb ? lb[jb] : 0xFFFFu);
+            }
+        }
+        settle(__ballot(d) != 0ull, blockIdx.x * 64 + l, a.resolved, a.mismatch, a.ctr);
     }
 }
 
@@ -685,7 +809,7 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
     BuildWorkspace w;
     const size_t n = (size_t)V;
     const size_t nt = (size_t)ceil_div(V, kTile);
-    w.sig_ws = c.take<char>(sig_workspace_bytes(S));
+    w.sig_ws = c.take<char>(sig_workspace_bytes(0, S));
     w.keys[0] = c.take<uint64_t>(n);
     w.keys[1] = c.take<uint64_t>(n);
     w.vals[0] = c.take<int32_t>(n);
@@ -743,7 +867,8 @@ extern "C" size_t cfgzip_build_classes_workspace_bytes(int32_t V, int32_t S) {
 
 extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                                     const uint16_t *table, int32_t S, const uint16_t *sig,
-                                    const uint64_t *hash, int32_t *class_of_token,
+                                    const uint64_t *hash, void *signatures_ws,
+                                    int32_t *class_of_token,
                                     int32_t *rep_of_class, int32_t *num_classes_dev,
                                     int32_t *num_classes_host, int32_t *collisions_host, void *ws,
                                     size_t ws_bytes, void *stream_) {
@@ -752,7 +877,7 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     if (!aligned_to(tok_off, 8) || !aligned_to(hash, 8) || !aligned_to(sig, 2) ||
         !aligned_to(table, 2) || !aligned_to(class_of_token, 4) || !aligned_to(rep_of_class, 4))
         return CFGZIP_E_INVALID;
-    if (!ws || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
+    if (!ws || !aligned_to(ws, 256) || !aligned_to(signatures_ws, 256)) return CFGZIP_E_WORKSPACE;
     BuildWorkspace w = carve_build_ws(ws, V, S);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -767,10 +892,15 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         if (n_cu <= 0) n_cu = 256;
     }
 
-    // without stored signatures the comparisons re-walk: tables first (independent of the sort)
+    // where the comparisons read signatures from
+    enum { FROM_STORE, FROM_ROWS, FROM_REWALK } source =
+        signatures_ws ? FROM_STORE : (sig ? FROM_ROWS : FROM_REWALK);
+    Tables store_tables{};
+    WalkStoreView store{};
+    if (source == FROM_STORE) view_signature_workspace(signatures_ws, V, S, &store_tables, &store);
     RewalkArgs ra{};
-    if (!sig) {
-        CFGZIP_TRY(prepare_tables(table, S, 0, false, w.sig_ws, &ra.T, stream));
+    auto prepare_rewalk = [&]() -> int {
+        CFGZIP_TRY(prepare_tables(table, S, 0, false, 0, w.sig_ws, &ra.T, nullptr, stream));
         ra.S = S;
         ra.wcap = walk_cap_for(S);
         ra.n = n;
@@ -780,7 +910,10 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         ra.resolved = w.resolved;
         ra.mismatch = w.mismatch;
         ra.ctr = w.ctr;
-    }
+        return CFGZIP_OK;
+    };
+    // re-walking needs its own tables: enqueue them first (independent of the sort)
+    if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk());
 
     // 1. sort (hash bits, first byte) with the token id as value
     int cur = 0;
@@ -817,21 +950,49 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     ra.head_pos = w.head_pos;
 
     // 2. equal-hash segments, chain set-up
-    hipLaunchKernelGGL(segments_kernel, dim3(nb), dim3(kThreads), 0, stream, keys, n, w.seg_head,
-                       w.head_pos, w.resolved, w.mismatch, w.min_id, w.rep_key, w.is_head_token,
-                       w.ctr);
-    CFGZIP_TRY(check_launch());
+    auto set_up_chains = [&]() -> int {
+        hipLaunchKernelGGL(segments_kernel, dim3(nb), dim3(kThreads), 0, stream, keys, n, w.seg_head,
+                           w.head_pos, w.resolved, w.mismatch, w.min_id, w.rep_key, w.is_head_token,
+                           w.ctr);
+        return check_launch();
+    };
+    CFGZIP_TRY(set_up_chains());
 
+    const int64_t wave_grid = ceil_div(std::min<int64_t>(n, (int64_t)n_cu * 32), kThreads / 64);
+    StoreVerifyArgs sva{};
+    sva.T = store_tables;
+    sva.store = store;
+    sva.V = V;
+    sva.S = S;
+    sva.n = n;
+    sva.vals = vals;
+    sva.head_pos = w.head_pos;
+    sva.resolved = w.resolved;
+    sva.mismatch = w.mismatch;
+    sva.ctr = w.ctr;
+    // compares every unsettled position i with position head_pos[i]
     auto verify_pairs = [&]() -> int {
-        if (sig) {
-            const int64_t waves = std::min<int64_t>(n, (int64_t)n_cu * 32);
-            hipLaunchKernelGGL(verify_stored_kernel, dim3((unsigned)ceil_div(waves, kThreads / 64)),
-                               dim3(kThreads), 0, stream, sig, S, vals, w.head_pos, w.resolved, n,
-                               w.mismatch, w.ctr);
+        if (source == FROM_STORE) {
+            hipLaunchKernelGGL(verify_store_same_row_kernel, grid_for(n), dim3(kThreads), 0, stream,
+                               sva);
+            CFGZIP_TRY(check_launch());
+            hipLaunchKernelGGL(verify_store_other_row_kernel, dim3((unsigned)ceil_div(n, 64)),
+                               dim3(kOtherRowThreads), 0, stream, sva);
+            return check_launch();
+        }
+        if (source == FROM_ROWS) {
+            hipLaunchKernelGGL(verify_stored_kernel, dim3((unsigned)wave_grid), dim3(kThreads), 0,
+                               stream, sig, S, vals, w.head_pos, w.resolved, n, w.mismatch, w.ctr);
             return check_launch();
         }
         return launch_rewalk(verify_pairs_rewalk_kernel<false>, verify_pairs_rewalk_kernel<true>, ra,
                              (int)ceil_div(n, kBatchTokens / 2), n_cu, stream);
+    };
+    // the chain links: head_pos[i] == i - 1 for every unsettled i
+    auto verify_links = [&]() -> int {
+        if (source != FROM_REWALK) return verify_pairs();
+        return launch_rewalk(verify_chain_rewalk_kernel<false>, verify_chain_rewalk_kernel<true>, ra,
+                             (int)ceil_div(n, kBatchTokens - 1), n_cu, stream);
     };
     // 4./5. class ids by ascending smallest member id, representatives
     auto number_classes = [&](const int32_t *anchor) -> int {
@@ -857,13 +1018,19 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
 
     // 3. chain links; the numbering is enqueued right behind them on the assumption that no
     //    link differs (then the segments are the classes), and redone in the rare other case
-    if (sig)
-        CFGZIP_TRY(verify_pairs());  // head_pos[i] == i - 1: neighbouring rows
-    else
-        CFGZIP_TRY(launch_rewalk(verify_chain_rewalk_kernel<false>, verify_chain_rewalk_kernel<true>,
-                                 ra, (int)ceil_div(n, kBatchTokens - 1), n_cu, stream));
+    CFGZIP_TRY(verify_links());
     CFGZIP_TRY(number_classes(w.seg_head));
     CFGZIP_TRY(read_counters());
+    if (source == FROM_STORE && host_ctr.store_unusable) {
+        // the workspace did not hold this call's walk vectors (or they had overflowed): start
+        // over from the chain set-up with the next source
+        source = sig ? FROM_ROWS : FROM_REWALK;
+        if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk());
+        CFGZIP_TRY(set_up_chains());
+        CFGZIP_TRY(verify_links());
+        CFGZIP_TRY(number_classes(w.seg_head));
+        CFGZIP_TRY(read_counters());
+    }
     const int32_t collisions = host_ctr.unresolved;
 
     if (collisions > 0) {

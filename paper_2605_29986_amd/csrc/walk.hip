@@ -26,17 +26,26 @@ struct WalkArgs {
     int32_t S;
     int32_t wcap;  // entries of w in LDS
     Tables T;
+    WalkStoreView store;
     uint16_t *sig_out;   // [V][S] or null
     uint64_t *hash_out;  // [V] or null
 };
 
 // Tt[b][q] = table[q][b]; the workgroups of the last grid row clear the padding behind Tt.
 __global__ __launch_bounds__(256) void transpose_table_kernel(const uint16_t *__restrict__ table,
-                                                              uint16_t *__restrict__ Tt, int S) {
+                                                              uint16_t *__restrict__ Tt, int S,
+                                                              WalkStore *store, int V) {
     __shared__ uint16_t tile[64][65];
     if (blockIdx.y == 4) {
         uint16_t *pad = Tt + (size_t)256 * S;
         for (int i = blockIdx.x * 256 + threadIdx.x; i < kTablePad; i += gridDim.x * 256) pad[i] = 0;
+        if (store && blockIdx.x == 0 && threadIdx.x == 0) {
+            store->magic = kWalkStoreMagic;
+            store->V = V;
+            store->S = S;
+            store->stride = walk_store_stride(S);
+            store->overflow = 0;
+        }
         return;
     }
     const int q0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
@@ -160,10 +169,25 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
             const int k = (int)min((int64_t)B.k, t_end - tcur);
             batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            if (a.hash_out) batch_walk<2, true>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
-            else batch_walk<2, false>(a.T, tab, S, a.tok_bytes, B, ldsb, w);
+            // the walk vectors are also kept for the class builder: token t at t * stride
+            const uint32_t stride = walk_store_stride(S);
+            uint16_t *keep = a.store.header ? a.store.wvec + (size_t)tcur * stride : nullptr;
+            if (a.hash_out) batch_walk<2, true>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
+            else batch_walk<2, false>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
             __syncthreads();
             if (a.hash_out && (int)threadIdx.x < k) a.hash_out[tcur + threadIdx.x] = B.hash[threadIdx.x];
+            if (a.store.header && (int)threadIdx.x < k) {
+                // image row, and zeros up to the next multiple of 8 entries behind the vector
+                const uint32_t m = threadIdx.x;
+                const uint32_t cnt = (uint32_t)(B.wstart[m + 1] - B.wstart[m]);
+                a.store.wrow[tcur + m] = (uint16_t)B.row[m];
+                if (cnt > stride) {
+                    a.store.header->overflow = 1;
+                } else {
+                    for (uint32_t j = cnt; j < ((cnt + 7u) & ~7u); ++j)
+                        a.store.wvec[(size_t)(tcur + m) * stride + j] = 0;
+                }
+            }
             if (a.sig_out) {
                 // sig[t][q] = w[idx[row][q]]
                 if (vec) {
@@ -212,10 +236,11 @@ struct SigWorkspace {
     int32_t *nimg;
     uint16_t *img, *idx;
     uint64_t *wsum;
+    WalkStoreView store;  // V > 0 only
     size_t bytes;
 };
 
-SigWorkspace carve_sig_ws(void *ws, int32_t S) {
+SigWorkspace carve_sig_ws(void *ws, int32_t V, int32_t S) {
     Carver c(ws);
     SigWorkspace w;
     w.Tt = c.take<uint16_t>((size_t)256 * S + kTablePad);
@@ -223,17 +248,23 @@ SigWorkspace carve_sig_ws(void *ws, int32_t S) {
     w.img = c.take<uint16_t>((size_t)kImageRows * S);
     w.idx = c.take<uint16_t>((size_t)kImageRows * S);
     w.wsum = c.take<uint64_t>((size_t)kImageRows * S);
+    w.store = WalkStoreView{nullptr, nullptr, nullptr};
+    if (V > 0) {
+        w.store.header = c.take<WalkStore>(1);
+        w.store.wrow = c.take<uint16_t>((size_t)V);
+        w.store.wvec = c.take<uint16_t>((size_t)V * walk_store_stride(S));
+    }
     w.bytes = c.used;
     return w;
 }
 
 }  // namespace
 
-int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, void *ws,
-                   Tables *out, hipStream_t stream) {
-    SigWorkspace w = carve_sig_ws(ws, S);
+int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, int32_t V,
+                   void *ws, Tables *out, WalkStoreView *store, hipStream_t stream) {
+    SigWorkspace w = carve_sig_ws(ws, V, S);
     hipLaunchKernelGGL(transpose_table_kernel, dim3((S + 63) / 64, 5), dim3(256), 0, stream, table,
-                       w.Tt, S);
+                       w.Tt, S, w.store.header, V);
     CFGZIP_TRY(check_launch());
     hipLaunchKernelGGL(image_tables_kernel, dim3(kImageRows), dim3(1024), 0, stream, w.Tt, S,
                        hash_seed, w.nimg, w.img, w.idx, want_wsum ? w.wsum : nullptr);
@@ -243,10 +274,21 @@ int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool wa
     out->img = w.img;
     out->idx = w.idx;
     out->wsum = want_wsum ? w.wsum : nullptr;
+    if (store) *store = w.store;
     return CFGZIP_OK;
 }
 
-size_t sig_workspace_bytes(int32_t S) { return carve_sig_ws(nullptr, S).bytes; }
+size_t sig_workspace_bytes(int32_t V, int32_t S) { return carve_sig_ws(nullptr, V, S).bytes; }
+
+void view_signature_workspace(void *ws, int32_t V, int32_t S, Tables *tables, WalkStoreView *store) {
+    SigWorkspace w = carve_sig_ws(ws, V, S);
+    tables->Tt = w.Tt;
+    tables->nimg = w.nimg;
+    tables->img = w.img;
+    tables->idx = w.idx;
+    tables->wsum = w.wsum;
+    *store = w.store;
+}
 
 }  // namespace cfgzip
 
@@ -254,7 +296,7 @@ using namespace cfgzip;
 
 extern "C" size_t cfgzip_signatures_workspace_bytes(int32_t V, int32_t S) {
     if (V <= 0 || S <= 0 || S > 65536) return 0;
-    return sig_workspace_bytes(S);
+    return sig_workspace_bytes(V, S);
 }
 
 extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
@@ -266,7 +308,7 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
     if (!aligned_to(tok_off, 8) || !aligned_to(table, 2) || !aligned_to(sig_out, 2) ||
         !aligned_to(hash_out, 8))
         return CFGZIP_E_INVALID;
-    if (!ws || ws_bytes < sig_workspace_bytes(S) || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
+    if (!ws || ws_bytes < sig_workspace_bytes(V, S) || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
     // tok_bytes may be null only if every token is empty; the kernels never read it then.
     hipStream_t stream = static_cast<hipStream_t>(stream_);
 
@@ -277,7 +319,7 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
     a.S = S;
     a.sig_out = sig_out;
     a.hash_out = hash_out;
-    CFGZIP_TRY(prepare_tables(table, S, hash_seed, hash_out != nullptr, ws, &a.T, stream));
+    CFGZIP_TRY(prepare_tables(table, S, hash_seed, hash_out != nullptr, V, ws, &a.T, &a.store, stream));
 
     int n_cu = 256;
     CFGZIP_TRY(device_cu_count(&n_cu));

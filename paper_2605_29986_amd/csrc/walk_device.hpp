@@ -45,10 +45,38 @@ struct Tables {
     const uint64_t *wsum;  // null when no hash is wanted
 };
 
+// Walk vectors kept in the signature workspace after cfgzip_signatures, so that the class
+// builder can compare signatures without walking again: token t has image row wrow[t] and its
+// vector is wvec[t * stride .. t * stride + nimg[wrow[t]]), padded with zeros to a multiple of
+// 8 entries (16-byte compares).  A token whose vector is longer than the stride does not fit;
+// then `overflow` is set and the store is unusable.
+struct WalkStore {
+    uint32_t magic;     // kWalkStoreMagic once the header is written for this (V, S)
+    int32_t V, S;
+    uint32_t stride;    // entries per token, a multiple of 8
+    uint32_t overflow;  // 1: some vector did not fit
+    uint32_t pad[3];
+};
+constexpr uint32_t kWalkStoreMagic = 0xCF621A1Cu;
+constexpr int kWalkStoreMaxStride = 256;  // entries kept per token at most (512 bytes)
+__host__ __device__ inline uint32_t walk_store_stride(int32_t S) {
+    const uint32_t s8 = ((uint32_t)S + 7u) & ~7u;
+    return s8 < (uint32_t)kWalkStoreMaxStride ? s8 : (uint32_t)kWalkStoreMaxStride;
+}
+
+struct WalkStoreView {
+    WalkStore *header;  // null: nothing is kept
+    uint16_t *wrow;     // [V]
+    uint16_t *wvec;     // [V][stride]
+};
+
 // Builds all tables in the signature workspace.  Host functions, defined in walk.hip.
-int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, void *ws,
-                   Tables *out, hipStream_t stream);
-size_t sig_workspace_bytes(int32_t S);
+// V > 0 also lays out (and resets) the walk store for V tokens.
+int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, int32_t V,
+                   void *ws, Tables *out, WalkStoreView *store, hipStream_t stream);
+size_t sig_workspace_bytes(int32_t V, int32_t S);
+// Views of a workspace that a finished cfgzip_signatures(V, S) call left behind.
+void view_signature_workspace(void *ws, int32_t V, int32_t S, Tables *tables, WalkStoreView *store);
 // Entries of w a batch may hold for an automaton of S states (>= 2 S, so that
 // any two tokens fit together).
 inline int walk_cap_for(int32_t S) { return 2 * S > kMinWalkCap ? 2 * S : kMinWalkCap; }
@@ -159,11 +187,12 @@ __device__ __forceinline__ void batch_stage_bytes(const Batch &B, const uint8_t 
 template <int U, bool LDS_BYTES, bool HASH>
 __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t *tab, int S,
                                                 const uint8_t *__restrict__ tok_bytes, Batch &B,
-                                                const uint8_t *ldsb, uint16_t *w) {
+                                                const uint8_t *ldsb, uint16_t *w,
+                                                uint16_t *keep, uint32_t keep_stride) {
     // every table index fits 32 bits: 257 rows of at most 65536 entries
     const uint32_t nt = blockDim.x, k = B.k, wtotal = B.wtotal, Su = (uint32_t)S;
     for (uint32_t i0 = threadIdx.x; i0 < wtotal; i0 += nt * U) {
-        uint32_t cur[U], nextb[U], rem[U], slot[U], src[U];
+        uint32_t cur[U], nextb[U], rem[U], slot[U], src[U], pos[U];
         uint64_t weight[U];
         const uint8_t *gbytes[U];  // !LDS_BYTES (over-long tokens, walked one at a time)
         uint32_t maxrem = 0;
@@ -174,12 +203,14 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
             cur[u] = 0;
             slot[u] = 0;
             src[u] = 0;
+            pos[u] = 0;
             nextb[u] = 0;
             weight[u] = 0;
             gbytes[u] = tok_bytes;
             if (i < wtotal) {
                 const uint32_t m = (uint32_t)batch_find(B.wstart, (int)k, (int)i);
-                const uint32_t e = (uint32_t)B.row[m] * Su + (i - (uint32_t)B.wstart[m]);
+                pos[u] = i - (uint32_t)B.wstart[m];
+                const uint32_t e = (uint32_t)B.row[m] * Su + pos[u];
                 slot[u] = m;
                 cur[u] = T.img[e];
                 if (HASH) weight[u] = T.wsum[e];
@@ -206,6 +237,9 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
             const uint32_t i = i0 + u * nt;
             if (i < wtotal) {
                 w[i] = (uint16_t)cur[u];
+                // slot m of the batch is token (first token of the batch) + m
+                if (keep && pos[u] < keep_stride)
+                    keep[(size_t)slot[u] * keep_stride + pos[u]] = (uint16_t)cur[u];
                 if (HASH)
                     atomicAdd(&B.hash[slot[u]], (unsigned long long)(weight[u] * (uint64_t)cur[u]));
             }
@@ -213,12 +247,16 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
     }
 }
 
+// `keep` (or null): where slot 0's walk vector is kept, slot m's follows keep_stride entries on.
 template <int U, bool HASH>
 __device__ __forceinline__ void batch_walk(const Tables &T, const uint16_t *tab, int S,
                                            const uint8_t *__restrict__ tok_bytes, Batch &B,
-                                           const uint8_t *ldsb, uint16_t *w) {
-    if (B.bytes_in_lds) batch_walk_impl<U, true, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
-    else batch_walk_impl<1, false, HASH>(T, tab, S, tok_bytes, B, ldsb, w);
+                                           const uint8_t *ldsb, uint16_t *w, uint16_t *keep = nullptr,
+                                           uint32_t keep_stride = 0) {
+    if (B.bytes_in_lds)
+        batch_walk_impl<U, true, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
+    else
+        batch_walk_impl<1, false, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
 }
 
 }  // namespace cfgzip

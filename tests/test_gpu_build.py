@@ -47,19 +47,30 @@ def _check_signatures(lib, vocab, table, seed=None):
     return want_sig, sig, h
 
 
-def _check_build(lib, vocab, table, stored=True, hash_override=None):
+def _check_build(lib, vocab, table, stored=True, hash_override=None, use_store=None):
+    """Builds the classes and compares them with the oracle's.  `use_store`: hand the
+    signature call's workspace to the class builder (True), do not (False), or both (None)."""
     from gpu_util import vocab_dev, dev
     tb, to, tt = vocab_dev(vocab, table)
     want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
     want_c, want_r = oracle.build_classes(want_sig, vocab.tok_off)
-    sig, h = lib.cfgzip_signatures(tb, to, tt, want_sig=stored)
+    V, S = vocab.V, table.shape[0]
+    ws = torch.empty(lib.load_library().cfgzip_signatures_workspace_bytes(V, S), dtype=torch.uint8,
+                     device="cuda")
+    sig, h = lib.cfgzip_signatures(tb, to, tt, want_sig=stored, workspace=ws)
     if hash_override is not None:
         h = hash_override(h)
-    c, r, C, coll = lib.cfgzip_build_classes(tb, to, tt, sig if stored else None, h)
-    assert C == len(want_r), (C, len(want_r))
-    assert (c.cpu().numpy() == want_c).all(), "class_of_token"
-    assert (r.cpu().numpy() == want_r).all(), "rep_of_class"
-    return C, coll
+    out = None
+    for with_store in ([True, False] if use_store is None else [use_store]):
+        c, r, C, coll = lib.cfgzip_build_classes(tb, to, tt, sig if stored else None, h,
+                                                 signatures_workspace=ws if with_store else None)
+        assert C == len(want_r), (with_store, C, len(want_r))
+        assert (c.cpu().numpy() == want_c).all(), f"class_of_token (store={with_store})"
+        assert (r.cpu().numpy() == want_r).all(), f"rep_of_class (store={with_store})"
+        if out is not None:
+            assert (C, coll > 0) == (out[0], out[1] > 0)
+        out = (C, coll)
+    return out
 
 
 @pytest.mark.parametrize("S", [1, 2, 3, 24, 33, 63, 64, 65, 100, 128, 129, 200, 256, 257, 288, 289,
@@ -153,6 +164,13 @@ def test_config4_build_hash_on_the_fly(lib):
     print("config 4: C =", C, "V/C =", vocab.V / C, "collisions =", coll, flush=True)
     assert C == len(want_r) and coll == 0
     assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+    # the same, comparing the compressed signatures the signature call left in its workspace
+    ws = torch.empty(lib.load_library().cfgzip_signatures_workspace_bytes(vocab.V, cfg["S"]),
+                     dtype=torch.uint8, device="cuda")
+    _, h = lib.cfgzip_signatures(tb, to, tt, want_sig=False, workspace=ws)
+    c, r, C, coll = lib.cfgzip_build_classes(tb, to, tt, None, h, signatures_workspace=ws)
+    assert C == len(want_r) and coll == 0
+    assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
 
 
 @pytest.mark.parametrize("stored", [True, False])
@@ -195,6 +213,37 @@ def test_build_random_automaton_every_token_its_own_class(lib):
     vocab = _random_vocab(rng, 5000, 6, empties=False)
     _check_build(lib, vocab, table)
     _check_build(lib, vocab, table, stored=False)
+
+
+def test_signature_workspace_that_does_not_match_is_ignored(lib, cfg1, cfg2_small):
+    """A workspace left by a call on another vocabulary / automaton, a zeroed one, and one
+    whose compressed signatures overflowed (random automaton: ~0.63 S states per token, more
+    than the 256 kept) must all give the same classes as no workspace at all."""
+    from gpu_util import vocab_dev
+    raw = lib.load_library()
+    v1, t1 = cfg1["vocab"], cfg1["table"]
+    v2, t2 = cfg2_small["vocab"], cfg2_small["table"]
+    tb, to, tt = vocab_dev(v2, t2)
+    want_sig = oracle.signatures(v2.tok_bytes, v2.tok_off, t2)
+    want_c, want_r = oracle.build_classes(want_sig, v2.tok_off)
+    need = max(raw.cfgzip_signatures_workspace_bytes(v1.V, 24),
+               raw.cfgzip_signatures_workspace_bytes(v2.V, 256))
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    _, h = lib.cfgzip_signatures(tb, to, tt, want_sig=False)
+    for case in ("zeroed", "other call"):
+        print("case", case, flush=True)
+        if case == "other call":
+            lib.cfgzip_signatures(*vocab_dev(v1, t1), want_sig=False, workspace=ws)
+        c, r, C, _ = lib.cfgzip_build_classes(tb, to, tt, None, h, signatures_workspace=ws)
+        assert C == len(want_r)
+        assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+    print("case overflow", flush=True)
+    rng = np.random.default_rng(77)
+    S = 1000
+    table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+    vocab = _random_vocab(rng, 700, 5, empties=True)
+    _check_build(lib, vocab, table, stored=False, use_store=True)
+    _check_build(lib, vocab, table, stored=True, use_store=True)
 
 
 def test_workspace_and_argument_errors(lib):

@@ -42,9 +42,11 @@ def test_host_only_queries(raw):
     raw.cfgzip_build_classes_workspace_bytes.restype = ctypes.c_size_t
     assert raw.cfgzip_version() >= 100
     s = raw.cfgzip_signatures_workspace_bytes(128256, 1024)
-    assert s >= 256 * 1024 * 2 + 1024 * 8
+    # transposed table + room for the compressed signatures (up to 256 uint16 per token)
+    assert s >= 256 * 1024 * 2 + 128256 * 256 * 2
     b = raw.cfgzip_build_classes_workspace_bytes(128256, 1024)
-    assert b > s + 128256 * (8 + 8 + 4 + 4)
+    # its own tables for the re-walk + sort buffers and per-position arrays
+    assert b > 256 * 1024 * 2 + 128256 * (8 + 8 + 4 + 4)
     assert raw.cfgzip_signatures_workspace_bytes(0, 10) == 0
     assert raw.cfgzip_build_classes_workspace_bytes(10, 70000) == 0
 
@@ -55,7 +57,7 @@ def test_null_and_range_arguments_are_rejected_without_a_gpu(raw):
     assert raw.cfgzip_map_to_rep(None, 1, None, 1, None, 1, None, None) == -1
     assert raw.cfgzip_signatures(None, None, 1, None, 1, None, None, ctypes.c_uint64(0), None,
                                  ctypes.c_size_t(0), None) == -1
-    assert raw.cfgzip_build_classes(None, None, 1, None, 1, None, None, None, None, None, None,
+    assert raw.cfgzip_build_classes(None, None, 1, None, 1, None, None, None, None, None, None, None,
                                     None, None, ctypes.c_size_t(0), None) == -1
 
 
