@@ -215,6 +215,43 @@ def test_build_random_automaton_every_token_its_own_class(lib):
     _check_build(lib, vocab, table, stored=False)
 
 
+def _structured_table(rng, S, n_narrow):
+    """A random automaton in which `n_narrow` byte columns have few distinct states (like a
+    lexer's) and the rest reject or scatter: mixes short and long walk vectors in one batch."""
+    table = np.zeros((S, 256), dtype=np.uint16)
+    for b in range(256):
+        kind = rng.integers(0, 3) if b >= n_narrow else 0
+        if kind == 0:      # few distinct targets
+            k = int(rng.integers(1, min(S, 12) + 1))
+            targets = rng.integers(0, S, size=k)
+            table[:, b] = targets[rng.integers(0, k, size=S)]
+        elif kind == 1:    # everything rejects
+            table[:, b] = 0
+        else:              # arbitrary
+            table[:, b] = rng.integers(0, S, size=S)
+    table[0, :] = 0        # state 0 absorbs
+    return table
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_cases_against_oracle(lib, seed):
+    """Random automata and vocabularies of many shapes: signatures, hash, classes and
+    representatives with every source of signatures the class builder knows."""
+    rng = np.random.default_rng(1000 + seed)
+    S = int(rng.choice([1, 2, 7, 24, 63, 64, 65, 130, 255, 256, 257, 300, 511, 777, 1024, 1500, 2100]))
+    V = int(rng.choice([1, 2, 63, 64, 65, 127, 129, 500, 2047, 2048, 2049, 3000]))
+    max_len = int(rng.choice([1, 2, 4, 9, 40]))
+    n_bytes = int(rng.choice([2, 5, 40, 256]))
+    table = _structured_table(rng, S, n_narrow=int(rng.choice([0, n_bytes // 2, n_bytes])))
+    vocab = _random_vocab(rng, V, max_len, n_bytes=n_bytes)
+    print(f"case seed={seed} S={S} V={V} max_len={max_len} n_bytes={n_bytes}", flush=True)
+    _check_signatures(lib, vocab, table)
+    stored = bool(rng.integers(0, 2))
+    _check_build(lib, vocab, table, stored=stored)
+    # a weak hash on top: collisions inside and across first-byte groups
+    _check_build(lib, vocab, table, stored=not stored, hash_override=lambda h: h & 0x3)
+
+
 def test_signature_workspace_that_does_not_match_is_ignored(lib, cfg1, cfg2_small):
     """A workspace left by a call on another vocabulary / automaton, a zeroed one, and one
     whose compressed signatures overflowed (random automaton: ~0.63 S states per token, more
