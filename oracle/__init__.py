@@ -135,6 +135,51 @@ def map_to_rep(tok, class_of_token, rep_of_class) -> np.ndarray:
     return out
 
 
+def live_states(table, accept) -> np.ndarray:
+    """uint8 [S]: 1 iff an accepting state is reachable from the state."""
+    table = _c(table, np.uint16)
+    accept = _c(accept, np.uint8)
+    S = table.shape[0]
+    assert table.shape == (S, 256) and accept.shape == (S,)
+    live = np.empty(S, dtype=np.uint8)
+    _load().oracle_live_states(_p(table), ctypes.c_int32(S), _p(accept), _p(live))
+    return live
+
+
+def state_masks(sig_rep, live) -> np.ndarray:
+    """int32 [S, W(C)]: bit k of row q = live[sig_rep[k][q]]."""
+    sig_rep = _c(sig_rep, np.uint16)
+    live = _c(live, np.uint8)
+    C, S = sig_rep.shape
+    out = np.empty((S, words_for(C)), dtype=np.int32)
+    _load().oracle_state_masks(_p(sig_rep), ctypes.c_int32(C), ctypes.c_int32(S), _p(live), _p(out))
+    return out
+
+
+def class_masks(state_mask, C: int, states) -> np.ndarray:
+    state_mask = _c(state_mask, np.int32)
+    states = _c(states, np.int32)
+    S = state_mask.shape[0]
+    assert state_mask.shape[1] == words_for(C)
+    out = np.empty((states.shape[0], words_for(C)), dtype=np.int32)
+    _load().oracle_class_masks(_p(state_mask), ctypes.c_int32(S), ctypes.c_int32(C), _p(states),
+                               ctypes.c_int32(states.shape[0]), _p(out))
+    return out
+
+
+def advance_states(sig_rep, class_of_token, tok, states) -> np.ndarray:
+    """Returns the new states (int32 [B])."""
+    sig_rep = _c(sig_rep, np.uint16)
+    c = _c(class_of_token, np.int32)
+    tok = _c(tok, np.int32)
+    out = np.array(states, dtype=np.int32, copy=True)
+    C, S = sig_rep.shape
+    _load().oracle_advance_states(_p(sig_rep), ctypes.c_int32(C), ctypes.c_int32(S), _p(c),
+                                  ctypes.c_int32(c.shape[0]), _p(tok), ctypes.c_int32(tok.shape[0]),
+                                  _p(out))
+    return out
+
+
 def signature_hash(sig, seed: int) -> np.ndarray:
     sig = _c(sig, np.uint16)
     V, S = sig.shape

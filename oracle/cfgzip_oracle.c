@@ -28,6 +28,18 @@
  *                         (bit-for-bit).
  *   oracle_map_to_rep     Section 3.1 "Inference" / Figure 1(a): sampled token
  *                         t(i) -> r[c[i]].
+ *   oracle_live_states    Section 2.2: a generated prefix is valid iff it is in Pr(L(G)), i.e.
+ *                         can be extended to a word of the language.  For a
+ *                         deterministic byte automaton with accepting states F:
+ *                         state q is live iff some byte string leads from q into F.
+ *   oracle_state_masks    Section 2.2 + Section 3.1 "Inference": the engine runs on the
+ *                         vocabulary E of representatives; its mask over E in automaton
+ *                         state q allows class k iff the state reached from q on the
+ *                         representative's bytes is live.
+ *   oracle_class_masks    the engine's mask m over E for each sequence of a batch (the row
+ *                         of its current state).
+ *   oracle_advance_states Section 3.1 "Inference": the engine's state is updated with the
+ *                         representative r[c[t]] of the sampled token t.
  *   oracle_hash           The library's signature hash (not in the paper; a
  *                         device of this implementation) written from its
  *                         formula:  H(t) = sum_q a_q * sig[t][q]  mod 2^64 with
@@ -192,6 +204,70 @@ void oracle_map_to_rep(const int32_t *tok, int32_t B, const int32_t *class_of_to
     for (int32_t b = 0; b < B; ++b) {
         int32_t t = tok[b];
         out[b] = (t < 0 || t >= V) ? -1 : rep_of_class[class_of_token[t]];
+    }
+}
+
+/* ---- the engine side for a deterministic byte automaton --------------- */
+
+/* live[q] = 1 iff an accepting state can be reached from q (with zero or more bytes). */
+void oracle_live_states(const uint16_t *table /* [S][256] */, int32_t S,
+                        const uint8_t *accept /* [S] */, uint8_t *live /* [S] */) {
+    for (int32_t q = 0; q < S; ++q) live[q] = accept[q] ? 1 : 0;
+    int changed = 1;
+    while (changed) {
+        changed = 0;
+        for (int32_t q = 0; q < S; ++q) {
+            if (live[q]) continue;
+            for (int b = 0; b < 256; ++b) {
+                if (live[table[(size_t)q * 256 + b]]) {
+                    live[q] = 1;
+                    changed = 1;
+                    break;
+                }
+            }
+        }
+    }
+}
+
+/* state_mask[q] bit k = live[ sig_rep[k][q] ]: class k is allowed in automaton state q. */
+void oracle_state_masks(const uint16_t *sig_rep /* [C][S] */, int32_t C, int32_t S,
+                        const uint8_t *live /* [S] */, int32_t *state_mask /* [S][W(C)] */) {
+    int64_t Wc = ((int64_t)C + 31) / 32;
+    for (int32_t q = 0; q < S; ++q) {
+        int32_t *row = state_mask + q * Wc;
+        for (int64_t w = 0; w < Wc; ++w) row[w] = 0;
+        for (int32_t k = 0; k < C; ++k) {
+            if (live[sig_rep[(size_t)k * S + q]])
+                row[k >> 5] = (int32_t)((uint32_t)row[k >> 5] | (1u << (k & 31)));
+        }
+    }
+}
+
+/* cls_bits[b] = state_mask[states[b]]; a state outside [0, S) allows nothing. */
+void oracle_class_masks(const int32_t *state_mask /* [S][W(C)] */, int32_t S, int32_t C,
+                        const int32_t *states /* [B] */, int32_t B,
+                        int32_t *cls_bits /* [B][W(C)] */) {
+    int64_t Wc = ((int64_t)C + 31) / 32;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t q = states[b];
+        for (int64_t w = 0; w < Wc; ++w)
+            cls_bits[b * Wc + w] = (q < 0 || q >= S) ? 0 : state_mask[q * Wc + w];
+    }
+}
+
+/* states[b] <- state reached from states[b] on the representative of tok[b]'s class;
+ * an id or state out of range gives -1. */
+void oracle_advance_states(const uint16_t *sig_rep /* [C][S] */, int32_t C, int32_t S,
+                           const int32_t *class_of_token /* [V] */, int32_t V,
+                           const int32_t *tok /* [B] */, int32_t B, int32_t *states /* [B] */) {
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t t = tok[b], q = states[b];
+        if (t < 0 || t >= V || q < 0 || q >= S) {
+            states[b] = -1;
+            continue;
+        }
+        int32_t k = class_of_token[t];
+        states[b] = (k < 0 || k >= C) ? -1 : (int32_t)sig_rep[(size_t)k * S + q];
     }
 }
 
