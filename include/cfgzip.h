@@ -188,6 +188,37 @@ int cfgzip_map_to_rep(const int32_t *tok, int32_t B,
                       const int32_t *rep_of_class, int32_t C,
                       int32_t *out, void *stream);
 
+/*
+ * Engine side for grammars given as a deterministic byte automaton.  The paper's engine works
+ * on the vocabulary E of class representatives (Section 3.1 "Inference"); for a byte
+ * automaton with accepting states that engine is a table look-up, and these three calls are
+ * it.  A token may follow a prefix iff the extended sequence is still a prefix of the
+ * language (Section 2.2), i.e. iff the state it leads to is live: an accepting state can be
+ * reached from it.
+ *
+ *   sig_rep   uint16 [C][S]  signatures of the C representatives (cfgzip_signatures on the
+ *                            representatives' byte strings): sig_rep[k][q] = state reached
+ *                            from q on the bytes of r[k]
+ *   live      uint8 [S]      1 iff an accepting state is reachable from the state
+ *
+ * cfgzip_state_masks (once per grammar):
+ *     state_mask[q] bit k = live[sig_rep[k][q]]        int32 [S][W(C)], pad bits 0
+ * cfgzip_class_masks (per decode step): the engine's mask over E for each sequence,
+ *     cls_bits[b] = state_mask[states[b]]              int32 [B][W(C)]; a state outside
+ *     [0, S) gives an all-zero row
+ * cfgzip_advance_states (per decode step): the engine consumes the representative of the
+ *     sampled token's class instead of the token,
+ *     states[b] <- sig_rep[class_of_token[tok[b]]][states[b]]     int32 [B], in place;
+ *     a token id, class id or state out of range gives -1
+ */
+int cfgzip_state_masks(const uint16_t *sig_rep, int32_t C, int32_t S, const uint8_t *live,
+                       int32_t *state_mask, void *stream);
+int cfgzip_class_masks(const int32_t *state_mask, int32_t S, int32_t C, const int32_t *states,
+                       int32_t B, int32_t *cls_bits, void *stream);
+int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
+                          const int32_t *class_of_token, int32_t V, const int32_t *tok, int32_t B,
+                          int32_t *states, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,11 +10,14 @@ There is no CPU fallback: calling anything without the built library raises.
 from .binding import (  # noqa: F401
     CfgzipError,
     DEFAULT_HASH_SEED,
+    cfgzip_advance_states,
     cfgzip_apply_mask,
     cfgzip_build_classes,
+    cfgzip_class_masks,
     cfgzip_expand_mask,
     cfgzip_map_to_rep,
     cfgzip_signatures,
+    cfgzip_state_masks,
     cfgzip_version,
     library_path,
     load_library,

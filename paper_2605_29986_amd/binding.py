@@ -71,6 +71,12 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_apply_mask.argtypes = [vp, i32, i32, i32, i64, vp, i32, vp, i32, vp, vp]
     lib.cfgzip_map_to_rep.restype = ctypes.c_int
     lib.cfgzip_map_to_rep.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_state_masks.restype = ctypes.c_int
+    lib.cfgzip_state_masks.argtypes = [vp, i32, i32, vp, vp, vp]
+    lib.cfgzip_class_masks.restype = ctypes.c_int
+    lib.cfgzip_class_masks.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+    lib.cfgzip_advance_states.restype = ctypes.c_int
+    lib.cfgzip_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -245,3 +251,49 @@ def cfgzip_map_to_rep(tok: torch.Tensor, class_of_token: torch.Tensor, rep_of_cl
                                rep_of_class.numel(), _dev(out, torch.int32, "out"), _stream(stream))
     _check("cfgzip_map_to_rep", rc)
     return out
+
+
+def cfgzip_state_masks(sig_rep: torch.Tensor, live: torch.Tensor, *,
+                       state_mask: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """state_mask[q] bit k = live[sig_rep[k][q]]; int32 [S, W(C)] from uint16 [C, S] and uint8 [S]."""
+    lib = load_library()
+    C, S = sig_rep.shape
+    if live.numel() != S:
+        raise ValueError("live must have one entry per automaton state")
+    if state_mask is None:
+        state_mask = torch.empty((S, words_for(C)), dtype=torch.int32, device=sig_rep.device)
+    rc = lib.cfgzip_state_masks(_dev(sig_rep, torch.uint16, "sig_rep"), C, S,
+                                _dev(live, torch.uint8, "live"),
+                                _dev(state_mask, torch.int32, "state_mask"), _stream(stream))
+    _check("cfgzip_state_masks", rc)
+    return state_mask
+
+
+def cfgzip_class_masks(state_mask: torch.Tensor, C: int, states: torch.Tensor, *,
+                       cls_bits: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """cls_bits[b] = state_mask[states[b]]; int32 [B, W(C)]."""
+    lib = load_library()
+    S = state_mask.shape[0]
+    B = states.numel()
+    if state_mask.shape[1] != words_for(C):
+        raise ValueError("state_mask must be [S, ceil(C/32)]")
+    if cls_bits is None:
+        cls_bits = torch.empty((B, words_for(C)), dtype=torch.int32, device=states.device)
+    rc = lib.cfgzip_class_masks(_dev(state_mask, torch.int32, "state_mask"), S, int(C),
+                                _dev(states, torch.int32, "states"), B,
+                                _dev(cls_bits, torch.int32, "cls_bits"), _stream(stream))
+    _check("cfgzip_class_masks", rc)
+    return cls_bits
+
+
+def cfgzip_advance_states(sig_rep: torch.Tensor, class_of_token: torch.Tensor, tok: torch.Tensor,
+                          states: torch.Tensor, *, stream=None) -> torch.Tensor:
+    """states[b] <- sig_rep[class_of_token[tok[b]]][states[b]], in place (-1 when out of range)."""
+    lib = load_library()
+    C, S = sig_rep.shape
+    rc = lib.cfgzip_advance_states(_dev(sig_rep, torch.uint16, "sig_rep"), C, S,
+                                   _dev(class_of_token, torch.int32, "class_of_token"),
+                                   class_of_token.numel(), _dev(tok, torch.int32, "tok"),
+                                   tok.numel(), _dev(states, torch.int32, "states"), _stream(stream))
+    _check("cfgzip_advance_states", rc)
+    return states

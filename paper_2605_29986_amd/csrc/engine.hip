@@ -1,0 +1,121 @@
+// Engine side for grammars given as a deterministic byte automaton (paper Section 2.2: a token
+// is allowed iff the extended sequence is still a prefix of the language; Section 3.1
+// "Inference": the engine runs on the vocabulary E of class representatives and is advanced
+// with r[c[t]] in place of the sampled token t).
+//
+// With sig_rep[k][q] = state reached from q on the bytes of class k's representative (the
+// signatures of the representatives) and live[q] = "an accepting state is reachable from q":
+//   state_mask[q] bit k = live[sig_rep[k][q]]      class-level mask of every automaton state,
+//                                                  computed once per grammar
+//   cls_bits[b]         = state_mask[state[b]]     the engine's mask m over E for sequence b
+//   state[b]           <- sig_rep[c[tok[b]]][state[b]]
+
+#include <algorithm>
+
+#include "common.hpp"
+
+namespace cfgzip {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kStateWords = 65536 / 32;  // one bit per uint16 value
+
+// Lanes are 64 consecutive states; a wave builds one 32-class word per state at a time from
+// 32 coalesced reads of signature rows, looking `live` up in an LDS bitmap.
+__global__ __launch_bounds__(kThreads) void state_masks_kernel(const uint16_t *__restrict__ sig_rep,
+                                                               int C, int S,
+                                                               const uint8_t *__restrict__ live,
+                                                               int32_t *__restrict__ state_mask,
+                                                               int Wc) {
+    __shared__ uint32_t live_bits[kStateWords];
+    for (int w = threadIdx.x; w < kStateWords; w += kThreads) {
+        uint32_t bits = 0;
+        for (int j = 0; j < 32; ++j) {
+            const int q = w * 32 + j;
+            if (q < S && live[q]) bits |= 1u << j;
+        }
+        live_bits[w] = bits;
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = blockIdx.x * 64 + lane;
+    if (q >= S) return;
+    const int waves = kThreads / 64;
+    for (int wi = blockIdx.y * waves + wave; wi < Wc; wi += gridDim.y * waves) {
+        uint32_t word = 0;
+#pragma unroll 8
+        for (int j = 0; j < 32; ++j) {
+            const int k = wi * 32 + j;
+            if (k < C) {
+                const uint32_t s = sig_rep[(size_t)k * S + q];
+                word |= ((live_bits[s >> 5] >> (s & 31)) & 1u) << j;
+            }
+        }
+        state_mask[(size_t)q * Wc + wi] = (int32_t)word;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void class_masks_kernel(const int32_t *__restrict__ state_mask,
+                                                               int S, int Wc,
+                                                               const int32_t *__restrict__ states,
+                                                               int32_t *__restrict__ cls_bits) {
+    const int b = blockIdx.x;
+    const int32_t q = states[b];
+    const bool ok = q >= 0 && q < S;
+    for (int w = threadIdx.x; w < Wc; w += kThreads)
+        cls_bits[(size_t)b * Wc + w] = ok ? state_mask[(size_t)q * Wc + w] : 0;
+}
+
+__global__ void advance_states_kernel(const uint16_t *__restrict__ sig_rep, int C, int S,
+                                      const int32_t *__restrict__ class_of_token, int V,
+                                      const int32_t *__restrict__ tok, int B, int32_t *states) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int32_t t = tok[b], q = states[b];
+    int32_t next = -1;
+    if (t >= 0 && t < V && q >= 0 && q < S) {
+        const int32_t k = class_of_token[t];
+        if (k >= 0 && k < C) next = (int32_t)sig_rep[(size_t)k * S + q];
+    }
+    states[b] = next;
+}
+
+}  // namespace
+}  // namespace cfgzip
+
+using namespace cfgzip;
+
+extern "C" int cfgzip_state_masks(const uint16_t *sig_rep, int32_t C, int32_t S, const uint8_t *live,
+                                  int32_t *state_mask, void *stream) {
+    if (!sig_rep || !live || !state_mask || C <= 0 || S <= 0 || S > 65536) return CFGZIP_E_INVALID;
+    if (!aligned_to(sig_rep, 2) || !aligned_to(state_mask, 4)) return CFGZIP_E_INVALID;
+    const int Wc = (int)words_for(C);
+    const int tiles = (int)ceil_div(S, 64);
+    // enough workgroups to fill the chip even for small automata
+    int rows = (int)std::min<int64_t>(ceil_div(Wc, kThreads / 64), std::max<int64_t>(1, 2048 / tiles));
+    hipLaunchKernelGGL(state_masks_kernel, dim3(tiles, rows), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), sig_rep, C, S, live, state_mask, Wc);
+    return check_launch();
+}
+
+extern "C" int cfgzip_class_masks(const int32_t *state_mask, int32_t S, int32_t C,
+                                  const int32_t *states, int32_t B, int32_t *cls_bits, void *stream) {
+    if (!state_mask || !states || !cls_bits || S <= 0 || C <= 0 || B <= 0) return CFGZIP_E_INVALID;
+    if (!aligned_to(state_mask, 4) || !aligned_to(states, 4) || !aligned_to(cls_bits, 4))
+        return CFGZIP_E_INVALID;
+    hipLaunchKernelGGL(class_masks_kernel, dim3(B), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), state_mask, S, (int)words_for(C), states,
+                       cls_bits);
+    return check_launch();
+}
+
+extern "C" int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
+                                     const int32_t *class_of_token, int32_t V, const int32_t *tok,
+                                     int32_t B, int32_t *states, void *stream) {
+    if (!sig_rep || !class_of_token || !tok || !states || C <= 0 || S <= 0 || V <= 0 || B <= 0)
+        return CFGZIP_E_INVALID;
+    hipLaunchKernelGGL(advance_states_kernel, dim3((B + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), sig_rep, C, S, class_of_token, V, tok, B,
+                       states);
+    return check_launch();
+}
