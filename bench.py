@@ -276,6 +276,53 @@ def main() -> int:
         f"{mask_ms * 1e3:.2f} us -> {achieved:.1f} GB/s ({achieved / HBM_PEAK_GBS:.1%} of HBM peak); "
         f"one-buffer (cache-resident) {mask_cached_ms * 1e3:.2f} us")
 
+    # ---- engine side for the byte automaton (next row after the hot path): per-state class
+    # masks once, then a closed step = class masks from states, fused expand + apply, advance on
+    # the representatives of the sampled tokens
+    rep_tokens = [vocab.token(int(t)) for t in r5_np]
+    rep_off = np.zeros(C + 1, dtype=np.int64)
+    rep_off[1:] = np.cumsum([len(t) for t in rep_tokens])
+    rep_bytes = np.frombuffer(b"".join(rep_tokens), dtype=np.uint8).copy()
+    sig_rep, _ = lib_mod.cfgzip_signatures(torch.from_numpy(rep_bytes).cuda(),
+                                           torch.from_numpy(rep_off).cuda(), tt, want_hash=False)
+    S5 = int(table.shape[0])
+    live_np = (rng.random(S5) < 0.5).astype(np.uint8)
+    live_np[0] = 0
+    live = torch.from_numpy(live_np).cuda()
+    state_mask = torch.empty((S5, (C + 31) // 32), dtype=torch.int32, device="cuda")
+    lib_mod.cfgzip_state_masks(sig_rep, live, state_mask=state_mask)
+    ms_state_masks = min(event_ms(lambda: lib_mod.cfgzip_state_masks(sig_rep, live, state_mask=state_mask),
+                                  stream) for _ in range(5))
+    states = torch.from_numpy(rng.integers(1, S5, size=B).astype(np.int32)).cuda()
+    cls_engine = torch.empty((B, (C + 31) // 32), dtype=torch.int32, device="cuda")
+    cm_args = (vp(state_mask.data_ptr()), i32(S5), i32(C), vp(states.data_ptr()), i32(B),
+               vp(cls_engine.data_ptr()), sptr)
+    adv_args = (vp(sig_rep.data_ptr()), i32(C), i32(S5), vp(c5.data_ptr()), i32(V), vp(tok.data_ptr()),
+                i32(B), vp(states.data_ptr()), sptr)
+    eng_mask_args = [(vp(lb.data_ptr()), i32(1), i32(B), i32(V), i64(V), vp(cls_engine.data_ptr()), i32(1),
+                      vp(c5.data_ptr()), i32(C), vp(tok_bits.data_ptr()), sptr) for lb in logit_bufs]
+
+    def engine_steps():
+        for i in range(args.steps):
+            rc = raw.cfgzip_class_masks(*cm_args)
+            rc |= apply_mask(*eng_mask_args[i % N_LOGIT_BUFFERS])
+            rc |= raw.cfgzip_advance_states(*adv_args)
+            if rc != 0:
+                raise RuntimeError(f"engine step failed, rc={rc}")
+    engine_steps()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    engine_steps()
+    torch.cuda.synchronize()
+    engine_us = (time.perf_counter() - t0) * 1e6 / args.steps
+    engine = {"workload": f"closed step: class masks from {B} automaton states (S={S5}, C={C}), fused "
+                          "expand + apply on bf16 logits, state advance on representatives",
+              "us_per_step": round(engine_us, 2),
+              "GBps": round(nbytes["mask_kernel"] / (engine_us * 1e-6) / 1e9, 1),
+              "ms_state_masks_once": round(ms_state_masks, 4)}
+    log(f"engine step (class masks + fused mask + advance): {engine_us:.2f} us/step; "
+        f"state masks [S={S5}][C={C}] once: {ms_state_masks * 1e3:.1f} us")
+
     build_cfgs = [int(x) for x in args.build_configs.split(",") if x]
     class_build = bench_class_build(lib_mod, raw, torch, build_cfgs, args.build_repeats) if build_cfgs else {}
 
@@ -304,6 +351,7 @@ def main() -> int:
                      "us_per_launch": round(mask_ms * 1e3, 3),
                      "us_per_launch_cache_resident": round(mask_cached_ms * 1e3, 3)},
         "class_build": class_build,
+        "engine": engine,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_decode(c5_np, r5_np, d)
