@@ -29,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E peak
+L1_LINE_RATE = 256 * 2.4e9  # vector-L1 cache-line look-ups per second on the chip
 N_LOGIT_BUFFERS = 8    # 8 x 65.7 MB = 525 MB > 256 MB memory-side cache
 # HBM bytes per launch of the mask kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/mask_kernel_config5_hbm_counters.md);
@@ -120,6 +121,10 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
             "table_reads_plain_walk": S * sum_len,
             "table_reads_image_walk": reads_done,
             "sig_store_GBps": round(2 * V * S / (ms_sig * 1e-3) / 1e9, 1) if stored else None,
+            # the walk's 2-byte table reads do not coalesce: one vector-L1 line look-up each, and a
+            # compute unit looks up one line per clock (256 CUs x 2.4 GHz); whole call, tables included
+            "table_reads_per_s": reads_done / (ms_sig * 1e-3),
+            "frac_of_l1_line_rate": round(reads_done / (ms_sig * 1e-3) / L1_LINE_RATE, 4),
         }
         log(f"class build config {idx}: V={V} S={S} C={C} signatures {ms_sig:.3f} ms, "
             f"total {ms_all:.3f} ms, {V * S / (ms_all * 1e-3):.3e} walks/s")

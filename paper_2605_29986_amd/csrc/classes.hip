@@ -420,17 +420,17 @@ __device__ __forceinline__ bool walk_store_usable(const StoreVerifyArgs &a, uint
            !hdr.overflow;
 }
 
-__global__ __launch_bounds__(kThreads) void verify_store_same_row_kernel(StoreVerifyArgs a) {
+__device__ __forceinline__ void verify_store_same_row(const StoreVerifyArgs &a, int block) {
     const uint32_t stride = walk_store_stride(a.S);
     if (!walk_store_usable(a, stride)) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->store_unusable = 1;
+        if (block == 0 && threadIdx.x == 0) a.ctr->store_unusable = 1;
         return;
     }
-    const int i = blockIdx.x * kThreads + threadIdx.x;
+    const int i = block * (int)blockDim.x + threadIdx.x;
     if (i >= a.n || a.resolved[i]) return;
     const int32_t ta = a.vals[i], tb = a.vals[a.head_pos[i]];
     const uint32_t ra = min((uint32_t)a.store.wrow[ta], 256u), rb = min((uint32_t)a.store.wrow[tb], 256u);
-    if (ra != rb) return;  // left to verify_store_other_row_kernel
+    if (ra != rb) return;  // left to verify_store_other_row
     const uint32_t cnt = min((uint32_t)a.T.nimg[ra], stride);
     const uint4 *wa = reinterpret_cast<const uint4 *>(a.store.wvec + (size_t)ta * stride);
     const uint4 *wb = reinterpret_cast<const uint4 *>(a.store.wvec + (size_t)tb * stride);
@@ -461,14 +461,14 @@ __global__ __launch_bounds__(kThreads) void verify_store_same_row_kernel(StoreVe
 // first bytes inside a segment): sig[q] = w[idx[row][q]] has to be compared for every q.  A
 // workgroup of 16 waves looks at 64 consecutive positions; every wave finds the same list of
 // such pairs and takes every 16th of it, staging the two vectors in LDS.
-constexpr int kOtherRowThreads = 1024;
-__global__ __launch_bounds__(kOtherRowThreads) void verify_store_other_row_kernel(StoreVerifyArgs a) {
-    __shared__ uint16_t staged[kOtherRowThreads / 64][2][kWalkStoreMaxStride];
+constexpr int kStoreVerifyThreads = 1024;
+__device__ __forceinline__ void verify_store_other_row(
+    const StoreVerifyArgs &a, int block, uint16_t (*staged)[2][kWalkStoreMaxStride]) {
     const uint32_t stride = walk_store_stride(a.S);
-    if (!walk_store_usable(a, stride)) return;  // reported by the same-row kernel
+    if (!walk_store_usable(a, stride)) return;  // reported by the same-row part
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int S = a.S;
-    const int i = blockIdx.x * 64 + lane;
+    const int i = block * 64 + lane;
     const bool todo = i < a.n && !a.resolved[i];
     int32_t ta = 0, tb = 0;
     uint32_t ra = 256, rb = 256;
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(kOtherRowThreads) void verify_store_other_row_kerne
     for (int ordinal = 0; list; ++ordinal) {
         const int l = __ffsll((unsigned long long)list) - 1;
         list &= list - 1;
-        if (ordinal % (kOtherRowThreads / 64) != wave) continue;  // wave-uniform
+        if (ordinal % (kStoreVerifyThreads / 64) != wave) continue;  // wave-uniform
         const int32_t sa = __shfl(ta, l, 64), sb = __shfl(tb, l, 64);
         const uint32_t qa = __shfl(ra, l, 64), qb = __shfl(rb, l, 64);
         const uint32_t na = min((uint32_t)a.T.nimg[qa], stride), nb = min((uint32_t)a.T.nimg[qb], stride);
@@ -515,8 +515,17 @@ __global__ __launch_bounds__(kOtherRowThreads) void verify_store_other_row_kerne
                 d |= (ja < na ? la[ja] : 0xFFFFu) != (jb < nb ? lb[jb] : 0xFFFFu);
             }
         }
-        settle(__ballot(d) != 0ull, blockIdx.x * 64 + l, a.resolved, a.mismatch, a.ctr);
+        settle(__ballot(d) != 0ull, block * 64 + l, a.resolved, a.mismatch, a.ctr);
     }
+}
+
+// Both parts in one launch (they settle disjoint positions): the first `same_row_blocks`
+// workgroups take one position per thread, the rest 64 positions per workgroup.
+__global__ __launch_bounds__(kStoreVerifyThreads) void verify_store_kernel(StoreVerifyArgs a,
+                                                                           int same_row_blocks) {
+    __shared__ uint16_t staged[kStoreVerifyThreads / 64][2][kWalkStoreMaxStride];
+    if ((int)blockIdx.x < same_row_blocks) verify_store_same_row(a, blockIdx.x);
+    else verify_store_other_row(a, blockIdx.x - same_row_blocks, staged);
 }
 
 // Signatures of two walked batch slots, compared without materialising either: directly on w
@@ -973,11 +982,10 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     // compares every unsettled position i with position head_pos[i]
     auto verify_pairs = [&]() -> int {
         if (source == FROM_STORE) {
-            hipLaunchKernelGGL(verify_store_same_row_kernel, grid_for(n), dim3(kThreads), 0, stream,
-                               sva);
-            CFGZIP_TRY(check_launch());
-            hipLaunchKernelGGL(verify_store_other_row_kernel, dim3((unsigned)ceil_div(n, 64)),
-                               dim3(kOtherRowThreads), 0, stream, sva);
+            const int same_row_blocks = (int)ceil_div(n, kStoreVerifyThreads);
+            hipLaunchKernelGGL(verify_store_kernel,
+                               dim3((unsigned)(same_row_blocks + ceil_div(n, 64))),
+                               dim3(kStoreVerifyThreads), 0, stream, sva, same_row_blocks);
             return check_launch();
         }
         if (source == FROM_ROWS) {
