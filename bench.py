@@ -33,7 +33,7 @@ L1_LINE_RATE = 256 * 2.4e9  # vector-L1 cache-line look-ups per second on the ch
 N_LOGIT_BUFFERS = 8    # 8 x 65.7 MB = 525 MB > 256 MB memory-side cache
 # HBM bytes per launch of the mask kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/mask_kernel_config5_hbm_counters.md);
-# set to None whenever mask.hip changes until the counters are taken again
+# set to None whenever the bf16 mask kernel changes until the counters are taken again
 MASK_KERNEL_TRAFFIC_BYTES = 141_630_000
 
 
@@ -182,6 +182,8 @@ def main() -> int:
     ap.add_argument("--build-configs", type=str, default="2,3,4")
     ap.add_argument("--build-repeats", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mask-variants", action="store_true",
+                    help="also time the other forms of the mask path at the same shape")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no cross-GPU part); "
@@ -328,6 +330,34 @@ def main() -> int:
     log(f"engine step (class masks + fused mask + advance): {engine_us:.2f} us/step; "
         f"state masks [S={S5}][C={C}] once: {ms_state_masks * 1e3:.1f} us")
 
+    # ---- optional: the other forms of the mask path at the same shape (kernel alone, rotating buffers)
+    mask_variants = {}
+    if args.mask_variants:
+        def time_loop(call_args_list, fn):
+            def loop():
+                for i in range(args.steps):
+                    fn(*call_args_list[i % len(call_args_list)])
+            loop()
+            return event_ms(loop, stream) / args.steps * 1e3  # us per launch
+        bf16_rw = 2 * B * V * 2
+        bits_v, bits_c, ids = B * ((V + 31) // 32) * 4, B * ((C + 31) // 32) * 4, V * 4
+        us = time_loop([a[:9] + (None,) + a[10:] for a in mask_args], apply_mask)
+        mask_variants["bf16_fused_no_token_mask_out"] = {"us": round(us, 2), "GBps": round((bf16_rw + bits_c + ids) / us / 1e3, 1)}
+        us = time_loop([(vp(cb.data_ptr()), i32(B), i32(C), vp(c5.data_ptr()), i32(V), vp(tok_bits.data_ptr()), sptr)
+                        for cb in cls_bufs], raw.cfgzip_expand_mask)
+        mask_variants["expand_only"] = {"us": round(us, 2), "GBps": round((bits_v + bits_c + ids) / us / 1e3, 1)}
+        us = time_loop([(vp(lb.data_ptr()), i32(1), i32(B), i32(V), i64(V), vp(tok_bits.data_ptr()), i32(0),
+                         None, i32(0), None, sptr) for lb in logit_bufs], apply_mask)
+        mask_variants["bf16_apply_from_token_mask"] = {"us": round(us, 2), "GBps": round((bf16_rw + bits_v) / us / 1e3, 1)}
+        f32_bufs = [torch.randn((B, V), dtype=torch.float32, device="cuda") for _ in range(4)]
+        us = time_loop([(vp(fb.data_ptr()), i32(0), i32(B), i32(V), i64(V), vp(cls_bufs[0].data_ptr()), i32(1),
+                         vp(c5.data_ptr()), i32(C), vp(tok_bits.data_ptr()), sptr) for fb in f32_bufs], apply_mask)
+        mask_variants["f32_fused_token_mask_out"] = {"us": round(us, 2),
+                                                     "GBps": round((2 * B * V * 4 + bits_v + bits_c + ids) / us / 1e3, 1)}
+        del f32_bufs
+        for k, v in mask_variants.items():
+            log(f"mask variant {k}: {v['us']} us -> {v['GBps']} GB/s")
+
     build_cfgs = [int(x) for x in args.build_configs.split(",") if x]
     class_build = bench_class_build(lib_mod, raw, torch, build_cfgs, args.build_repeats) if build_cfgs else {}
 
@@ -358,6 +388,8 @@ def main() -> int:
         "class_build": class_build,
         "engine": engine,
     }
+    if mask_variants:
+        result["mask_variants"] = mask_variants
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_decode(c5_np, r5_np, d)
         if build_cfgs:

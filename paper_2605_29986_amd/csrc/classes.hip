@@ -848,7 +848,7 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
 inline dim3 grid_for(int n) { return dim3((unsigned)ceil_div(n, kThreads)); }
 
 template <typename Kern>
-int launch_rewalk(Kern kern_lds, Kern kern_global, const RewalkArgs &a, int n_chunks, int n_cu,
+int launch_rewalk(Kern kern_lds, Kern kern_global, const RewalkArgs &a, int n_chunks,
                   hipStream_t stream) {
     if (a.wcap > kMaxLdsWalkEntries) {
         hipLaunchKernelGGL(kern_global, dim3((unsigned)std::min(n_chunks, kGlobalWalkGrid)),
@@ -994,13 +994,13 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
             return check_launch();
         }
         return launch_rewalk(verify_pairs_rewalk_kernel<false>, verify_pairs_rewalk_kernel<true>, ra,
-                             (int)ceil_div(n, kBatchTokens / 2), n_cu, stream);
+                             (int)ceil_div(n, kBatchTokens / 2), stream);
     };
     // the chain links: head_pos[i] == i - 1 for every unsettled i
     auto verify_links = [&]() -> int {
         if (source != FROM_REWALK) return verify_pairs();
         return launch_rewalk(verify_chain_rewalk_kernel<false>, verify_chain_rewalk_kernel<true>, ra,
-                             (int)ceil_div(n, kBatchTokens - 1), n_cu, stream);
+                             (int)ceil_div(n, kBatchTokens - 1), stream);
     };
     // 4./5. class ids by ascending smallest member id, representatives
     auto number_classes = [&](const int32_t *anchor) -> int {

@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(MaskArgs a) {
         } else {  // fp32: two 16-byte accesses per thread and row
             uint32_t *base = reinterpret_cast<uint32_t *>(a.logits) + (int64_t)r0 * a.row_stride + col0;
             constexpr uint32_t NINF = 0xFF800000u;
-            constexpr int U = kUnroll > 1 ? kUnroll / 2 : 1;
+            constexpr int U = 4;  // rows in flight (eight 16-byte loads): measured best of 1, 2, 4
             auto do_rows = [&](int r, auto count) {
                 constexpr int N = decltype(count)::value;
                 u32x4 x[N][2];
