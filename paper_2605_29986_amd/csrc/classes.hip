@@ -2,7 +2,7 @@
 // and pick representatives (paper Section 3.1 "Pre-Computation").
 //
 // Pipeline (all on the device):
-//   1. stable LSD radix sort of the 40-bit key (low 32 bits of the hash, first
+//   1. stable LSD radix sort of the key (low 32 or 40 bits of the hash, first
 //      byte of the token) with the token id as value, 8 bits per pass, two
 //      kernels per pass: per-tile digit counts, then a scatter that ranks its
 //      tile and adds over the counts of the earlier tiles itself;
@@ -36,10 +36,11 @@ constexpr int kItems = 8;
 constexpr int kTile = kThreads * kItems;  // keys per workgroup in sort and scan kernels
 constexpr int kRadixBits = 8;
 constexpr int kBins = 1 << kRadixBits;
-constexpr int kHashBits = 32;                   // hash bits that take part in the sort
-constexpr int kKeyBits = kHashBits + 8;         // + first byte
-constexpr int kPasses = kKeyBits / kRadixBits;  // 5
-constexpr uint64_t kHashMask = (1ull << kHashBits) - 1ull;
+// Hash bits that take part in the sort, above the 8 bits of the first byte.  Two classes that
+// agree in these bits only cost a pass through the collision rounds (C classes: about
+// C^2 / 2^(bits+1) such pairs), so small vocabularies sort 32 bits (5 passes) and large ones 40.
+constexpr int32_t kLargeVocabulary = 1 << 18;
+inline int hash_bits_for(int32_t V) { return V > kLargeVocabulary ? 40 : 32; }
 static_assert(kThreads == kBins, "one thread per bin in the sort kernels");
 
 struct Counters {
@@ -55,10 +56,11 @@ struct Counters {
 // of that 0 with a real first byte only costs a slower comparison)
 __device__ __forceinline__ uint64_t sort_key(const uint64_t *__restrict__ hash,
                                              const int64_t *__restrict__ tok_off,
-                                             const uint8_t *__restrict__ tok_bytes, int t) {
+                                             const uint8_t *__restrict__ tok_bytes, int t,
+                                             uint64_t hash_mask) {
     const int64_t beg = tok_off[t];
     const uint32_t fb = tok_off[t + 1] > beg ? (uint32_t)tok_bytes[beg] : 0u;
-    return ((hash[t] & kHashMask) << 8) | fb;
+    return ((hash[t] & hash_mask) << 8) | fb;
 }
 
 // Digit counts of one pass per tile: hist[tile][digit].  The first pass forms its keys from
@@ -67,7 +69,7 @@ template <bool FIRST>
 __global__ __launch_bounds__(kThreads) void radix_hist_kernel(
     const uint64_t *__restrict__ hash, const int64_t *__restrict__ tok_off,
     const uint8_t *__restrict__ tok_bytes, const uint64_t *__restrict__ keys, int n, int shift,
-    uint32_t *hist) {
+    uint64_t hash_mask, uint32_t *hist) {
     __shared__ uint32_t bins[kBins];
     bins[threadIdx.x] = 0;
     __syncthreads();
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void radix_hist_kernel(
     for (int j = 0; j < kItems; ++j) {
         const int idx = base + j * kThreads + threadIdx.x;
         if (idx < n) {
-            const uint64_t key = FIRST ? sort_key(hash, tok_off, tok_bytes, idx) : keys[idx];
+            const uint64_t key = FIRST ? sort_key(hash, tok_off, tok_bytes, idx, hash_mask) : keys[idx];
             atomicAdd(&bins[(uint32_t)(key >> shift) & (kBins - 1)], 1u);
         }
     }
@@ -93,6 +95,7 @@ struct ScatterArgs {
     uint64_t *keys_out;
     int32_t *vals_out;
     const uint32_t *hist;  // [nb][256] digit counts of this pass per input tile
+    uint64_t hash_mask;
     int n, nb, shift;
 };
 
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(ScatterArgs a) 
         const int idx = chunk + j * 64 + lane;
         const bool valid = idx < a.n;
         key[j] = !valid ? 0ull
-                 : FIRST ? sort_key(a.hash, a.tok_off, a.tok_bytes, idx)
+                 : FIRST ? sort_key(a.hash, a.tok_off, a.tok_bytes, idx, a.hash_mask)
                          : a.keys_in[idx];
         const uint32_t d = (uint32_t)(key[j] >> a.shift) & (kBins - 1);
         uint64_t peers = __ballot(valid);
@@ -925,8 +928,11 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk());
 
     // 1. sort (hash bits, first byte) with the token id as value
+    const int hash_bits = hash_bits_for(V);
+    const uint64_t hash_mask = (1ull << hash_bits) - 1ull;
+    const int passes = (hash_bits + 8) / kRadixBits;
     int cur = 0;
-    for (int pass = 0; pass < kPasses; ++pass) {
+    for (int pass = 0; pass < passes; ++pass) {
         ScatterArgs sa{};
         sa.hash = hash;
         sa.tok_off = tok_off;
@@ -936,17 +942,18 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         sa.keys_out = w.keys[cur];
         sa.vals_out = w.vals[cur];
         sa.hist = w.hist;
+        sa.hash_mask = hash_mask;
         sa.n = n;
         sa.nb = nb;
         sa.shift = pass * kRadixBits;
         if (pass == 0) {
             hipLaunchKernelGGL(radix_hist_kernel<true>, dim3(nb), dim3(kThreads), 0, stream, hash,
-                               tok_off, tok_bytes, nullptr, n, sa.shift, w.hist);
+                               tok_off, tok_bytes, nullptr, n, sa.shift, hash_mask, w.hist);
             CFGZIP_TRY(check_launch());
             hipLaunchKernelGGL(radix_scatter_kernel<true>, dim3(nb), dim3(kThreads), 0, stream, sa);
         } else {
             hipLaunchKernelGGL(radix_hist_kernel<false>, dim3(nb), dim3(kThreads), 0, stream, hash,
-                               tok_off, tok_bytes, sa.keys_in, n, sa.shift, w.hist);
+                               tok_off, tok_bytes, sa.keys_in, n, sa.shift, hash_mask, w.hist);
             CFGZIP_TRY(check_launch());
             hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(nb), dim3(kThreads), 0, stream, sa);
         }

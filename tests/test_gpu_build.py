@@ -252,6 +252,20 @@ def test_random_cases_against_oracle(lib, seed):
     _check_build(lib, vocab, table, stored=not stored, hash_override=lambda h: h & 0x3)
 
 
+def test_million_token_vocabulary(lib):
+    """Many tiles in the sort (489) and in the scans; the tiny automaton keeps the oracle fast."""
+    cfg = si.make_config(1, V=1_000_003)
+    vocab, table = cfg["vocab"], cfg["table"]
+    _check_signatures(lib, vocab, table)
+    C, coll = _check_build(lib, vocab, table)
+    print("V = 1,000,003: C =", C, "collisions =", coll, flush=True)
+    _check_build(lib, vocab, table, stored=False, use_store=False)
+    # 393,149 classes squeezed into 2^20 hash values: tens of thousands of collisions at scale
+    C2, coll2 = _check_build(lib, vocab, table, use_store=True, hash_override=lambda h: h & 0xFFFFF)
+    print("with a 20-bit hash: collisions =", coll2, flush=True)
+    assert C2 == C and coll2 > 1000
+
+
 def test_signature_workspace_that_does_not_match_is_ignored(lib, cfg1, cfg2_small):
     """A workspace left by a call on another vocabulary / automaton, a zeroed one, and one
     whose compressed signatures overflowed (random automaton: ~0.63 S states per token, more
