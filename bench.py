@@ -392,8 +392,8 @@ def main() -> int:
         result["mask_variants"] = mask_variants
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline_decode(c5_np, r5_np, d)
-        if build_cfgs:
-            result["class_build"]["cpu_baseline"] = cpu_baseline_build(build_cfgs[-1])
+        for idx in build_cfgs:  # the oracle's class build on the same workloads, host cores
+            result["class_build"][f"config{idx}"]["cpu_baseline"] = cpu_baseline_build(idx)
     print(json.dumps(result), flush=True)
     return 0
 
