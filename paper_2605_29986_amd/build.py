@@ -33,6 +33,9 @@ def find_hipcc() -> str:
     raise RuntimeError("hipcc not found; libcfgzip.so cannot be built")
 
 
+TOOL_PATH = os.path.join(LIB_DIR, "gather_rate")  # calibration tool for the walk kernels' roofline
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(LIB_DIR, exist_ok=True)
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
@@ -41,6 +44,13 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(tmp, LIB_PATH)
+    tool_flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    tmp = TOOL_PATH + ".tmp.%d" % os.getpid()
+    cmd = [find_hipcc(), *tool_flags, "-o", tmp, os.path.join(CSRC, "tools", "gather_rate.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, TOOL_PATH)
     return LIB_PATH
 
 
