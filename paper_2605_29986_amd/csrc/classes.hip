@@ -542,7 +542,7 @@ __device__ __forceinline__ bool slots_differ(const Batch &B, const Tables &T, in
     const uint16_t *wm = w + B.wstart[sm], *wh = w + B.wstart[sh];
     bool diff = false;
     if (rm == rh) {
-        const int cnt = B.wstart[sm + 1] - B.wstart[sm];
+        const int cnt = B.cnt[sm];
         for (int j = lane; j < cnt; j += 64) diff |= wm[j] != wh[j];
     } else if ((S % 8) == 0) {
         const uint4 *im = reinterpret_cast<const uint4 *>(T.idx + (size_t)rm * S);
@@ -619,7 +619,7 @@ __global__ __launch_bounds__(kThreads) void verify_chain_rewalk_kernel(RewalkArg
             const int links = min(B.k - 1, i_end - icur);
             batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            batch_walk<2, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
+            batch_walk<false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
             __syncthreads();
             for (int l = 1 + wave; l <= links; l += kThreads / 64) {
                 if (!B.aux[l]) continue;  // wave-uniform
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(kThreads) void verify_pairs_rewalk_kernel(RewalkArg
             const int pairs = min(B.k / 2, i_end - icur);
             batch_stage_bytes(B, a.tok_bytes, ldsb);
             __syncthreads();
-            batch_walk<2, false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
+            batch_walk<false>(a.T, a.T.Tt, a.S, a.tok_bytes, B, ldsb, w);
             __syncthreads();
             for (int p = wave; p < pairs; p += kThreads / 64) {
                 if (!B.aux[2 * p]) continue;  // wave-uniform

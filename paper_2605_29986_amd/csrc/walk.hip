@@ -172,21 +172,15 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
             // the walk vectors are also kept for the class builder: token t at t * stride
             const uint32_t stride = walk_store_stride(S);
             uint16_t *keep = a.store.header ? a.store.wvec + (size_t)tcur * stride : nullptr;
-            if (a.hash_out) batch_walk<2, true>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
-            else batch_walk<2, false>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
+            if (a.hash_out) batch_walk<true>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
+            else batch_walk<false>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
             __syncthreads();
             if (a.hash_out && (int)threadIdx.x < k) a.hash_out[tcur + threadIdx.x] = B.hash[threadIdx.x];
             if (a.store.header && (int)threadIdx.x < k) {
-                // image row, and zeros up to the next multiple of 8 entries behind the vector
+                // image row of the kept vector (the walk wrote the vector and its zero padding)
                 const uint32_t m = threadIdx.x;
-                const uint32_t cnt = (uint32_t)(B.wstart[m + 1] - B.wstart[m]);
                 a.store.wrow[tcur + m] = (uint16_t)B.row[m];
-                if (cnt > stride) {
-                    a.store.header->overflow = 1;
-                } else {
-                    for (uint32_t j = cnt; j < ((cnt + 7u) & ~7u); ++j)
-                        a.store.wvec[(size_t)(tcur + m) * stride + j] = 0;
-                }
+                if ((uint32_t)B.cnt[m] > stride) a.store.header->overflow = 1;
             }
             if (a.sig_out) {
                 // sig[t][q] = w[idx[row][q]]
@@ -326,7 +320,7 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
     const int64_t n_chunks = ceil_div(V, kBatchTokens);
     const bool lds_table = (size_t)S * 512 <= kLdsTableLimit;
     // the signatures kernel walks one token at a time in the worst case: S entries suffice
-    a.wcap = std::max(kMinWalkCap, S);
+    a.wcap = std::max(kMinWalkCap, (S + kWalkGroup - 1) / kWalkGroup * kWalkGroup);
     if (lds_table) {
         const size_t dyn = (size_t)S * 512 + (size_t)a.wcap * 2;
         auto kern = signatures_kernel<true>;

@@ -36,6 +36,7 @@ constexpr int kImageRows = 257;     // 256 first bytes + the "empty token" row
 constexpr int kBatchTokens = 64;    // tokens a workgroup walks together (one per lane of a wave)
 constexpr int kByteCap = 4096;      // token bytes staged in LDS per batch
 constexpr int kMinWalkCap = 8192;   // walks (entries of w) held in LDS per batch, at least
+constexpr int kWalkGroup = 8;       // walks of one token that a thread carries together
 
 struct Tables {
     const uint16_t *Tt;
@@ -77,9 +78,12 @@ int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool wa
 size_t sig_workspace_bytes(int32_t V, int32_t S);
 // Views of a workspace that a finished cfgzip_signatures(V, S) call left behind.
 void view_signature_workspace(void *ws, int32_t V, int32_t S, Tables *tables, WalkStoreView *store);
-// Entries of w a batch may hold for an automaton of S states (>= 2 S, so that
-// any two tokens fit together).
-inline int walk_cap_for(int32_t S) { return 2 * S > kMinWalkCap ? 2 * S : kMinWalkCap; }
+// Entries of w a batch may hold for an automaton of S states: room for any two tokens, each
+// padded to a whole number of walk groups.
+inline int walk_cap_for(int32_t S) {
+    const int two = 2 * ((S + kWalkGroup - 1) / kWalkGroup * kWalkGroup);
+    return two > kMinWalkCap ? two : kMinWalkCap;
+}
 
 __device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint32_t index) {
     // index-th output (0-based) of the SplitMix64 generator seeded with `seed`
@@ -101,14 +105,19 @@ __device__ __forceinline__ int wave_inclusive_sum(int v) {
 }
 
 // A batch of up to kBatchTokens byte strings that a workgroup walks together.
-// Slot m owns walks [wstart[m], wstart[m+1]) and staged bytes [boff[m], boff[m+1]).
-// A slot with no walks (an unused lane) has wstart[m] == wstart[m+1].
+// Slot m has cnt[m] walks; they are carried in groups of kWalkGroup (the last group padded),
+// groups [gstart[m], gstart[m+1]), and their end states land in w[wstart[m] ..], a region
+// padded to whole groups whose padding reads 0.  Staged bytes: [boff[m], boff[m+1]).
+// A slot with no walks (an unused lane) has no groups.
 struct Batch {
     int32_t k;             // slots in use
     int32_t wtotal;        // walks of the batch
     int32_t btotal;        // staged bytes of the batch
     int32_t bytes_in_lds;  // 0: a single over-long token, its bytes are read from global memory
+    int32_t gtotal;        // walk groups of the batch
     int32_t wstart[kBatchTokens + 1];
+    int32_t gstart[kBatchTokens + 1];
+    int32_t cnt[kBatchTokens];
     int32_t boff[kBatchTokens + 1];
     int32_t len[kBatchTokens];
     int32_t row[kBatchTokens];  // image row: first byte, or 256 for an empty byte string
@@ -141,16 +150,21 @@ __device__ __forceinline__ int batch_fill(Batch &B, const Tables &T, const uint8
     const int len = !used ? 0 : (len64 > 0x7FFFFFFF ? 0x7FFFFFFF : (int)len64);
     const int row = len > 0 ? (int)tok_bytes[beg] : 256;
     const int n = used ? T.nimg[row] : 0;
+    const int groups = (n + kWalkGroup - 1) / kWalkGroup;
+    const int npad = groups * kWalkGroup;
     const int lenc = len > kByteCap ? kByteCap + 1 : len;
-    const int incl_n = wave_inclusive_sum(n);
+    const int incl_n = wave_inclusive_sum(npad);
+    const int incl_g = wave_inclusive_sum(groups);
     const int incl_b = wave_inclusive_sum(lenc);
     const bool fits = lane < min_lanes || (incl_n <= wcap && incl_b <= kByteCap);
     const uint64_t mask = __ballot(fits);
-    // accepted lanes form a prefix: both sums are non-decreasing
+    // accepted lanes form a prefix: the sums are non-decreasing
     int k = mask == ~0ull ? 64 : __ffsll((unsigned long long)~mask) - 1;
     k -= k % group;
     if (lane < k) {
-        B.wstart[lane] = incl_n - n;
+        B.wstart[lane] = incl_n - npad;
+        B.gstart[lane] = incl_g - groups;
+        B.cnt[lane] = n;
         B.boff[lane] = incl_b - lenc;
         B.len[lane] = len;
         B.row[lane] = row;
@@ -159,9 +173,11 @@ __device__ __forceinline__ int batch_fill(Batch &B, const Tables &T, const uint8
     }
     if (lane == k - 1) {
         B.wstart[k] = incl_n;
+        B.gstart[k] = incl_g;
         B.boff[k] = incl_b;
         B.k = k;
         B.wtotal = incl_n;
+        B.gtotal = incl_g;
         B.btotal = incl_b;
         B.bytes_in_lds = incl_b <= kByteCap ? 1 : 0;
     }
@@ -180,83 +196,65 @@ __device__ __forceinline__ void batch_stage_bytes(const Batch &B, const uint8_t 
 }
 
 // Walks every (slot, image state) pair of the batch: w[wstart[m] + j] = state reached from
-// img[row][j] on bytes 1.. of slot m.  The walk is a chain of dependent table reads, so a
-// thread keeps U independent walks in flight, fetches the next byte while the current table
-// read is outstanding, and loads the hash weight before the walk starts.  With HASH, also
-// accumulates B.hash[m] += wsum[row][j] * w (order-free).
-template <int U, bool LDS_BYTES, bool HASH>
+// img[row][j] on bytes 1.. of slot m (0 in the padding).  A walk is a chain of dependent table
+// reads, so a thread carries a group of kWalkGroup walks of ONE slot: they share the bytes,
+// have the same length, and give eight independent reads per step; the next byte is fetched
+// while the current reads are outstanding.  With HASH, adds the group's part of
+// sum_j wsum[row][j] * w[j] to B.hash[m] (order-free).  `keep` (or null) is where slot 0's
+// walk vector is kept, slot m's follows keep_stride entries on (keep_stride a multiple of
+// kWalkGroup; a vector longer than that is cut off).
+template <bool LDS_BYTES, bool HASH>
 __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t *tab, int S,
                                                 const uint8_t *__restrict__ tok_bytes, Batch &B,
-                                                const uint8_t *ldsb, uint16_t *w,
-                                                uint16_t *keep, uint32_t keep_stride) {
+                                                const uint8_t *ldsb, uint16_t *w, uint16_t *keep,
+                                                uint32_t keep_stride) {
     // every table index fits 32 bits: 257 rows of at most 65536 entries
-    const uint32_t nt = blockDim.x, k = B.k, wtotal = B.wtotal, Su = (uint32_t)S;
-    for (uint32_t i0 = threadIdx.x; i0 < wtotal; i0 += nt * U) {
-        uint32_t cur[U], nextb[U], rem[U], slot[U], src[U], pos[U];
-        uint64_t weight[U];
-        const uint8_t *gbytes[U];  // !LDS_BYTES (over-long tokens, walked one at a time)
-        uint32_t maxrem = 0;
+    const uint32_t nt = blockDim.x, k = B.k, gtotal = B.gtotal, Su = (uint32_t)S;
+    for (uint32_t g = threadIdx.x; g < gtotal; g += nt) {
+        const uint32_t m = (uint32_t)batch_find(B.gstart, (int)k, (int)g);
+        const uint32_t j0 = (g - (uint32_t)B.gstart[m]) * kWalkGroup;
+        const uint32_t n = (uint32_t)B.cnt[m];
+        const uint32_t e0 = (uint32_t)B.row[m] * Su + j0;
+        uint32_t cur[kWalkGroup];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * nt;
-            rem[u] = 0;
-            cur[u] = 0;
-            slot[u] = 0;
-            src[u] = 0;
-            pos[u] = 0;
-            nextb[u] = 0;
-            weight[u] = 0;
-            gbytes[u] = tok_bytes;
-            if (i < wtotal) {
-                const uint32_t m = (uint32_t)batch_find(B.wstart, (int)k, (int)i);
-                pos[u] = i - (uint32_t)B.wstart[m];
-                const uint32_t e = (uint32_t)B.row[m] * Su + pos[u];
-                slot[u] = m;
-                cur[u] = T.img[e];
-                if (HASH) weight[u] = T.wsum[e];
-                rem[u] = B.len[m] > 0 ? (uint32_t)B.len[m] - 1u : 0u;
-                src[u] = (LDS_BYTES ? (uint32_t)B.boff[m] : 0u) + 1u;  // index of byte 1
-                if (!LDS_BYTES) gbytes[u] = tok_bytes + B.beg[m];
-                if (rem[u] > 0) nextb[u] = LDS_BYTES ? ldsb[src[u]] : gbytes[u][src[u]];
-                maxrem = max(maxrem, rem[u]);
-            }
-        }
-        for (uint32_t p = 0; p < maxrem; ++p) {
+        for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)T.img[e0 + u] : 0u;
+        const uint32_t rem = B.len[m] > 0 ? (uint32_t)B.len[m] - 1u : 0u;
+        const uint32_t lsrc = (uint32_t)B.boff[m] + 1u;                               // byte 1 in ldsb
+        const uint8_t *gsrc = LDS_BYTES ? tok_bytes : tok_bytes + B.beg[m] + 1;       // or in memory
+        uint32_t nextb = 0;
+        if (rem > 0) nextb = LDS_BYTES ? ldsb[lsrc] : gsrc[0];
+        for (uint32_t p = 0; p < rem; ++p) {
+            const uint32_t b = nextb;
+            if (p + 1 < rem) nextb = LDS_BYTES ? ldsb[lsrc + p + 1] : gsrc[(size_t)p + 1];
+            const uint16_t *col = tab + b * Su;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (p < rem[u]) {
-                    const uint32_t b = nextb[u];
-                    if (p + 1 < rem[u])
-                        nextb[u] = LDS_BYTES ? ldsb[src[u] + p + 1] : gbytes[u][(size_t)src[u] + p + 1];
-                    cur[u] = tab[b * Su + cur[u]];
-                }
-            }
+            for (int u = 0; u < kWalkGroup; ++u) cur[u] = col[cur[u]];
         }
+        uint64_t term = 0;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * nt;
-            if (i < wtotal) {
-                w[i] = (uint16_t)cur[u];
-                // slot m of the batch is token (first token of the batch) + m
-                if (keep && pos[u] < keep_stride)
-                    keep[(size_t)slot[u] * keep_stride + pos[u]] = (uint16_t)cur[u];
-                if (HASH)
-                    atomicAdd(&B.hash[slot[u]], (unsigned long long)(weight[u] * (uint64_t)cur[u]));
-            }
+        for (int u = 0; u < kWalkGroup; ++u) {
+            if (j0 + u >= n) cur[u] = 0;  // padding
+            else if (HASH) term += T.wsum[e0 + u] * (uint64_t)cur[u];
         }
+        uint16_t *dst = w + (uint32_t)B.wstart[m] + j0;
+#pragma unroll
+        for (int u = 0; u < kWalkGroup; ++u) dst[u] = (uint16_t)cur[u];
+        if (keep && j0 < keep_stride) {
+            uint16_t *kd = keep + (size_t)m * keep_stride + j0;
+#pragma unroll
+            for (int u = 0; u < kWalkGroup; ++u) kd[u] = (uint16_t)cur[u];
+        }
+        if (HASH) atomicAdd(&B.hash[m], (unsigned long long)term);
     }
 }
 
-// `keep` (or null): where slot 0's walk vector is kept, slot m's follows keep_stride entries on.
-template <int U, bool HASH>
+template <bool HASH>
 __device__ __forceinline__ void batch_walk(const Tables &T, const uint16_t *tab, int S,
                                            const uint8_t *__restrict__ tok_bytes, Batch &B,
                                            const uint8_t *ldsb, uint16_t *w, uint16_t *keep = nullptr,
                                            uint32_t keep_stride = 0) {
-    if (B.bytes_in_lds)
-        batch_walk_impl<U, true, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
-    else
-        batch_walk_impl<1, false, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
+    if (B.bytes_in_lds) batch_walk_impl<true, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
+    else batch_walk_impl<false, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
 }
 
 }  // namespace cfgzip
