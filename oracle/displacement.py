@@ -165,3 +165,137 @@ def right_linear_grammar(table, accepting: Iterable[int], reject: int = 0) -> Li
             if q2 in acc:
                 prods.append((q, a, ()))
     return prods
+
+
+# ---------------------------------------------------------------------------------------------
+# Bounded, level-by-level form of Algorithm 1 and the fixed-length encoding of its result.
+#
+# A library that computes displacements into fixed-size buffers has to bound what Algorithm 1
+# leaves unbounded.  This section states those bounds and the encoding once more, on the CPU:
+#   * symbols are integers 0 .. N-1 (N <= 4096), a production body has at most 4 of them;
+#   * a configuration is (input queue, output stack, A_prev); the frontier after p bytes is the
+#     SET of configurations Algorithm 1's recursion reaches at depth p;
+#   * the computation of a token OVERFLOWS when a successor would hold more than MAX_IN queue
+#     symbols or more than MAX_OUT stack symbols, when the successors of one frontier, counted
+#     with multiplicity (one per configuration and matching production), number more than
+#     MAX_FRONTIER, or when the encoded set does not fit a row;
+#   * an overflowing token is given a row and a hash that no other token has (it becomes a
+#     class of its own: a smaller compression, never a wrong one).
+# Without overflow the result is the set Algorithm 1 returns; the tests pin that.
+# ---------------------------------------------------------------------------------------------
+
+DISP_MAX_IN = 8
+DISP_MAX_OUT = 12
+DISP_MAX_FRONTIER = 128
+DISP_ROW_LEN = 256
+DISP_REC_LEN = 2 + DISP_MAX_IN + DISP_MAX_OUT   # padded record: ni, no, queue, stack
+DISP_OK = 0
+DISP_OVERFLOW = 1
+_M64 = (1 << 64) - 1
+
+
+def displacement_bounded(token: Sequence[int], productions: Sequence[Production], adjacency):
+    """Algorithm 1 taken one byte at a time over the set of live configurations.  Returns the
+    frozenset of (queue, stack) pairs, or None on overflow (see above).  `adjacency` is a set of
+    (Y, Z) pairs."""
+    by_terminal: Dict[int, List[Tuple[int, Stack]]] = defaultdict(list)
+    for A, a, beta in sorted(set((A, a, tuple(beta)) for (A, a, beta) in productions)):
+        by_terminal[a].append((A, beta))
+    frontier = {((), (), None)}
+    for ch in token:
+        successors = []
+        for (q, s, prev) in frontier:
+            if len(s) == 0:      # stack backtrack
+                for A, beta in by_terminal.get(ch, ()):
+                    if prev is None or (prev, A) in adjacency:
+                        successors.append((q + (A,), beta, A))
+            else:                # pop the top, push the body
+                for A, beta in by_terminal.get(ch, ()):
+                    if A == s[0]:
+                        successors.append((q, beta + s[1:], A))
+        if len(successors) > DISP_MAX_FRONTIER:
+            return None
+        for (q, s, _p) in successors:
+            if len(q) > DISP_MAX_IN or len(s) > DISP_MAX_OUT:
+                return None
+        frontier = set(successors)
+    return frozenset((q, s) for (q, s, _p) in frontier)
+
+
+def displacement_record(pair) -> List[int]:
+    q, s = pair
+    return ([len(q), len(s)] + list(q) + [0] * (DISP_MAX_IN - len(q))
+            + list(s) + [0] * (DISP_MAX_OUT - len(s)))
+
+
+def _mix_record(rec: Sequence[int], seed: int) -> int:
+    """FNV-1a style pass over the 16-bit entries, then the SplitMix64 finaliser."""
+    h = (seed ^ 0x9E3779B97F4A7C15) & _M64
+    for x in rec:
+        h = ((h ^ x) * 0x100000001B3) & _M64
+    h ^= h >> 30
+    h = (h * 0xBF58476D1CE4E5B9) & _M64
+    h ^= h >> 27
+    h = (h * 0x94D049BB133111EB) & _M64
+    h ^= h >> 31
+    return h
+
+
+def encode_displacement(pairs, token_id: int, seed: int):
+    """(row of DISP_ROW_LEN 16-bit values, 64-bit hash, status) of one token.
+    Row: [number of pairs, then per pair in ascending order of its padded record:
+    ni, no, queue symbols, stack symbols], zero filled.  Hash: the sum over pairs of
+    _mix_record(padded record).  Overflow: row [0xFFFF, id low 16, id high 16, 0 ..], hash the
+    mix of that row's first DISP_REC_LEN entries."""
+    row = None
+    if pairs is not None:
+        recs = sorted(displacement_record(p) for p in pairs)
+        flat = [len(recs)]
+        for r in recs:
+            flat += r[:2] + r[2:2 + r[0]] + r[2 + DISP_MAX_IN:2 + DISP_MAX_IN + r[1]]
+        if len(flat) <= DISP_ROW_LEN:
+            row = flat + [0] * (DISP_ROW_LEN - len(flat))
+            h = sum(_mix_record(r, seed) for r in recs) & _M64
+            return row, h, DISP_OK
+    row = [0xFFFF, token_id & 0xFFFF, (token_id >> 16) & 0xFFFF] + [0] * (DISP_ROW_LEN - 3)
+    return row, _mix_record(row[:DISP_REC_LEN], seed), DISP_OVERFLOW
+
+
+def decode_displacement(row: Sequence[int]):
+    """Inverse of encode_displacement for a row with status DISP_OK."""
+    n, pos, out = int(row[0]), 1, set()
+    for _ in range(n):
+        ni, no = int(row[pos]), int(row[pos + 1])
+        q = tuple(int(x) for x in row[pos + 2:pos + 2 + ni])
+        s = tuple(int(x) for x in row[pos + 2 + ni:pos + 2 + ni + no])
+        out.add((q, s))
+        pos += 2 + ni + no
+    return frozenset(out)
+
+
+def displacement_rows(tokens: Sequence[bytes], productions: Sequence[Production], seed: int,
+                      adjacency=None):
+    """Rows, hashes and status of a whole vocabulary: (uint16 [V][ROW], uint64 [V], int32 [V])."""
+    import numpy as np
+    if adjacency is None:
+        adjacency = stack_adjacency(productions)
+    V = len(tokens)
+    rows = np.zeros((V, DISP_ROW_LEN), np.uint16)
+    hashes = np.zeros(V, np.uint64)
+    status = np.zeros(V, np.int32)
+    for t, tok in enumerate(tokens):
+        r, h, st = encode_displacement(displacement_bounded(tuple(tok), productions, adjacency),
+                                       t, seed)
+        rows[t], hashes[t], status[t] = r, h, st
+    return rows, hashes, status
+
+
+def adjacency_bits(adjacency, N: int):
+    """The relation as a bit matrix: bit (Y & 31) of word [Z][Y >> 5] is set iff (Y, Z) is
+    stack-adjacent (rows indexed by the symbol consumed next)."""
+    import numpy as np
+    W = (N + 31) // 32
+    bits = np.zeros((N, W), np.uint32)
+    for (Y, Z) in adjacency:
+        bits[Z, Y >> 5] |= np.uint32(1 << (Y & 31))
+    return bits

@@ -1,0 +1,97 @@
+"""Seeded context-free grammars in Greibach normal form over bytes, as flat arrays.
+
+Every production is  A -> a B_1 .. B_n  with one terminal byte `a` and at most
+MAX_BODY non-terminals.  Non-terminals are numbered 0 .. N-1.  Productions are unique and
+sorted by (byte, head, body): the order in which the GPU library expects them.
+
+Nothing here parses anything or computes displacements: these are inputs only.
+"""
+
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+from .vocab import Vocab, vocab_from_tokens
+
+MAX_BODY = 4
+
+
+@dataclass
+class Grammar:
+    N: int                  # number of non-terminals
+    head: np.ndarray        # uint16 [P]
+    byte: np.ndarray        # uint8  [P]
+    length: np.ndarray      # uint8  [P]   body length 0..MAX_BODY
+    body: np.ndarray        # uint16 [P, MAX_BODY] (unused entries 0)
+
+    @property
+    def P(self) -> int:
+        return int(self.head.shape[0])
+
+    def productions(self) -> List[Tuple[int, int, Tuple[int, ...]]]:
+        """[(A, a, (B_1, .., B_n))] in the array order."""
+        return [(int(self.head[i]), int(self.byte[i]),
+                 tuple(int(x) for x in self.body[i, :int(self.length[i])])) for i in range(self.P)]
+
+
+def grammar_from_productions(N: int, prods: Sequence[Tuple[int, int, Sequence[int]]]) -> Grammar:
+    uniq = sorted({(int(a), int(A), tuple(int(x) for x in beta)) for (A, a, beta) in prods})
+    P = len(uniq)
+    g = Grammar(N=N, head=np.zeros(P, np.uint16), byte=np.zeros(P, np.uint8),
+                length=np.zeros(P, np.uint8), body=np.zeros((P, MAX_BODY), np.uint16))
+    for i, (a, A, beta) in enumerate(uniq):
+        assert 0 <= A < N and 0 <= a < 256 and len(beta) <= MAX_BODY and all(0 <= b < N for b in beta)
+        g.head[i], g.byte[i], g.length[i] = A, a, len(beta)
+        g.body[i, :len(beta)] = beta
+    return g
+
+
+def make_random_gnf(seed: int, n_nt: int, alphabet: bytes, n_prod: int, max_body: int = 3,
+                    unary_fraction: float = 0.35) -> Grammar:
+    """Random productions; every non-terminal gets at least one production without body (so
+    every symbol can be popped) and bodies of 1..max_body symbols otherwise."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    prods = set()
+    for A in range(n_nt):
+        prods.add((A, int(alphabet[rng.integers(len(alphabet))]), ()))
+    while len(prods) < n_prod:
+        A = int(rng.integers(n_nt))
+        a = int(alphabet[rng.integers(len(alphabet))])
+        k = 0 if rng.random() < unary_fraction else int(rng.integers(1, max_body + 1))
+        prods.add((A, a, tuple(int(x) for x in rng.integers(0, n_nt, size=k))))
+    return grammar_from_productions(n_nt, list(prods))
+
+
+def make_bracket_gnf(seed: int, n_atoms: int = 6) -> Tuple[Grammar, bytes]:
+    """A small expression language with nesting, already in Greibach normal form:
+        E -> atom | atom O | '(' E C | '(' E C O | '[' E D | '[' E D O
+        O -> op E            C -> ')'            D -> ']'
+    over atoms a.., two bracket kinds and a few operators; plus a list rule
+        E -> '{' E L         L -> ',' E L | '}' | '}' O
+    Non-terminals: E=0, O=1, C=2, D=3, L=4."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    E, O, C, D, L = range(5)
+    atoms = bytes(rng.choice(np.frombuffer(b"abcdefghijklmnopqrstuvwxyz0123456789", np.uint8),
+                             size=n_atoms, replace=False))
+    prods = []
+    for a in atoms:
+        prods += [(E, a, ()), (E, a, (O,))]
+    prods += [(E, ord("("), (E, C)), (E, ord("("), (E, C, O)), (E, ord("["), (E, D)),
+              (E, ord("["), (E, D, O)), (E, ord("{"), (E, L))]
+    for op in b"+-*":
+        prods.append((O, op, (E,)))
+    prods += [(C, ord(")"), ()), (D, ord("]"), ()), (L, ord(","), (E, L)), (L, ord("}"), ()),
+              (L, ord("}"), (O,))]
+    return grammar_from_productions(5, prods), atoms
+
+
+def make_token_strings(seed: int, V: int, alphabet: bytes, max_len: int) -> Vocab:
+    """V byte strings, length uniform on 1..max_len, bytes uniform over `alphabet`."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    alpha = np.frombuffer(alphabet, dtype=np.uint8)
+    toks = [bytes(alpha[rng.integers(0, len(alpha), size=int(rng.integers(1, max_len + 1)))])
+            for _ in range(V)]
+    return vocab_from_tokens(toks)

@@ -1,0 +1,190 @@
+"""Pins for the bounded, level-by-level form of Algorithm 1 and for the fixed-length row
+encoding of a displacement set (the form the GPU library is compared with).
+
+The bounded form is pinned against the recursive Algorithm 1 (itself pinned by Figure 3, by
+Appendix B's second formulation and by the right-linear special case), the overflow rules by
+grammars built to cross exactly one bound each, the encoding by decoding it again."""
+
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import displacement as D
+from synthetic_inputs.grammar import (grammar_from_productions, make_bracket_gnf, make_random_gnf,
+                                      make_token_strings)
+
+
+def _all_tokens(alphabet: bytes, max_len: int):
+    return [bytes(w) for n in range(0, max_len + 1) for w in itertools.product(alphabet, repeat=n)]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_bounded_form_equals_algorithm_1(seed):
+    g = make_random_gnf(100 + seed, n_nt=5, alphabet=b"abc", n_prod=16, max_body=3)
+    prods = g.productions()
+    adj = D.stack_adjacency(prods)
+    seen_backtrack = overflowed = 0
+    toks = _all_tokens(b"abc", 4)
+    for tok in toks:
+        want = D.displacement(tuple(tok), prods, adjacency=adj)
+        got = D.displacement_bounded(tuple(tok), prods, adj)
+        if got is None:      # a dense random grammar can cross the frontier bound
+            overflowed += 1
+            continue
+        assert got == want, tok
+        seen_backtrack += any(len(q) >= 2 for (q, _s) in want)
+    assert seen_backtrack > 0, "some token must need a second stack backtrack"
+    assert overflowed * 4 < len(toks)
+
+
+def test_bounded_form_on_figure_3():
+    from tests.test_oracle_displacement import _read_fig3
+    token, prods, _steps, res_i, res_o = _read_fig3()
+    names = sorted({p[0] for p in prods} | {b for p in prods for b in p[2]})
+    num = {n: i for i, n in enumerate(names)}
+    iprods = [(num[A], ord(a), tuple(num[b] for b in beta)) for (A, a, beta) in prods]
+    adj = D.stack_adjacency(iprods)
+    got = D.displacement_bounded(tuple(token.encode()), iprods, adj)
+    assert got == frozenset({(tuple(num[x] for x in res_i), tuple(num[x] for x in res_o))})
+
+
+def test_empty_token_and_dead_token():
+    g = make_random_gnf(3, n_nt=3, alphabet=b"ab", n_prod=6)
+    prods = g.productions()
+    adj = D.stack_adjacency(prods)
+    assert D.displacement_bounded((), prods, adj) == frozenset({((), ())})
+    assert D.displacement_bounded((ord("z"),), prods, adj) == frozenset()
+    row, h, st = D.encode_displacement(frozenset(), 5, seed=1)
+    assert st == D.DISP_OK and row == [0] * D.DISP_ROW_LEN and h == 0
+
+
+def test_overflow_of_the_input_queue():
+    # X -> x A A makes (A, A) stack-adjacent; A -> a.  "a" * k keeps backtracking into A.
+    prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ())]
+    adj = D.stack_adjacency(prods)
+    assert (1, 1) in adj
+    ok = D.displacement_bounded((ord("a"),) * D.DISP_MAX_IN, prods, adj)
+    assert ok == frozenset({((1,) * D.DISP_MAX_IN, ())})
+    assert D.displacement_bounded((ord("a"),) * (D.DISP_MAX_IN + 1), prods, adj) is None
+    # the unbounded algorithm goes on
+    assert D.displacement((ord("a"),) * (D.DISP_MAX_IN + 1), prods) == \
+        frozenset({((1,) * (D.DISP_MAX_IN + 1), ())})
+
+
+def test_overflow_of_the_output_stack():
+    prods = [(0, ord("a"), (0, 0, 0, 0))]   # each byte: pop one, push four
+    adj = D.stack_adjacency(prods)
+    for k in range(1, 6):
+        got = D.displacement_bounded((ord("a"),) * k, prods, adj)
+        depth = 4 + 3 * (k - 1)
+        if depth <= D.DISP_MAX_OUT:
+            assert got == frozenset({((0,), (0,) * depth)})
+        else:
+            assert got is None
+
+
+def test_overflow_of_the_frontier_counts_successors_with_multiplicity():
+    n = D.DISP_MAX_FRONTIER
+    prods = [(i, ord("a"), ()) for i in range(n)]
+    adj = D.stack_adjacency(prods)
+    got = D.displacement_bounded((ord("a"),), prods, adj)
+    assert got is not None and len(got) == n
+    prods.append((n, ord("a"), ()))
+    assert D.displacement_bounded((ord("a"),), prods, D.stack_adjacency(prods)) is None
+    # two configurations that fall together after the next byte still count twice:
+    # 65 heads A_i -> a B, then B -> b C | b D gives 130 successors but only 130 distinct... use
+    # heads that all keep the same queue: S -> s B (one config), B -> b X_i for 129 bodies
+    prods = [(0, ord("s"), (1,))] + [(1, ord("b"), (2 + i,)) for i in range(n + 1)]
+    assert D.displacement_bounded((ord("s"), ord("b")), prods, set()) is None
+    assert len(D.displacement((ord("s"), ord("b")), prods)) == n + 1
+
+
+def test_overflow_of_the_row():
+    # 100 pairs of 2 + 1 + 1 entries: 401 > 256 entries, though the frontier bound holds
+    prods = [(i, ord("a"), (0,)) for i in range(100)]
+    pairs = D.displacement_bounded((ord("a"),), prods, set())
+    assert pairs is not None and len(pairs) == 100
+    row, h, st = D.encode_displacement(pairs, 70000, seed=9)
+    assert st == D.DISP_OVERFLOW
+    assert row[:4] == [0xFFFF, 70000 & 0xFFFF, 70000 >> 16, 0] and len(row) == D.DISP_ROW_LEN
+    row2, h2, _ = D.encode_displacement(None, 70001, seed=9)
+    assert row2 != row and h2 != h
+    # the largest set that still fits: 63 pairs of 4 entries + the count = 253
+    row, _h, st = D.encode_displacement(frozenset(list(pairs)[:63]), 0, seed=9)
+    assert st == D.DISP_OK and row[0] == 63
+    _row, _h, st = D.encode_displacement(frozenset(list(pairs)[:64]), 0, seed=9)
+    assert st == D.DISP_OVERFLOW   # 1 + 64 * 4 = 257
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_encoding_round_trip_and_order_freedom(seed):
+    g = make_random_gnf(40 + seed, n_nt=5, alphabet=b"abc", n_prod=12, max_body=3)
+    prods = g.productions()
+    adj = D.stack_adjacency(prods)
+    rng = np.random.default_rng(seed)
+    rows = {}
+    checked = 0
+    for t, tok in enumerate(_all_tokens(b"abc", 4)):
+        pairs = D.displacement_bounded(tuple(tok), prods, adj)
+        row, h, st = D.encode_displacement(pairs, t, seed=77)
+        if st != D.DISP_OK:     # a large set of an ambiguous grammar
+            assert pairs is None or 1 + sum(2 + len(q) + len(o) for q, o in pairs) > D.DISP_ROW_LEN
+            continue
+        checked += 1
+        assert D.decode_displacement(row) == pairs
+        assert all(0 <= x < 65536 for x in row)
+        # a set has no order: any order of the same pairs encodes alike
+        shuffled = list(pairs)
+        rng.shuffle(shuffled)
+        assert D.encode_displacement(shuffled, t, seed=77)[:2] == (row, h)
+        # equal rows <=> equal sets, and then equal hashes
+        key = tuple(row)
+        if key in rows:
+            assert rows[key] == (pairs, h)
+        rows[key] = (pairs, h)
+    assert checked >= 100
+    by_set = {}
+    for key, (pairs, h) in rows.items():
+        assert pairs not in by_set
+        by_set[pairs] = key
+    hashes = [h for (_p, h) in rows.values()]
+    assert len(set(hashes)) == len(hashes), "distinct small sets should not collide"
+
+
+def test_hash_depends_on_seed_and_on_every_record_entry():
+    base = ((1, 2, 3), (4, 5))
+    h0 = D.encode_displacement([base], 0, seed=1)[1]
+    assert D.encode_displacement([base], 0, seed=2)[1] != h0
+    for variant in [((1, 2), (3, 4, 5)), ((1, 2, 3, 0), (4, 5)), ((1, 2, 3), (4, 5, 0)),
+                    ((3, 2, 1), (4, 5)), ((1, 2, 3), (5, 4))]:
+        assert D.encode_displacement([variant], 0, seed=1)[1] != h0
+    two = D.encode_displacement([base, ((), ())], 0, seed=1)[1]
+    assert two == (h0 + D.encode_displacement([((), ())], 0, seed=1)[1]) % (1 << 64)
+
+
+def test_rows_of_a_vocabulary_and_bracket_grammar_classes():
+    g, atoms = make_bracket_gnf(5)
+    prods = g.productions()
+    v = make_token_strings(6, 300, atoms + b"()[]{},+-*", 4)
+    toks = v.tokens()
+    rows, hashes, status = D.displacement_rows(toks, prods, seed=3)
+    assert rows.shape == (300, D.DISP_ROW_LEN) and rows.dtype == np.uint16
+    assert (status == D.DISP_OK).all()
+    adj = D.stack_adjacency(prods)
+    for t in range(0, 300, 7):
+        assert D.decode_displacement(rows[t]) == D.displacement(tuple(toks[t]), prods, adjacency=adj)
+    # two atoms are interchangeable everywhere, an atom and an operator are not
+    a0, a1 = bytes([atoms[0]]), bytes([atoms[1]])
+    r = D.displacement_rows([a0, a1, b"+", a0 + b"+" + a1, a1 + b"+" + a0, b"(" + a0, b"[" + a0],
+                            prods, seed=3)[0]
+    assert (r[0] == r[1]).all() and not (r[0] == r[2]).all()
+    assert (r[3] == r[4]).all() and not (r[5] == r[6]).all()
+
+
+def test_adjacency_bit_matrix_layout():
+    adj = {(3, 1), (40, 1), (0, 2)}
+    bits = D.adjacency_bits(adj, 41)
+    assert bits.shape == (41, 2)
+    assert bits[1, 0] == 1 << 3 and bits[1, 1] == 1 << 8 and bits[2, 0] == 1
+    assert int(bits.sum()) == (1 << 3) + (1 << 8) + 1
