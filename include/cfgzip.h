@@ -116,7 +116,10 @@ int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t 
  * signatures in `signatures_ws`; the rows of `sig`; or, with neither, signatures
  * recomputed from the automaton.
  *
- *   tok_bytes, tok_off, V, table, S   as for cfgzip_signatures
+ *   tok_bytes, tok_off, V, table, S   as for cfgzip_signatures.  `table` may be NULL when `sig`
+ *              is given and `signatures_ws` is NULL: the rows of `sig` are then the only source
+ *              and may be any fixed-length encoding in which equal rows mean equivalent tokens
+ *              (S = row length), e.g. the rows of cfgzip_displacements
  *   sig        uint16 [V][S] from cfgzip_signatures, or NULL
  *   hash       uint64 [V]    from cfgzip_signatures (or any function of the signature)
  *   signatures_ws  the workspace of a finished cfgzip_signatures call with the same
@@ -218,6 +221,59 @@ int cfgzip_class_masks(const int32_t *state_mask, int32_t S, int32_t C, const in
 int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
                           const int32_t *class_of_token, int32_t V, const int32_t *tok, int32_t B,
                           int32_t *states, void *stream);
+
+/*
+ * General case: grammars in Greibach normal form (paper Section 2.1), every production
+ *     A -> a B_1 .. B_n,   one terminal byte a, 0 <= n <= 4 non-terminals,
+ * non-terminals numbered 0 .. N-1, N <= 4096, given as flat arrays
+ *     prod_head uint16 [P], prod_byte uint8 [P], prod_len uint8 [P] (n), prod_body uint16 [P][4]
+ * in strictly ascending order of (byte, head, body), bodies compared symbol by symbol with a
+ * proper prefix first (so no production occurs twice).  The order and the value ranges are
+ * checked on the device; a grammar that breaks them is reported, not computed (below).
+ *
+ * cfgzip_stack_adjacency (paper Section 3.2.2, Appendix C): the relation "Y can be consumed
+ * right before Z":  for every production A -> a B_1 .. B_n Z beta with n >= 1, every Y that is
+ * reachable from B_n along right-most body symbols (B_n itself included) and has a production
+ * without body.
+ *     adj_out      int32 [N][W(N)]   bit Y of row Z <=> (Y, Z) stack-adjacent
+ *     invalid_out  int32 [1] or NULL 1 if the grammar broke a rule above (adj_out then
+ *                                    holds no result), else 0
+ *
+ * cfgzip_displacements (paper Section 3.2.1, Algorithm 1, with the backtrack restricted to
+ * stack-adjacent symbols): the displacement set of every token, i.e. the pairs (input queue,
+ * output stack) with which the token can be read by the one-state pushdown automaton of the
+ * grammar; the first backtrack may take any production of the first byte.  Each set is
+ * written as a row of CFGZIP_DISP_ROW 16-bit values so that equal sets give equal rows:
+ *     row[0] = number of pairs; then, per pair, in ascending order of the padded record
+ *     (ni, no, queue padded with 0 to 8, stack padded with 0 to 12; stack top first):
+ *     ni, no, the ni queue symbols, the no stack symbols; the rest of the row is 0.
+ * hash_out[t] is the sum over the pairs of a 64-bit mix of the padded record and hash_seed
+ * (a function of the set, for cfgzip_build_classes; never part of a result).
+ * Bounds: queue <= 8 symbols, stack <= 12, successors of all live configurations per byte
+ * <= 128 (counted before duplicates are dropped), row <= CFGZIP_DISP_ROW entries.  A token
+ * that crosses one gets status CFGZIP_DISP_OVERFLOW and a row no other token has
+ * (0xFFFF, id & 0xFFFF, id >> 16, 0 ..): it forms a class of its own.
+ *     rows_out    uint16 [V][CFGZIP_DISP_ROW], 8-byte aligned
+ *     hash_out    uint64 [V]
+ *     status_out  int32 [V] or NULL: CFGZIP_DISP_OK, CFGZIP_DISP_OVERFLOW, or
+ *                 CFGZIP_DISP_BAD_GRAMMAR for every token (rows and hashes then 0)
+ *     ws          cfgzip_displacements_workspace_bytes(N) bytes, 256-byte aligned (both calls)
+ * Grouping: cfgzip_build_classes(tok_bytes, tok_off, V, NULL, CFGZIP_DISP_ROW, rows, hash, NULL, ..).
+ */
+#define CFGZIP_DISP_ROW 256
+#define CFGZIP_DISP_OK 0
+#define CFGZIP_DISP_OVERFLOW 1
+#define CFGZIP_DISP_BAD_GRAMMAR 2
+size_t cfgzip_displacements_workspace_bytes(int32_t N);
+int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
+                           const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
+                           int32_t N, int32_t *adj_out, int32_t *invalid_out,
+                           void *ws, size_t ws_bytes, void *stream);
+int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                         const uint16_t *prod_head, const uint8_t *prod_byte,
+                         const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
+                         int32_t N, uint16_t *rows_out, uint64_t *hash_out, int32_t *status_out,
+                         uint64_t hash_seed, void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

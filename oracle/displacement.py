@@ -194,13 +194,22 @@ DISP_OVERFLOW = 1
 _M64 = (1 << 64) - 1
 
 
-def displacement_bounded(token: Sequence[int], productions: Sequence[Production], adjacency):
-    """Algorithm 1 taken one byte at a time over the set of live configurations.  Returns the
-    frozenset of (queue, stack) pairs, or None on overflow (see above).  `adjacency` is a set of
-    (Y, Z) pairs."""
+def index_productions(productions: Sequence[Production]):
+    """The distinct productions, by terminal and by (terminal, head)."""
     by_terminal: Dict[int, List[Tuple[int, Stack]]] = defaultdict(list)
+    by_pair: Dict[Tuple[int, int], List[Stack]] = defaultdict(list)
     for A, a, beta in sorted(set((A, a, tuple(beta)) for (A, a, beta) in productions)):
         by_terminal[a].append((A, beta))
+        by_pair[(a, A)].append(beta)
+    return by_terminal, by_pair
+
+
+def displacement_bounded(token: Sequence[int], productions: Sequence[Production], adjacency,
+                         index=None):
+    """Algorithm 1 taken one byte at a time over the set of live configurations.  Returns the
+    frozenset of (queue, stack) pairs, or None on overflow (see above).  `adjacency` is a set of
+    (Y, Z) pairs; `index` = index_productions(productions) if the caller has it already."""
+    by_terminal, by_pair = index if index is not None else index_productions(productions)
     frontier = {((), (), None)}
     for ch in token:
         successors = []
@@ -210,9 +219,8 @@ def displacement_bounded(token: Sequence[int], productions: Sequence[Production]
                     if prev is None or (prev, A) in adjacency:
                         successors.append((q + (A,), beta, A))
             else:                # pop the top, push the body
-                for A, beta in by_terminal.get(ch, ()):
-                    if A == s[0]:
-                        successors.append((q, beta + s[1:], A))
+                for beta in by_pair.get((ch, s[0]), ()):
+                    successors.append((q, beta + s[1:], s[0]))
         if len(successors) > DISP_MAX_FRONTIER:
             return None
         for (q, s, _p) in successors:
@@ -283,9 +291,10 @@ def displacement_rows(tokens: Sequence[bytes], productions: Sequence[Production]
     rows = np.zeros((V, DISP_ROW_LEN), np.uint16)
     hashes = np.zeros(V, np.uint64)
     status = np.zeros(V, np.int32)
+    index = index_productions(productions)
     for t, tok in enumerate(tokens):
-        r, h, st = encode_displacement(displacement_bounded(tuple(tok), productions, adjacency),
-                                       t, seed)
+        r, h, st = encode_displacement(
+            displacement_bounded(tuple(tok), productions, adjacency, index), t, seed)
         rows[t], hashes[t], status[t] = r, h, st
     return rows, hashes, status
 

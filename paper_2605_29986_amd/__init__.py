@@ -9,14 +9,20 @@ There is no CPU fallback: calling anything without the built library raises.
 
 from .binding import (  # noqa: F401
     CfgzipError,
+    DISP_BAD_GRAMMAR,
+    DISP_OK,
+    DISP_OVERFLOW,
+    DISP_ROW,
     DEFAULT_HASH_SEED,
     cfgzip_advance_states,
     cfgzip_apply_mask,
     cfgzip_build_classes,
     cfgzip_class_masks,
+    cfgzip_displacements,
     cfgzip_expand_mask,
     cfgzip_map_to_rep,
     cfgzip_signatures,
+    cfgzip_stack_adjacency,
     cfgzip_state_masks,
     cfgzip_version,
     library_path,

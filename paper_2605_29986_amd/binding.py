@@ -77,6 +77,13 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_class_masks.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.cfgzip_advance_states.restype = ctypes.c_int
     lib.cfgzip_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_displacements_workspace_bytes.restype = sz
+    lib.cfgzip_displacements_workspace_bytes.argtypes = [i32]
+    lib.cfgzip_stack_adjacency.restype = ctypes.c_int
+    lib.cfgzip_stack_adjacency.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.cfgzip_displacements.restype = ctypes.c_int
+    lib.cfgzip_displacements.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64,
+                                         vp, sz, vp]
     _lib = lib
     return lib
 
@@ -145,7 +152,8 @@ def cfgzip_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: tor
     return sig_out, hash_out
 
 
-def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: torch.Tensor,
+def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor,
+                         table: Optional[torch.Tensor],
                          sig: Optional[torch.Tensor], hash: torch.Tensor, *,
                          class_of_token: Optional[torch.Tensor] = None,
                          rep_of_class: Optional[torch.Tensor] = None,
@@ -154,10 +162,11 @@ def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: 
     """Returns (class_of_token int32 [V], rep_of_class int32 [C] (a view of the first C
     entries), C, collisions).  `signatures_workspace` is the untouched workspace tensor of the
     cfgzip_signatures call that produced `hash` (its compressed signatures are compared
-    instead of `sig` rows or a second walk)."""
+    instead of `sig` rows or a second walk).  With table=None the rows of `sig` (any row
+    length) are grouped as they are."""
     lib = load_library()
     V = tok_off.numel() - 1
-    S = table.shape[0]
+    S = table.shape[0] if table is not None else (sig.shape[1] if sig is not None else 0)
     dev = tok_off.device
     if class_of_token is None:
         class_of_token = torch.empty((V,), dtype=torch.int32, device=dev)
@@ -171,7 +180,7 @@ def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: 
     rc = lib.cfgzip_build_classes(
         _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
         _dev(tok_off, torch.int64, "tok_off"), V,
-        _dev(table, torch.uint16, "table"), S,
+        _dev(table, torch.uint16, "table") if table is not None else None, S,
         _dev(sig, torch.uint16, "sig") if sig is not None else None,
         _dev(hash, torch.int64, "hash"),
         _dev(signatures_workspace, torch.uint8, "signatures_workspace")
@@ -297,3 +306,56 @@ def cfgzip_advance_states(sig_rep: torch.Tensor, class_of_token: torch.Tensor, t
                                    tok.numel(), _dev(states, torch.int32, "states"), _stream(stream))
     _check("cfgzip_advance_states", rc)
     return states
+
+
+DISP_ROW = 256
+DISP_OK, DISP_OVERFLOW, DISP_BAD_GRAMMAR = 0, 1, 2
+
+
+def _grammar_args(prod_head, prod_byte, prod_len, prod_body):
+    P = prod_head.numel()
+    if prod_body.shape != (P, 4):
+        raise ValueError("prod_body must have shape [P, 4]")
+    return (_dev(prod_head, torch.uint16, "prod_head"), _dev(prod_byte, torch.uint8, "prod_byte"),
+            _dev(prod_len, torch.uint8, "prod_len"), _dev(prod_body, torch.uint16, "prod_body"), P)
+
+
+def cfgzip_stack_adjacency(prod_head: torch.Tensor, prod_byte: torch.Tensor,
+                           prod_len: torch.Tensor, prod_body: torch.Tensor, N: int, *,
+                           workspace: Optional[torch.Tensor] = None, stream=None):
+    """(adj int32 [N, W(N)], invalid int32 [1]): bit Y of row Z <=> (Y, Z) stack-adjacent."""
+    lib = load_library()
+    dev = prod_head.device
+    adj = torch.empty((N, words_for(N)), dtype=torch.int32, device=dev)
+    invalid = torch.empty((1,), dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(N), dev)
+    h, b, ln, bd, P = _grammar_args(prod_head, prod_byte, prod_len, prod_body)
+    rc = lib.cfgzip_stack_adjacency(h, b, ln, bd, P, N, adj.data_ptr(), invalid.data_ptr(),
+                                    workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _check("cfgzip_stack_adjacency", rc)
+    return adj, invalid
+
+
+def cfgzip_displacements(tok_bytes: torch.Tensor, tok_off: torch.Tensor, prod_head: torch.Tensor,
+                         prod_byte: torch.Tensor, prod_len: torch.Tensor, prod_body: torch.Tensor,
+                         N: int, *, hash_seed: int = DEFAULT_HASH_SEED,
+                         workspace: Optional[torch.Tensor] = None, stream=None):
+    """(rows uint16 [V, DISP_ROW], hash int64 [V] holding uint64 bit patterns, status int32 [V])."""
+    lib = load_library()
+    V = tok_off.numel() - 1
+    dev = tok_off.device
+    rows = torch.empty((V, DISP_ROW), dtype=torch.uint16, device=dev)
+    hashes = torch.empty((V,), dtype=torch.int64, device=dev)
+    status = torch.empty((V,), dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(N), dev)
+    h, b, ln, bd, P = _grammar_args(prod_head, prod_byte, prod_len, prod_body)
+    rc = lib.cfgzip_displacements(
+        _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
+        _dev(tok_off, torch.int64, "tok_off"), V, h, b, ln, bd, P, N,
+        rows.data_ptr(), hashes.data_ptr(), status.data_ptr(),
+        ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF),
+        workspace.data_ptr(), workspace.numel(), _stream(stream))
+    _check("cfgzip_displacements", rc)
+    return rows, hashes, status

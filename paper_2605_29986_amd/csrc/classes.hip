@@ -884,7 +884,9 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
                                     int32_t *rep_of_class, int32_t *num_classes_dev,
                                     int32_t *num_classes_host, int32_t *collisions_host, void *ws,
                                     size_t ws_bytes, void *stream_) {
-    if (!tok_off || !table || !hash || !class_of_token || !rep_of_class) return CFGZIP_E_INVALID;
+    if (!tok_off || !hash || !class_of_token || !rep_of_class) return CFGZIP_E_INVALID;
+    // without an automaton there is nothing to walk: the rows of `sig` are all there is
+    if (!table && (!sig || signatures_ws)) return CFGZIP_E_INVALID;
     if (V <= 0 || S <= 0 || S > 65536) return CFGZIP_E_INVALID;
     if (!aligned_to(tok_off, 8) || !aligned_to(hash, 8) || !aligned_to(sig, 2) ||
         !aligned_to(table, 2) || !aligned_to(class_of_token, 4) || !aligned_to(rep_of_class, 4))

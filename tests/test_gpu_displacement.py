@@ -1,0 +1,228 @@
+"""GPU parity, general case: cfgzip_stack_adjacency (Appendix C) and cfgzip_displacements
+(Algorithm 1) against the CPU oracle, bit for bit (relation, rows, hashes, status), and the
+classes cfgzip_build_classes forms from the rows against the oracle's grouping and, for
+right-linear grammars, against the byte-walk classes."""
+
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import synthetic_inputs as si
+from oracle import displacement as D
+from synthetic_inputs.grammar import (Grammar, grammar_from_productions, make_bracket_gnf,
+                                      make_random_gnf, make_token_strings)
+from synthetic_inputs.vocab import vocab_from_tokens
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SEED = 0x5EED
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_29986_amd as p
+    p.load_library()
+    return p
+
+
+def _grammar_dev(g: Grammar):
+    from gpu_util import dev
+    return dev(g.head), dev(g.byte), dev(g.length), dev(g.body)
+
+
+def _check_adjacency(lib, g: Grammar):
+    prods = g.productions()
+    want = D.adjacency_bits(D.stack_adjacency(prods), g.N)
+    adj, invalid = lib.cfgzip_stack_adjacency(*_grammar_dev(g), g.N)
+    assert int(invalid.item()) == 0
+    assert (adj.cpu().numpy().view(np.uint32) == want).all()
+
+
+def _check_rows(lib, g: Grammar, vocab, expect_overflow=None):
+    from gpu_util import dev, hash_np
+    prods = g.productions()
+    toks = vocab.tokens()
+    want_rows, want_hash, want_status = D.displacement_rows(toks, prods, seed=SEED)
+    rows, hashes, status = lib.cfgzip_displacements(dev(vocab.tok_bytes), dev(vocab.tok_off),
+                                                    *_grammar_dev(g), g.N, hash_seed=SEED)
+    got_status = status.cpu().numpy()
+    got_rows = rows.cpu().numpy()
+    bad = np.nonzero(got_status != want_status)[0]
+    assert bad.size == 0, (bad[:5], [toks[i] for i in bad[:5]])
+    bad = np.nonzero((got_rows != want_rows).any(axis=1))[0]
+    assert bad.size == 0, (bad[:5], [toks[i] for i in bad[:5]], got_rows[bad[0]][:24],
+                           want_rows[bad[0]][:24])
+    assert (hash_np(hashes) == want_hash).all()
+    if expect_overflow is not None:
+        assert bool((want_status == D.DISP_OVERFLOW).any()) == expect_overflow
+    # grouping the rows: the library's classes against the oracle's
+    c, r, C, _coll = lib.cfgzip_build_classes(dev(vocab.tok_bytes), dev(vocab.tok_off), None, rows,
+                                              hashes)
+    want_c, want_r = oracle.build_classes(want_rows, vocab.tok_off)
+    assert C == len(want_r)
+    assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+    return want_rows, want_status, want_c
+
+
+def _all_tokens(alphabet: bytes, max_len: int):
+    return vocab_from_tokens([bytes(w) for n in range(0, max_len + 1)
+                              for w in itertools.product(alphabet, repeat=n)])
+
+
+def _figure3_grammar():
+    from test_oracle_displacement import _read_fig3
+    token, prods, _steps, res_i, res_o = _read_fig3()
+    names = sorted({p[0] for p in prods} | {b for p in prods for b in p[2]})
+    num = {n: i for i, n in enumerate(names)}
+    g = grammar_from_productions(len(names), [(num[A], ord(a), tuple(num[b] for b in beta))
+                                              for (A, a, beta) in prods])
+    return g, token.encode(), tuple(num[x] for x in res_i), tuple(num[x] for x in res_o)
+
+
+def test_figure_3(lib):
+    print("case figure 3", flush=True)
+    g, token, res_i, res_o = _figure3_grammar()
+    _check_adjacency(lib, g)
+    vocab = vocab_from_tokens([token[:n] for n in range(len(token) + 1)] + [b"xyz", b"zz", b"abx"])
+    rows, status, _c = _check_rows(lib, g, vocab, expect_overflow=False)
+    assert D.decode_displacement(rows[len(token)]) == frozenset({(res_i, res_o)})
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_grammars_every_short_token(lib, seed):
+    print(f"case random grammar seed={seed}", flush=True)
+    g = make_random_gnf(300 + seed, n_nt=5 + seed, alphabet=b"abc", n_prod=12 + 3 * seed, max_body=3)
+    _check_adjacency(lib, g)
+    _check_rows(lib, g, _all_tokens(b"abc", 5))
+
+
+@pytest.mark.parametrize("n_nt,n_prod,max_body", [(1, 3, 2), (33, 120, 4), (64, 300, 4), (65, 500, 3),
+                                                  (700, 3000, 4), (4096, 9000, 4)])
+def test_adjacency_sizes(lib, n_nt, n_prod, max_body):
+    print(f"case adjacency N={n_nt} P={n_prod}", flush=True)
+    g = make_random_gnf(n_nt * 3 + 1, n_nt=n_nt, alphabet=bytes(range(97, 123)), n_prod=max(n_prod, n_nt + 1),
+                        max_body=max_body)
+    _check_adjacency(lib, g)
+
+
+def test_chain_of_right_most_symbols_needs_every_closure_round(lib):
+    """A_0 -> a A_1, A_1 -> a A_2, .., A_k -> a (unary only at the end of the chain), and
+    S -> s A_0 Z: (A_k, Z) is found only by following all k edges."""
+    print("case closure chain", flush=True)
+    k = 200
+    prods = [(i, ord("a"), (i + 1,)) for i in range(k)] + [(k, ord("a"), ())]
+    prods += [(k + 1, ord("s"), (0, k + 2)), (k + 2, ord("z"), ())]
+    g = grammar_from_productions(k + 3, prods)
+    assert D.stack_adjacency(g.productions()) == {(k, k + 2)}
+    _check_adjacency(lib, g)
+
+
+def test_bracket_grammar_vocabulary(lib):
+    print("case bracket grammar", flush=True)
+    g, atoms = make_bracket_gnf(5)
+    _check_adjacency(lib, g)
+    vocab = make_token_strings(6, 5000, atoms + b"()[]{},+-*", 6)
+    rows, status, c = _check_rows(lib, g, vocab)
+    assert (status == D.DISP_OK).mean() > 0.99
+    assert len(set(c.tolist())) < 0.5 * vocab.V, "an expression grammar compresses"
+
+
+def test_each_bound_overflows_alone(lib):
+    print("case overflow bounds", flush=True)
+    a = ord("a")
+    # input queue
+    g = grammar_from_productions(2, [(0, ord("x"), (1, 1)), (1, a, ())])
+    _check_adjacency(lib, g)
+    _check_rows(lib, g, vocab_from_tokens([b"a" * n for n in range(0, 12)]), expect_overflow=True)
+    # output stack
+    g = grammar_from_productions(1, [(0, a, (0, 0, 0, 0))])
+    _check_rows(lib, g, vocab_from_tokens([b"a" * n for n in range(0, 7)]), expect_overflow=True)
+    # successors per byte: exactly at the bound, one above, and counted with multiplicity
+    n = D.DISP_MAX_FRONTIER
+    g = grammar_from_productions(n, [(i, a, ()) for i in range(n)])
+    _check_rows(lib, g, vocab_from_tokens([b"a", b"aa"]))
+    g = grammar_from_productions(n + 1, [(i, a, ()) for i in range(n + 1)])
+    _check_rows(lib, g, vocab_from_tokens([b"a", b"b", b""]), expect_overflow=True)
+    g = grammar_from_productions(n + 3, [(0, ord("s"), (1,))] + [(1, ord("b"), (2 + i,)) for i in range(n + 1)])
+    _check_rows(lib, g, vocab_from_tokens([b"s", b"sb", b"b"]), expect_overflow=True)
+    # row length: 63 pairs fit, 64 do not
+    for heads in (63, 64, 100):
+        g = grammar_from_productions(heads, [(i, a, (0,)) for i in range(heads)])
+        _check_rows(lib, g, vocab_from_tokens([b"a"]), expect_overflow=heads > 63)
+
+
+def test_long_stacks_and_queues_at_their_bounds(lib):
+    print("case bounds reached", flush=True)
+    # queue of exactly 8 with stacks, deep stack of exactly 12
+    prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ()), (1, ord("b"), (2, 2, 2, 2)),
+             (2, ord("c"), (2, 2, 2)), (2, ord("d"), ())]
+    g = grammar_from_productions(3, prods)
+    toks = [b"a" * 7 + b"b", b"a" * 7 + b"bc", b"a" * 7 + b"bcc", b"a" * 7 + b"bccc", b"a" * 7 + b"bccd",
+            b"bccdddd", b"a" * 8 + b"b", b"bdddd", b"bddddd", b"a" * 7 + b"bcccc", b"a" * 7 + b"bccccc"]
+    rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks))
+    assert status.tolist() == [0, 0, 0, 0, 0, 0, 1, 0, 0, 0, 1]
+    assert D.decode_displacement(rows[1]) == frozenset({((1,) * 8, (2,) * 6)})
+    assert D.decode_displacement(rows[9]) == frozenset({((1,) * 8, (2,) * 12)})
+
+
+def test_right_linear_grammar_gives_the_byte_walk_classes(lib, cfg1):
+    """Config 1's automaton as a right-linear grammar: displacement classes == walk classes."""
+    print("case right-linear config 1", flush=True)
+    from gpu_util import dev, vocab_dev
+    table, vocab = cfg1["table"], cfg1["vocab"]
+    S = table.shape[0]
+    accepting = [q for q in range(1, S) if q % 3 == 1]
+    g = grammar_from_productions(S, D.right_linear_grammar(table, accepting))
+    _check_adjacency(lib, g)
+    _rows, status, c_disp = _check_rows(lib, g, vocab, expect_overflow=False)
+    tb, to, tt = vocab_dev(vocab, table)
+    sig, h = lib.cfgzip_signatures(tb, to, tt)
+    c_walk, _r, _C, _ = lib.cfgzip_build_classes(tb, to, tt, sig, h)
+    assert (c_walk.cpu().numpy() == c_disp).all()
+
+
+def test_unsorted_or_out_of_range_grammar_is_reported(lib):
+    print("case bad grammar", flush=True)
+    from gpu_util import dev
+    g = make_random_gnf(9, n_nt=6, alphabet=b"ab", n_prod=14)
+    vocab = _all_tokens(b"ab", 3)
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+
+    def run(gr, N):
+        rows, hashes, status = lib.cfgzip_displacements(tb, to, *_grammar_dev(gr), N)
+        _adj, invalid = lib.cfgzip_stack_adjacency(*_grammar_dev(gr), N)
+        return rows.cpu().numpy(), status.cpu().numpy(), int(invalid.item())
+
+    rows, status, invalid = run(g, g.N)
+    assert invalid == 0 and (status != 2).all()
+    swapped = Grammar(g.N, g.head.copy(), g.byte.copy(), g.length.copy(), g.body.copy())
+    for arr in (swapped.head, swapped.byte, swapped.length, swapped.body):
+        arr[[3, 4]] = arr[[4, 3]]
+    rows, status, invalid = run(swapped, g.N)
+    assert invalid == 1 and (status == 2).all() and (rows == 0).all()
+    twice = Grammar(g.N, np.repeat(g.head, 2), np.repeat(g.byte, 2), np.repeat(g.length, 2),
+                    np.repeat(g.body, 2, axis=0))
+    assert run(twice, g.N)[2] == 1
+    rows, status, invalid = run(g, int(g.head.max()))        # a head >= N
+    assert invalid == 1 and (status == 2).all()
+    long_body = Grammar(g.N, g.head.copy(), g.byte.copy(), g.length.copy(), g.body.copy())
+    long_body.length[0] = 5
+    assert run(long_body, g.N)[2] == 1
+
+
+def test_argument_errors(lib):
+    from gpu_util import dev
+    g = make_random_gnf(9, n_nt=6, alphabet=b"ab", n_prod=14)
+    vocab = _all_tokens(b"ab", 2)
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+    with pytest.raises(lib.CfgzipError):
+        lib.cfgzip_displacements(tb, to, *_grammar_dev(g), 5000)
+    with pytest.raises(lib.CfgzipError):
+        lib.cfgzip_displacements(tb, to, *_grammar_dev(g), g.N,
+                                 workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(lib.CfgzipError):   # no automaton and no rows
+        lib.cfgzip_build_classes(tb, to, None, None, torch.zeros(vocab.V, dtype=torch.int64, device="cuda"))
