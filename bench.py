@@ -152,6 +152,75 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
     return out
 
 
+def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
+    """General case: displacement sets of config 3's vocabulary over the JSON grammar in
+    Greibach normal form, then the classes from the rows.  cpu_sample > 0 also times the
+    oracle (pure Python, one core) on that many leading tokens."""
+    import synthetic_inputs as si
+    from synthetic_inputs.grammar import make_json_gnf
+    g = make_json_gnf()
+    vocab = si.make_config(3)["vocab"]
+    V = vocab.V
+    stream = torch.cuda.current_stream()
+    tb = torch.from_numpy(vocab.tok_bytes).cuda()
+    to = torch.from_numpy(vocab.tok_off).cuda()
+    gd = [torch.from_numpy(x).cuda() for x in (g.head, g.byte, g.length, g.body)]
+    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(g.N), dtype=torch.uint8, device="cuda")
+    ws_bld = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, lib_mod.DISP_ROW), dtype=torch.uint8,
+                         device="cuda")
+    c = torch.empty((V,), dtype=torch.int32, device="cuda")
+    r = torch.empty((V,), dtype=torch.int32, device="cuda")
+    res = {}
+
+    def run_adj():
+        lib_mod.cfgzip_stack_adjacency(*gd, g.N, workspace=ws)
+
+    def run_disp():
+        res["rows"] = lib_mod.cfgzip_displacements(tb, to, *gd, g.N, workspace=ws)
+
+    def run_build():
+        rows, hashes, _st = res["rows"]
+        res["cls"] = lib_mod.cfgzip_build_classes(tb, to, None, rows, hashes, class_of_token=c,
+                                                  rep_of_class=r, workspace=ws_bld)
+
+    run_adj(); run_disp(); run_build(); torch.cuda.synchronize()
+    t_adj, t_disp, t_all = [], [], []
+    for _ in range(repeats):
+        t_adj.append(event_ms(run_adj, stream))
+        t_disp.append(event_ms(run_disp, stream))
+        t_all.append(event_ms(lambda: (run_disp(), run_build()), stream))
+    status = res["rows"][2].cpu().numpy()
+    C = res["cls"][2]
+    ms_all = min(t_all)
+    out = {
+        "workload": "JSON grammar in Greibach normal form (%d non-terminals, %d productions) x "
+                    "config 3 vocabulary" % (g.N, g.P),
+        "V": V, "N": g.N, "P": g.P, "C": C, "V_over_C": round(V / C, 2),
+        "overflow_tokens": int((status == lib_mod.DISP_OVERFLOW).sum()),
+        "ms_stack_adjacency": round(min(t_adj), 4),
+        "ms_displacements": round(min(t_disp), 4),     # adjacency included
+        "ms_total_with_classes": round(ms_all, 4),
+        "tokens_per_s": V / (ms_all * 1e-3),
+        "token_bytes_per_s": int(vocab.tok_off[-1]) / (min(t_disp) * 1e-3),
+    }
+    log(f"displacement: V={V} N={g.N} P={g.P} C={C} overflow={out['overflow_tokens']} adjacency "
+        f"{min(t_adj):.3f} ms, displacements {min(t_disp):.3f} ms, with classes {ms_all:.3f} ms")
+    if cpu_sample > 0:
+        from oracle import displacement as D
+        import oracle
+        n = min(cpu_sample, V)
+        toks = vocab.tokens()[:n]
+        prods = g.productions()
+        t0 = time.perf_counter()
+        rows, _h, _st = D.displacement_rows(toks, prods, seed=1)
+        oracle.build_classes(rows, vocab.tok_off[:n + 1])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {n} tokens of the same vocabulary, same grammar "
+                                         "(adjacency, bounded Algorithm 1, row encoding, grouping)"}
+    return out
+
+
 def cpu_baseline_decode(c5, r5, d, budget_s: float = 10.0, max_steps: int = 2000):
     """The oracle's decode step (expand, apply, map) on full-size steps, timed on the host."""
     import oracle
@@ -202,6 +271,8 @@ def main() -> int:
     ap.add_argument("--build-configs", type=str, default="2,3,4")
     ap.add_argument("--build-repeats", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-displacement", action="store_true",
+                    help="skip the general-case (grammar) pre-computation workload")
     ap.add_argument("--mask-variants", action="store_true",
                     help="also time the other forms of the mask path at the same shape")
     args = ap.parse_args()
@@ -419,6 +490,9 @@ def main() -> int:
         "class_build": class_build,
         "engine": engine,
     }
+    if not args.no_displacement:
+        result["displacement"] = bench_displacement(lib_mod, raw, torch, args.build_repeats,
+                                                    0 if args.no_cpu_baseline else 30000)
     if mask_variants:
         result["mask_variants"] = mask_variants
     if not args.no_cpu_baseline:

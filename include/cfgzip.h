@@ -227,6 +227,7 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
  *     A -> a B_1 .. B_n,   one terminal byte a, 0 <= n <= 4 non-terminals,
  * non-terminals numbered 0 .. N-1, N <= 4096, given as flat arrays
  *     prod_head uint16 [P], prod_byte uint8 [P], prod_len uint8 [P] (n), prod_body uint16 [P][4]
+ *     (prod_body 8-byte aligned)
  * in strictly ascending order of (byte, head, body), bodies compared symbol by symbol with a
  * proper prefix first (so no production occurs twice).  The order and the value ranges are
  * checked on the device; a grammar that breaks them is reported, not computed (below).

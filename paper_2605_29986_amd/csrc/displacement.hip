@@ -33,11 +33,22 @@ constexpr int kMaxOut = 12;
 constexpr int kMaxFrontier = 128;
 constexpr int kRowLen = 256;
 constexpr int kRecLen = 2 + kMaxIn + kMaxOut;  // ni, no, queue, stack
-constexpr int kPrevAt = kRecLen;               // symbol consumed last, kNone before any
-constexpr int kRecStride = 26;                 // uint16 per record in LDS: 13 words, odd
-constexpr int kRecWords = kRecStride / 2;
+constexpr int kPrevAt = kRecLen;               // symbol consumed last, "none" before any
 constexpr int kMaxSymbols = 4096;
-constexpr uint16_t kNone = 0xFFFF;
+constexpr int kMaxByteSymbols = 255;           // up to here a symbol (and "none") fits a byte
+
+// A record in LDS: kRecLen entries, the symbol consumed last, zero padding up to an odd number
+// of 32-bit words (lanes that read one record each then hit different banks).  Grammars with
+// at most kMaxByteSymbols symbols use byte entries: half the LDS per token, twice the waves
+// per compute unit.
+template <typename Sym>
+struct Rec {
+    static constexpr int kStride = sizeof(Sym) == 1 ? 28 : 26;  // entries: 7 or 13 words
+    static constexpr int kWords = kStride * (int)sizeof(Sym) / 4;
+    static constexpr int kOrderWords = (kRecLen * (int)sizeof(Sym) + 3) / 4;
+    static constexpr int kBits = 8 * (int)sizeof(Sym);
+    static constexpr int kNone = (1 << kBits) - 1;
+};
 
 constexpr int kStatusOk = 0;
 constexpr int kStatusOverflow = 1;
@@ -62,6 +73,7 @@ struct GrammarWorkspace {
     uint32_t *unary;    // [W]: symbols with a production without body
     uint32_t *reach[2]; // [N][W]: reachability over "right-most body symbol" edges
     uint32_t *adj;      // [N][W]: bit Y of row Z <=> (Y, Z) stack-adjacent
+    int32_t *pair_first;  // [256][N]: 1 + index of the first production with (terminal, head), 0 = none
     size_t clear_words; // words from hdr to the end that start at zero
     size_t bytes;
 };
@@ -80,6 +92,7 @@ GrammarWorkspace carve_grammar_ws(void *ws, int N) {
     g.unary = reinterpret_cast<uint32_t *>(take(W * 4));
     g.reach[0] = reinterpret_cast<uint32_t *>(take((size_t)N * W * 4));
     g.adj = reinterpret_cast<uint32_t *>(take((size_t)N * W * 4));
+    g.pair_first = reinterpret_cast<int32_t *>(take((size_t)256 * N * 4));
     g.clear_words = off / 4;
     g.reach[1] = reinterpret_cast<uint32_t *>(take((size_t)N * W * 4));  // fully written
     g.bytes = off;
@@ -128,6 +141,7 @@ __global__ void grammar_index_kernel(Grammar g, GrammarWorkspace w) {
     if (i == g.P - 1)
         for (int x = b + 1; x <= 256; ++x) w.byte_off[x] = g.P;
     const int A = g.head[i];
+    if (i == 0 || g.byte[i - 1] != b || g.head[i - 1] != A) w.pair_first[(size_t)b * g.N + A] = i + 1;
     if (len == 0) {
         atomicOr(&w.unary[A >> 5], 1u << (A & 31));
     } else {
@@ -208,6 +222,7 @@ struct DisplacementArgs {
     Grammar g;
     const GrammarHeader *hdr;
     const int32_t *byte_off;
+    const int32_t *pair_first;
     const uint32_t *adj;
     const uint8_t *tok_bytes;
     const int64_t *tok_off;
@@ -217,7 +232,8 @@ struct DisplacementArgs {
     uint64_t seed;
 };
 
-__device__ inline uint64_t mix_record(const uint16_t *rec, uint64_t seed) {
+template <typename Sym>
+__device__ inline uint64_t mix_record(const Sym *rec, uint64_t seed) {
     uint64_t h = seed ^ 0x9E3779B97F4A7C15ull;
     for (int k = 0; k < kRecLen; ++k) h = (h ^ rec[k]) * 0x100000001B3ull;
     h ^= h >> 30;
@@ -228,19 +244,24 @@ __device__ inline uint64_t mix_record(const uint16_t *rec, uint64_t seed) {
     return h;
 }
 
+template <typename Sym>
 __device__ inline bool records_equal(const uint32_t *a, const uint32_t *b) {
-    for (int k = 0; k < kRecWords; ++k)
+    for (int k = 0; k < Rec<Sym>::kWords; ++k)
         if (a[k] != b[k]) return false;
     return true;
 }
 
-// ascending order of the 16-bit entries (entry 2k is the low half of word k)
+// ascending order of the entries: in the first word that differs, the lowest entry that
+// differs decides (entry e of a word sits at bits e * kBits and up).  Called once the symbol
+// consumed last has been cleared, so the words beyond entry kRecLen - 1 are equal.
+template <typename Sym>
 __device__ inline bool record_less(const uint32_t *a, const uint32_t *b) {
-    for (int k = 0; k < kRecLen / 2; ++k) {
+    for (int k = 0; k < Rec<Sym>::kOrderWords; ++k) {
         const uint32_t x = a[k], y = b[k];
         if (x != y) {
-            if ((x ^ y) & 0xFFFFu) return (x & 0xFFFFu) < (y & 0xFFFFu);
-            return x < y;
+            const int shift = (__ffs(x ^ y) - 1) & ~(Rec<Sym>::kBits - 1);
+            const uint32_t mask = (uint32_t)Rec<Sym>::kNone;
+            return ((x >> shift) & mask) < ((y >> shift) & mask);
         }
     }
     return false;
@@ -248,7 +269,8 @@ __device__ inline bool record_less(const uint32_t *a, const uint32_t *b) {
 
 // Drops every record of src[0..m) that equals an earlier one and packs the rest into dst;
 // returns how many are left.  Called by the whole wave; m <= kMaxFrontier.
-__device__ int drop_duplicates(const uint16_t (*src)[kRecStride], uint16_t (*dst)[kRecStride],
+template <typename Sym>
+__device__ int drop_duplicates(const Sym (*src)[Rec<Sym>::kStride], Sym (*dst)[Rec<Sym>::kStride],
                                int m, int lane) {
     int kept = 0;
     for (int base = 0; base < kMaxFrontier; base += 64) {
@@ -257,7 +279,7 @@ __device__ int drop_duplicates(const uint16_t (*src)[kRecStride], uint16_t (*dst
         if (keep) {
             const uint32_t *mine = reinterpret_cast<const uint32_t *>(src[i]);
             for (int j = 0; j < i; ++j)
-                if (records_equal(mine, reinterpret_cast<const uint32_t *>(src[j]))) {
+                if (records_equal<Sym>(mine, reinterpret_cast<const uint32_t *>(src[j]))) {
                     keep = false;
                     break;
                 }
@@ -267,15 +289,18 @@ __device__ int drop_duplicates(const uint16_t (*src)[kRecStride], uint16_t (*dst
             const int pos = kept + __popcll(mask & ((1ull << lane) - 1ull));
             const uint32_t *s = reinterpret_cast<const uint32_t *>(src[i]);
             uint32_t *d = reinterpret_cast<uint32_t *>(dst[pos]);
-            for (int k = 0; k < kRecWords; ++k) d[k] = s[k];
+            for (int k = 0; k < Rec<Sym>::kWords; ++k) d[k] = s[k];
         }
         kept += __popcll(mask);
     }
     return kept;
 }
 
+template <typename Sym>
 __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
-    __shared__ __align__(8) uint16_t buf[2][kMaxFrontier][kRecStride];
+    constexpr int kRecStride = Rec<Sym>::kStride;
+    constexpr int kNone = Rec<Sym>::kNone;
+    __shared__ __align__(8) Sym buf[2][kMaxFrontier][kRecStride];
     __shared__ __align__(8) uint16_t row[kRowLen];
     __shared__ int n_emit, crossed, total_len;
     __shared__ unsigned long long hash_sum;
@@ -294,7 +319,7 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
     const int64_t b0 = a.tok_off[t], b1 = a.tok_off[t + 1];
 
     // the start configuration: nothing consumed, nothing pushed
-    if (lane < kRecStride) buf[0][0][lane] = lane == kPrevAt ? kNone : 0;
+    if (lane < kRecStride) buf[0][0][lane] = (Sym)(lane == kPrevAt ? kNone : 0);
     if (lane == 0) crossed = 0;
     int n = 1, cur = 0;
     bool overflow = false;
@@ -305,44 +330,44 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
         const int lo = a.byte_off[ch], hi = a.byte_off[ch + 1];
         if (lane == 0) n_emit = 0;
         __syncthreads();
-        uint16_t(*src)[kRecStride] = buf[cur];
-        uint16_t(*dst)[kRecStride] = buf[cur ^ 1];
+        Sym(*src)[kRecStride] = buf[cur];
+        Sym(*dst)[kRecStride] = buf[cur ^ 1];
 
         // pops: a lane per configuration (few productions per (terminal, head))
         for (int c = lane; c < n; c += 64) {
-            const uint16_t *rec = src[c];
+            const Sym *rec = src[c];
             const int no = rec[1];
             if (no == 0) continue;
             const int top = rec[2 + kMaxIn];
-            int l = lo, h = hi;
-            while (l < h) {
-                const int m = (l + h) >> 1;
-                if (g.head[m] < top) l = m + 1; else h = m;
-            }
-            for (int i = l; i < hi && g.head[i] == top; ++i) {
+            const int first = a.pair_first[(size_t)ch * g.N + top] - 1;
+            if (first < 0) continue;
+            for (int i = first; i < hi && g.head[i] == top; ++i) {
                 const int len = g.len[i];
+                const uint2 body2 = reinterpret_cast<const uint2 *>(g.body)[i];
+                const uint16_t body[kMaxBody] = {(uint16_t)(body2.x & 0xFFFF), (uint16_t)(body2.x >> 16),
+                                                 (uint16_t)(body2.y & 0xFFFF), (uint16_t)(body2.y >> 16)};
                 const int slot = atomicAdd(&n_emit, 1);
                 if (no - 1 + len > kMaxOut) {
                     crossed = 1;
                 } else if (slot < kMaxFrontier) {
-                    uint16_t *o = dst[slot];
+                    Sym *o = dst[slot];
                     o[0] = rec[0];
-                    o[1] = (uint16_t)(no - 1 + len);
+                    o[1] = (Sym)(no - 1 + len);
                     for (int k = 0; k < kMaxIn; ++k) o[2 + k] = rec[2 + k];
                     for (int k = 0; k < kMaxOut; ++k) {
-                        uint16_t v = 0;
-                        if (k < len) v = g.body[i * kMaxBody + k];
+                        Sym v = 0;
+                        if (k < len) v = (Sym)body[k];
                         else if (k - len + 1 < no) v = rec[2 + kMaxIn + k - len + 1];
                         o[2 + kMaxIn + k] = v;
                     }
-                    o[kPrevAt] = (uint16_t)top;
+                    o[kPrevAt] = (Sym)top;
                     for (int k = kPrevAt + 1; k < kRecStride; ++k) o[k] = 0;
                 }
             }
         }
         // stack backtracks: the wave per configuration (every production of the terminal)
         for (int c = 0; c < n; ++c) {
-            const uint16_t *rec = src[c];
+            const Sym *rec = src[c];
             if (rec[1] != 0) continue;  // the same for every lane
             const int ni = rec[0];
             const int prev = rec[kPrevAt];
@@ -352,18 +377,21 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
                     !((a.adj[(size_t)A * g.W + (prev >> 5)] >> (prev & 31)) & 1u))
                     continue;
                 const int len = g.len[i];
+                const uint2 body2 = reinterpret_cast<const uint2 *>(g.body)[i];
+                const uint16_t body[kMaxBody] = {(uint16_t)(body2.x & 0xFFFF), (uint16_t)(body2.x >> 16),
+                                                 (uint16_t)(body2.y & 0xFFFF), (uint16_t)(body2.y >> 16)};
                 const int slot = atomicAdd(&n_emit, 1);
                 if (ni + 1 > kMaxIn) {
                     crossed = 1;
                 } else if (slot < kMaxFrontier) {
-                    uint16_t *o = dst[slot];
-                    o[0] = (uint16_t)(ni + 1);
-                    o[1] = (uint16_t)len;
+                    Sym *o = dst[slot];
+                    o[0] = (Sym)(ni + 1);
+                    o[1] = (Sym)len;
                     for (int k = 0; k < kMaxIn; ++k)
-                        o[2 + k] = k < ni ? rec[2 + k] : (k == ni ? (uint16_t)A : (uint16_t)0);
+                        o[2 + k] = k < ni ? rec[2 + k] : (k == ni ? (Sym)A : (Sym)0);
                     for (int k = 0; k < kMaxOut; ++k)
-                        o[2 + kMaxIn + k] = k < len ? g.body[i * kMaxBody + k] : (uint16_t)0;
-                    o[kPrevAt] = (uint16_t)A;
+                        o[2 + kMaxIn + k] = k < len ? (Sym)body[k] : (Sym)0;
+                    o[kPrevAt] = (Sym)A;
                     for (int k = kPrevAt + 1; k < kRecStride; ++k) o[k] = 0;
                 }
             }
@@ -374,12 +402,12 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
             overflow = true;
             break;
         }
-        n = drop_duplicates(dst, src, m, lane);  // back into the buffer just read
+        n = drop_duplicates<Sym>(dst, src, m, lane);  // back into the buffer just read
         __syncthreads();
     }
 
-    uint16_t(*front)[kRecStride] = buf[cur];
-    uint16_t(*other)[kRecStride] = buf[cur ^ 1];
+    Sym(*front)[kRecStride] = buf[cur];
+    Sym(*other)[kRecStride] = buf[cur ^ 1];
     int start0 = 0, start1 = 0;  // where this lane's records begin in the row
     if (!overflow) {
         // the displacement forgets the symbol consumed last
@@ -389,15 +417,15 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
             hash_sum = 0;
         }
         __syncthreads();
-        n = drop_duplicates(front, other, n, lane);
+        n = drop_duplicates<Sym>(front, other, n, lane);
         __syncthreads();
         // canonical order by counting: a record starts behind all smaller ones
         for (int c = lane, u = 0; c < n; c += 64, ++u) {
             const uint32_t *mine = reinterpret_cast<const uint32_t *>(other[c]);
             int start = 1;
             for (int j = 0; j < n; ++j) {
-                const uint16_t *r = other[j];
-                if (j != c && record_less(reinterpret_cast<const uint32_t *>(r), mine))
+                const Sym *r = other[j];
+                if (j != c && record_less<Sym>(reinterpret_cast<const uint32_t *>(r), mine))
                     start += 2 + r[0] + r[1];
             }
             if (u == 0) start0 = start; else start1 = start;
@@ -410,7 +438,7 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
     __syncthreads();
     if (overflow) {
         if (lane == 0) {
-            row[0] = kNone;
+            row[0] = 0xFFFF;
             row[1] = (uint16_t)(t & 0xFFFF);
             row[2] = (uint16_t)((uint32_t)t >> 16);
         }
@@ -422,7 +450,7 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
     } else {
         if (lane == 0) row[0] = (uint16_t)n;
         for (int c = lane, u = 0; c < n; c += 64, ++u) {
-            const uint16_t *r = other[c];
+            const Sym *r = other[c];
             int pos = u == 0 ? start0 : start1;
             const int ni = r[0], no = r[1];
             row[pos++] = (uint16_t)ni;
@@ -444,7 +472,7 @@ int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, cons
                        const uint16_t *prod_body, int32_t P, int32_t N) {
     if (!prod_head || !prod_byte || !prod_len || !prod_body) return CFGZIP_E_INVALID;
     if (P <= 0 || N <= 0 || N > kMaxSymbols) return CFGZIP_E_INVALID;
-    if (!aligned_to(prod_head, 2) || !aligned_to(prod_body, 2)) return CFGZIP_E_INVALID;
+    if (!aligned_to(prod_head, 2) || !aligned_to(prod_body, 8)) return CFGZIP_E_INVALID;
     return CFGZIP_OK;
 }
 
@@ -504,6 +532,7 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
     a.g = g;
     a.hdr = w.hdr;
     a.byte_off = w.byte_off;
+    a.pair_first = w.pair_first;
     a.adj = w.adj;
     a.tok_bytes = tok_bytes;
     a.tok_off = tok_off;
@@ -511,6 +540,9 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
     a.hash = hash_out;
     a.status = status_out;
     a.seed = hash_seed;
-    hipLaunchKernelGGL(displacement_kernel, dim3((unsigned)V), dim3(64), 0, stream, a);
+    if (N <= kMaxByteSymbols)
+        hipLaunchKernelGGL(displacement_kernel<uint8_t>, dim3((unsigned)V), dim3(64), 0, stream, a);
+    else
+        hipLaunchKernelGGL(displacement_kernel<uint16_t>, dim3((unsigned)V), dim3(64), 0, stream, a);
     return check_launch();
 }

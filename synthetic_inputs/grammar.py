@@ -95,3 +95,80 @@ def make_token_strings(seed: int, V: int, alphabet: bytes, max_len: int) -> Voca
     toks = [bytes(alpha[rng.integers(0, len(alpha), size=int(rng.integers(1, max_len + 1)))])
             for _ in range(V)]
     return vocab_from_tokens(toks)
+
+
+JSON_NONTERMINALS = ["VAL", "STR", "ESC", "HEX", "NUMT", "NUMD", "FRAC", "FRACT", "EXP", "EXPD",
+                     "EXPT", "OBJ", "OBJT", "MEMBER", "COLON", "ARR", "ARRT", "SP", "TR", "TU",
+                     "TE", "FA", "FL", "FS", "NU", "NL", "NL2"]
+
+
+def make_json_gnf() -> Grammar:
+    """The JSON value language over bytes, written directly in Greibach normal form (every
+    production starts with its terminal byte; what must follow waits on the stack).  Strings
+    take any byte from 0x20 up except the quote and the backslash, with the usual escapes;
+    numbers have optional fraction and exponent; one blank may follow ',' and ':' and '{'.
+    Stands in for the JSON grammars of the paper's experiments, which come from a schema
+    compiler that is not available here."""
+    nt = {name: i for i, name in enumerate(JSON_NONTERMINALS)}
+    P: List[Tuple[int, int, Tuple[int, ...]]] = []
+
+    def add(head: str, byte, *body: str):
+        b = byte if isinstance(byte, int) else ord(byte)
+        P.append((nt[head], b, tuple(nt[x] for x in body)))
+
+    digits = b"0123456789"
+    value_starts: List[Tuple[int, Tuple[str, ...]]] = [(ord('"'), ("STR",)), (ord("-"), ("NUMD",)),
+                                                       (ord("{"), ("OBJ",)), (ord("["), ("ARR",)),
+                                                       (ord("t"), ("TR",)), (ord("f"), ("FA",)),
+                                                       (ord("n"), ("NU",))]
+    for d in digits:
+        value_starts += [(d, ()), (d, ("NUMT",))]
+    for b, body in value_starts:
+        add("VAL", b, *body)
+        add("ARR", b, *body, "ARRT")
+    add("ARR", "]")
+    add("ARRT", "]")
+    add("ARRT", ",", "VAL", "ARRT")
+    add("ARRT", ",", "SP", "VAL", "ARRT")
+    add("OBJ", "}")
+    add("OBJ", '"', "STR", "COLON", "VAL", "OBJT")
+    add("OBJ", " ", "OBJ")
+    add("OBJT", "}")
+    add("OBJT", ",", "MEMBER", "OBJT")
+    add("OBJT", ",", "SP", "MEMBER", "OBJT")
+    add("MEMBER", '"', "STR", "COLON", "VAL")
+    add("COLON", ":")
+    add("COLON", ":", "SP")
+    add("SP", " ")
+    add("SP", "\n")
+    # strings
+    add("STR", '"')
+    add("STR", "\\", "ESC", "STR")
+    for c in range(0x20, 0x100):
+        if c not in (ord('"'), ord("\\")):
+            add("STR", c, "STR")
+    for c in '"\\/bfnrt':
+        add("ESC", c)
+    add("ESC", "u", "HEX", "HEX", "HEX", "HEX")
+    for c in b"0123456789abcdefABCDEF":
+        add("HEX", c)
+    # numbers
+    for d in digits:
+        add("NUMT", d), add("NUMT", d, "NUMT")
+        add("NUMD", d), add("NUMD", d, "NUMT")
+        add("FRAC", d), add("FRAC", d, "FRACT")
+        add("FRACT", d), add("FRACT", d, "FRACT")
+        add("EXP", d), add("EXP", d, "EXPT")
+        add("EXPD", d), add("EXPD", d, "EXPT")
+        add("EXPT", d), add("EXPT", d, "EXPT")
+    add("NUMT", ".", "FRAC")
+    for e in "eE":
+        add("NUMT", e, "EXP")
+        add("FRACT", e, "EXP")
+    add("EXP", "+", "EXPD")
+    add("EXP", "-", "EXPD")
+    # literals true / false / null
+    add("TR", "r", "TU"), add("TU", "u", "TE"), add("TE", "e")
+    add("FA", "a", "FL"), add("FL", "l", "FS"), add("FS", "s", "TE")
+    add("NU", "u", "NL"), add("NL", "l", "NL2"), add("NL2", "l")
+    return grammar_from_productions(len(JSON_NONTERMINALS), P)

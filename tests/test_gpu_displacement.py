@@ -131,6 +131,39 @@ def test_bracket_grammar_vocabulary(lib):
     assert len(set(c.tolist())) < 0.5 * vocab.V, "an expression grammar compresses"
 
 
+def test_large_grammar(lib):
+    """Thousands of productions over all 256 byte values."""
+    print("case large grammar", flush=True)
+    g = make_random_gnf(77, n_nt=60, alphabet=bytes(range(256)), n_prod=5000, max_body=4)
+    assert g.P == 5000
+    _check_adjacency(lib, g)
+    vocab = make_token_strings(78, 6000, bytes(range(256)), 5)
+    rows, status, _c = _check_rows(lib, g, vocab)
+    assert ((status == D.DISP_OK) & (rows[:, 0] > 0)).sum() > 500, "enough tokens must stay alive"
+
+
+def test_more_symbols_than_fit_a_byte(lib):
+    """Above 255 symbols the kernel keeps 16-bit entries in its records."""
+    print("case 300 and 256 symbols", flush=True)
+    for n_nt, n_prod in ((300, 900), (256, 800), (255, 800)):
+        g = make_random_gnf(n_nt, n_nt=n_nt, alphabet=bytes(range(64, 128)), n_prod=n_prod, max_body=3)
+        vocab = make_token_strings(n_nt + 1, 3000, bytes(range(64, 128)), 4)
+        rows, status, _c = _check_rows(lib, g, vocab)
+        assert ((status == D.DISP_OK) & (rows[:, 0] > 0)).sum() > 300
+        assert rows[:, 2:].max() >= 200, "high symbol numbers must show up in the rows"
+
+
+def test_long_tokens(lib):
+    print("case long tokens", flush=True)
+    g, atoms = make_bracket_gnf(5)
+    a0 = bytes([atoms[0]])
+    toks = [b"((" + a0, (a0 + b"+") * 40 + a0, (a0 + b"+") * 32, b"[" + (a0 + b"*") * 70 + a0 + b"]",
+            a0 * 200, (a0 + b"-") * 31 + a0 + b"+" , b""]
+    rows, status, _c = _check_rows(lib, g, vocab_from_tokens(toks))
+    assert status.tolist() == [0] * len(toks)
+    assert rows[1][0] > 0 and rows[3][0] > 0 and rows[4][0] == 0
+
+
 def test_each_bound_overflows_alone(lib):
     print("case overflow bounds", flush=True)
     a = ord("a")
@@ -226,3 +259,44 @@ def test_argument_errors(lib):
                                  workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     with pytest.raises(lib.CfgzipError):   # no automaton and no rows
         lib.cfgzip_build_classes(tb, to, None, None, torch.zeros(vocab.V, dtype=torch.int64, device="cuda"))
+
+
+def test_json_grammar_full_vocabulary(lib):
+    """The measured workload at full size: the JSON grammar against config 3's 128,256 tokens.
+    Every 8th token's row, hash and status against the oracle; the grouping of all rows against
+    numpy's row-wise unique (what the classes are is fixed by the rows)."""
+    print("case json grammar, full vocabulary", flush=True)
+    from gpu_util import dev, hash_np
+    from synthetic_inputs.grammar import make_json_gnf
+    g = make_json_gnf()
+    vocab = si.make_config(3)["vocab"]
+    prods = g.productions()
+    _check_adjacency(lib, g)
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+    rows, hashes, status = lib.cfgzip_displacements(tb, to, *_grammar_dev(g), g.N, hash_seed=SEED)
+    got_rows, got_hash, got_status = rows.cpu().numpy(), hash_np(hashes), status.cpu().numpy()
+    adj = D.stack_adjacency(prods)
+    index = D.index_productions(prods)
+    n_overflow = 0
+    for t in range(0, vocab.V, 8):
+        pairs = D.displacement_bounded(tuple(vocab.token(t)), prods, adj, index)
+        row, h, st = D.encode_displacement(pairs, t, SEED)
+        assert got_status[t] == st and got_hash[t] == h and (got_rows[t] == np.array(row, np.uint16)).all(), \
+            (t, vocab.token(t))
+        n_overflow += st == D.DISP_OVERFLOW
+    assert 0 < n_overflow < vocab.V // 8 // 10
+    c, r, C, _coll = lib.cfgzip_build_classes(tb, to, None, rows, hashes)
+    c, r = c.cpu().numpy(), r.cpu().numpy()
+    _uniq, first, inverse = np.unique(got_rows, axis=0, return_index=True, return_inverse=True)
+    inverse = inverse.reshape(-1)
+    assert C == len(first)
+    # same partition: class ids are issued by smallest member id
+    order = np.argsort(first)
+    rank = np.empty_like(order)
+    rank[order] = np.arange(len(order))
+    assert (rank[inverse] == c).all()
+    lens = np.diff(vocab.tok_off)
+    assert (c[r] == np.arange(C)).all()
+    best = np.full(C, np.iinfo(np.int64).max)
+    np.minimum.at(best, c, lens * vocab.V + np.arange(vocab.V))
+    assert (best % vocab.V == r).all()
