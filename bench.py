@@ -277,7 +277,7 @@ def main() -> int:
                     help="also time the other forms of the mask path at the same shape")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the path has no cross-GPU part); "
+        print("bench.py: the library runs on exactly one GPU (the path has no cross-GPU part); "
               "use --gpus 1", file=sys.stderr)
         return 2
 
