@@ -189,6 +189,22 @@ def signature_hash(sig, seed: int) -> np.ndarray:
     return out
 
 
+def nfa_signatures(tok_bytes, tok_off, nfa) -> np.ndarray:
+    """uint32 [V, S, W]: bit row of the states reachable from q on the bytes of token t, for a
+    non-deterministic byte automaton nfa[b][q] = bit row of successors (uint32 [256, S, W])."""
+    tok_bytes = _c(tok_bytes, np.uint8)
+    tok_off = _c(tok_off, np.int64)
+    nfa = _c(nfa, np.uint32)
+    V = tok_off.shape[0] - 1
+    S = nfa.shape[1]
+    W = (S + 31) // 32
+    assert nfa.shape == (256, S, W)
+    out = np.empty((V, S, W), dtype=np.uint32)
+    _load().oracle_nfa_signatures(_p(tok_bytes), _p(tok_off), ctypes.c_int32(V), _p(nfa),
+                                  ctypes.c_int32(S), _p(out))
+    return out
+
+
 def splitmix64_stream(seed: int, n: int) -> np.ndarray:
     state = ctypes.c_uint64(seed)
     lib = _load()

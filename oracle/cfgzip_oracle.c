@@ -40,6 +40,10 @@
  *                         of its current state).
  *   oracle_advance_states Section 3.1 "Inference": the engine's state is updated with the
  *                         representative r[c[t]] of the sampled token t.
+ *   oracle_nfa_signatures Section 3.2.1 for a right-linear grammar that is NOT deterministic
+ *                         (several productions q -> a q' per state and byte): the
+ *                         displacement of t is the relation {(q, q') : q' reachable from q
+ *                         on bytes(t)}, kept as one bit row per start state.
  *   oracle_hash           The library's signature hash (not in the paper; a
  *                         device of this implementation) written from its
  *                         formula:  H(t) = sum_q a_q * sig[t][q]  mod 2^64 with
@@ -294,4 +298,33 @@ void oracle_hash(const uint16_t *sig /* [V][S] */, int32_t V, int32_t S, uint64_
         hash_out[t] = h;
     }
     free(a);
+}
+
+/* Non-deterministic byte automaton: nfa[b][q] is the bit row (W = ceil(S/32) words, bit q' & 31
+ * of word q' >> 5) of the states that may follow q on byte b.  out[t][q] = bit row of the states
+ * reachable from q on the bytes of token t (the identity for an empty token).  Pad bits 0. */
+void oracle_nfa_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                           const uint32_t *nfa /* [256][S][W] */, int32_t S,
+                           uint32_t *out /* [V][S][W] */) {
+    const int32_t W = (S + 31) / 32;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int32_t t = 0; t < V; ++t) {
+        uint32_t *cur = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)W);
+        uint32_t *nxt = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)W);
+        for (int32_t q = 0; q < S; ++q) {
+            for (int32_t w = 0; w < W; ++w) cur[w] = 0;
+            cur[q >> 5] = 1u << (q & 31);
+            for (int64_t p = tok_off[t]; p < tok_off[t + 1]; ++p) {
+                const uint32_t *step = nfa + (size_t)tok_bytes[p] * S * W;
+                for (int32_t w = 0; w < W; ++w) nxt[w] = 0;
+                for (int32_t x = 0; x < S; ++x)
+                    if ((cur[x >> 5] >> (x & 31)) & 1u)
+                        for (int32_t w = 0; w < W; ++w) nxt[w] |= step[(size_t)x * W + w];
+                uint32_t *tmp = cur; cur = nxt; nxt = tmp;
+            }
+            for (int32_t w = 0; w < W; ++w) out[((size_t)t * S + q) * W + w] = cur[w];
+        }
+        free(cur);
+        free(nxt);
+    }
 }
