@@ -276,6 +276,26 @@ int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32
                          int32_t N, uint16_t *rows_out, uint64_t *hash_out, int32_t *status_out,
                          uint64_t hash_seed, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Non-deterministic byte automata (paper Section 3.2.1 for a right-linear grammar with several
+ * productions q -> a q' per state and byte): the displacement of token t is the relation
+ *     R_t = {(q, q') : q' can be reached from q on bytes(t)},
+ * the boolean product of the per-byte relations; R of the empty token is the identity.
+ *
+ *   nfa       int32 [256][S][W(S)]  bit q' of row nfa[b][q] <=> q' may follow q on byte b
+ *                                   (pad bits must be 0)
+ *   S         1 .. 256
+ *   rel_out   int32 [V][S][W(S)]    bit q' of row rel_out[t][q] <=> (q, q') in R_t; pad bits 0
+ *   hash_out  uint64 [V] or NULL    the hash of cfgzip_signatures taken over the relation read
+ *                                   as 2 * S * W(S) 16-bit entries (low half of a word first)
+ * Grouping: cfgzip_build_classes(tok_bytes, tok_off, V, NULL, 2 * S * W(S), (uint16*)rel_out,
+ * hash_out, NULL, ..).  A deterministic automaton gives one-bit rows and the classes of the
+ * byte walk.
+ */
+int cfgzip_nfa_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                          const int32_t *nfa, int32_t S, int32_t *rel_out, uint64_t *hash_out,
+                          uint64_t hash_seed, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

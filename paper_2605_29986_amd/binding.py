@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_class_masks.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.cfgzip_advance_states.restype = ctypes.c_int
     lib.cfgzip_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_nfa_signatures.restype = ctypes.c_int
+    lib.cfgzip_nfa_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp]
     lib.cfgzip_displacements_workspace_bytes.restype = sz
     lib.cfgzip_displacements_workspace_bytes.argtypes = [i32]
     lib.cfgzip_stack_adjacency.restype = ctypes.c_int
@@ -359,3 +361,23 @@ def cfgzip_displacements(tok_bytes: torch.Tensor, tok_off: torch.Tensor, prod_he
         workspace.data_ptr(), workspace.numel(), _stream(stream))
     _check("cfgzip_displacements", rc)
     return rows, hashes, status
+
+
+def cfgzip_nfa_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, nfa: torch.Tensor, *,
+                          want_hash: bool = True, hash_seed: int = DEFAULT_HASH_SEED, stream=None):
+    """(rel int32 [V, S, W(S)], hash int64 [V] or None) for nfa int32 [256, S, W(S)]."""
+    lib = load_library()
+    V = tok_off.numel() - 1
+    S = nfa.shape[1]
+    if nfa.shape != (256, S, words_for(S)):
+        raise ValueError("nfa must have shape [256, S, W(S)]")
+    dev = tok_off.device
+    rel = torch.empty((V, S, words_for(S)), dtype=torch.int32, device=dev)
+    hashes = torch.empty((V,), dtype=torch.int64, device=dev) if want_hash else None
+    rc = lib.cfgzip_nfa_signatures(
+        _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
+        _dev(tok_off, torch.int64, "tok_off"), V, _dev(nfa, torch.int32, "nfa"), S,
+        rel.data_ptr(), hashes.data_ptr() if want_hash else None,
+        ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF), _stream(stream))
+    _check("cfgzip_nfa_signatures", rc)
+    return rel, hashes

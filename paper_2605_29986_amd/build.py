@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libcfgzip.so")
-SOURCES = ["mask.hip", "walk.hip", "classes.hip", "engine.hip", "displacement.hip"]
+SOURCES = ["mask.hip", "walk.hip", "classes.hip", "engine.hip", "displacement.hip", "nfa.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",

@@ -1,0 +1,144 @@
+// Signatures over a non-deterministic byte automaton (paper Section 3.2.1 for a right-linear
+// grammar with several productions q -> a q' per state and byte).  The displacement of token t
+// is then the relation R_t = {(q, q') : q' reachable from q on bytes(t)}, the boolean product of
+// the per-byte transition relations; it is kept as one bit row per start state.
+//
+// A thread owns one (token, start state) pair and carries the set of current states as W words
+// in registers.  Per byte it ORs together the successor rows of the set's members, visiting set
+// bits only, so the cost follows the number of live states (one or a few for a lexer), not S;
+// a set that has become empty stops early.  The 64-bit hash is the same multilinear form as for
+// the byte walk, over the relation read as 16-bit entries, so any split over threads gives the
+// same bits.
+
+#include <algorithm>
+
+#include "common.hpp"
+
+namespace cfgzip {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxNfaStates = 256;
+
+__device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint32_t index) {
+    // index-th output (0-based) of the SplitMix64 generator seeded with `seed`
+    uint64_t z = seed + (uint64_t)(index + 1u) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+struct NfaArgs {
+    const uint8_t *tok_bytes;
+    const int64_t *tok_off;
+    const uint32_t *nfa;  // [256][S][W]
+    uint32_t *rel;        // [V][S][W]
+    uint64_t *hash;       // [V] or null
+    uint64_t seed;
+    int V, S;
+    int threads_per_token;  // 64, 128 or 256: S rounded up
+    uint32_t last_word_mask;  // the bits of a row's last word that are states
+};
+
+template <int W>
+__global__ __launch_bounds__(kThreads) void nfa_walk_kernel(NfaArgs a) {
+    __shared__ unsigned long long hash_sum[kThreads / 64];
+    const int slot = threadIdx.x / a.threads_per_token;
+    const int q = threadIdx.x % a.threads_per_token;
+    const int t = blockIdx.x * (kThreads / a.threads_per_token) + slot;
+    if (threadIdx.x < kThreads / 64) hash_sum[threadIdx.x] = 0;
+    __syncthreads();
+    const bool active = t < a.V && q < a.S;
+    uint64_t h = 0;
+    if (active) {
+        uint32_t cur[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) cur[w] = (q >> 5) == w ? 1u << (q & 31) : 0u;
+        const int64_t b0 = a.tok_off[t], b1 = a.tok_off[t + 1];
+        for (int64_t p = b0; p < b1; ++p) {
+            const uint32_t *step = a.nfa + (size_t)a.tok_bytes[p] * a.S * W;
+            uint32_t nxt[W];
+#pragma unroll
+            for (int w = 0; w < W; ++w) nxt[w] = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                uint32_t bits = cur[w];
+                while (bits) {
+                    const int x = w * 32 + __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    const uint32_t *row = step + (size_t)x * W;
+#pragma unroll
+                    for (int k = 0; k < W; ++k) nxt[k] |= row[k];
+                }
+            }
+            nxt[W - 1] &= a.last_word_mask;  // a stray pad bit must not become a state number
+            uint32_t any = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                cur[w] = nxt[w];
+                any |= nxt[w];
+            }
+            if (!any) break;  // no state left: the row stays empty
+        }
+        uint32_t *out = a.rel + ((size_t)t * a.S + q) * W;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            out[w] = cur[w];
+            if (a.hash) {
+                const uint32_t e = 2u * (uint32_t)(q * W + w);  // 16-bit entries 2(qW+w), 2(qW+w)+1
+                h += (splitmix64_at(a.seed, e) | 1ull) * (uint64_t)(cur[w] & 0xFFFFu);
+                h += (splitmix64_at(a.seed, e + 1u) | 1ull) * (uint64_t)(cur[w] >> 16);
+            }
+        }
+    }
+    if (a.hash) {
+        if (active && h) atomicAdd(&hash_sum[slot], (unsigned long long)h);
+        __syncthreads();
+        if (q == 0 && t < a.V) a.hash[t] = hash_sum[slot];
+    }
+}
+
+template <int W>
+int launch_nfa(const NfaArgs &a, hipStream_t stream) {
+    const int per_block = kThreads / a.threads_per_token;
+    hipLaunchKernelGGL(nfa_walk_kernel<W>, dim3((unsigned)ceil_div(a.V, per_block)), dim3(kThreads), 0,
+                       stream, a);
+    return check_launch();
+}
+
+}  // namespace
+}  // namespace cfgzip
+
+using namespace cfgzip;
+
+extern "C" int cfgzip_nfa_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                                     const int32_t *nfa, int32_t S, int32_t *rel_out,
+                                     uint64_t *hash_out, uint64_t hash_seed, void *stream_) {
+    if (!tok_off || !nfa || !rel_out) return CFGZIP_E_INVALID;
+    if (V <= 0 || S <= 0 || S > kMaxNfaStates) return CFGZIP_E_INVALID;
+    if (!aligned_to(tok_off, 8) || !aligned_to(nfa, 4) || !aligned_to(rel_out, 4) ||
+        !aligned_to(hash_out, 8))
+        return CFGZIP_E_INVALID;
+    NfaArgs a{};
+    a.tok_bytes = tok_bytes;
+    a.tok_off = tok_off;
+    a.nfa = reinterpret_cast<const uint32_t *>(nfa);
+    a.rel = reinterpret_cast<uint32_t *>(rel_out);
+    a.hash = hash_out;
+    a.seed = hash_seed;
+    a.V = V;
+    a.S = S;
+    a.threads_per_token = S <= 64 ? 64 : (S <= 128 ? 128 : 256);
+    a.last_word_mask = (S & 31) ? (1u << (S & 31)) - 1u : 0xFFFFFFFFu;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    switch ((S + 31) / 32) {
+        case 1: return launch_nfa<1>(a, stream);
+        case 2: return launch_nfa<2>(a, stream);
+        case 3: return launch_nfa<3>(a, stream);
+        case 4: return launch_nfa<4>(a, stream);
+        case 5: return launch_nfa<5>(a, stream);
+        case 6: return launch_nfa<6>(a, stream);
+        case 7: return launch_nfa<7>(a, stream);
+        default: return launch_nfa<8>(a, stream);
+    }
+}

@@ -1,0 +1,110 @@
+"""GPU parity, non-deterministic byte automata: cfgzip_nfa_signatures against the oracle bit
+for bit (relations and hashes), and the classes cfgzip_build_classes forms from the relations."""
+
+import numpy as np
+import pytest
+
+import oracle
+import synthetic_inputs as si
+from synthetic_inputs.nfa import add_transitions, make_lexer_nfa, nfa_from_dfa
+from synthetic_inputs.vocab import vocab_from_tokens
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SEED = 0xC0FFEE
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_29986_amd as p
+    p.load_library()
+    return p
+
+
+def _check(lib, vocab, nfa, classes=True):
+    from gpu_util import dev, hash_np
+    V, S, W = vocab.V, nfa.shape[1], nfa.shape[2]
+    want = oracle.nfa_signatures(vocab.tok_bytes, vocab.tok_off, nfa)
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+    rel, h = lib.cfgzip_nfa_signatures(tb, to, dev(nfa), hash_seed=SEED)
+    got = rel.cpu().numpy().view(np.uint32)
+    bad = np.nonzero((got != want).any(axis=(1, 2)))[0]
+    assert bad.size == 0, (bad[:5], [vocab.token(int(i)) for i in bad[:5]])
+    rows16 = np.ascontiguousarray(want).view(np.uint16).reshape(V, S * W * 2)
+    assert (hash_np(h) == oracle.signature_hash(rows16, SEED)).all()
+    if classes:
+        rows = rel.view(torch.uint16).reshape(V, S * W * 2)
+        c, r, C, _coll = lib.cfgzip_build_classes(tb, to, None, rows, h)
+        want_c, want_r = oracle.build_classes(rows16, vocab.tok_off)
+        assert C == len(want_r)
+        assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+        return want, want_c
+    return want, None
+
+
+def _random_nfa(rng, S, n_sym, per_row):
+    """every (byte < n_sym, state) gets Poisson(per_row) successors"""
+    W = (S + 31) // 32
+    nfa = np.zeros((256, S, W), np.uint32)
+    for b in range(n_sym):
+        for q in range(S):
+            for x in rng.integers(0, S, size=rng.poisson(per_row)):
+                nfa[b, q, x >> 5] |= np.uint32(1 << (int(x) & 31))
+    return nfa
+
+
+@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 64, 65, 100, 128, 129, 160, 200, 255, 256])
+def test_random_relations(lib, S):
+    print(f"case S={S}", flush=True)
+    rng = np.random.default_rng(S)
+    nfa = _random_nfa(rng, S, 4, 1.2)
+    toks = [bytes(rng.integers(0, 5, size=int(n)).astype(np.uint8)) for n in rng.integers(0, 9, size=700)]
+    toks += [b"", bytes([0, 1, 2, 3] * 40), bytes([9]), bytes([0] * 300)]
+    want, _ = _check(lib, vocab_from_tokens(toks), nfa)
+    assert want.any() and not want[len(toks) - 2].any()
+
+
+def test_dense_relation_fills_every_row(lib):
+    print("case dense", flush=True)
+    rng = np.random.default_rng(3)
+    nfa = _random_nfa(rng, 256, 2, 6.0)
+    toks = [bytes(rng.integers(0, 2, size=int(n)).astype(np.uint8)) for n in rng.integers(1, 7, size=300)]
+    want, _ = _check(lib, vocab_from_tokens(toks), nfa)
+    long_ones = want[np.array([len(t) for t in toks]) >= 5]
+    assert np.unpackbits(long_ones.view(np.uint8)).mean() > 0.95, "nearly every pair is reachable"
+
+
+def test_deterministic_automaton_gives_the_byte_walk_classes(lib, cfg1, cfg2_small):
+    from gpu_util import vocab_dev
+    for cfg in (cfg1, cfg2_small):
+        print(f"case config {cfg['index']}", flush=True)
+        table, vocab = cfg["table"], cfg["vocab"]
+        _want, c_rel = _check(lib, vocab, nfa_from_dfa(table))
+        tb, to, tt = vocab_dev(vocab, table)
+        sig, h = lib.cfgzip_signatures(tb, to, tt)
+        c_walk, _r, _C, _ = lib.cfgzip_build_classes(tb, to, tt, sig, h)
+        assert (c_walk.cpu().numpy() == c_rel).all()
+
+
+def test_lexer_nfa_full_vocabulary(lib):
+    """The measured workload: config 2's vocabulary against its lexer with a tenth of the live
+    transitions doubled."""
+    print("case lexer nfa, config 2", flush=True)
+    cfg = si.make_config(2)
+    nfa = make_lexer_nfa(cfg["seed"] + 500, cfg["S"], 0.10)
+    want, c = _check(lib, cfg["vocab"], nfa)
+    det, c_det = _check(lib, cfg["vocab"], nfa_from_dfa(cfg["table"]), classes=True)
+    assert ((want & det) == det).all(), "added transitions only add pairs"
+    assert len(set(c.tolist())) != len(set(c_det.tolist()))
+
+
+def test_argument_errors(lib):
+    from gpu_util import dev
+    v = vocab_from_tokens([b"a", b"b"])
+    tb, to = dev(v.tok_bytes), dev(v.tok_off)
+    with pytest.raises(lib.CfgzipError):
+        lib.cfgzip_nfa_signatures(tb, to, torch.zeros((256, 257, 9), dtype=torch.int32, device="cuda"))
+    with pytest.raises(ValueError):
+        lib.cfgzip_nfa_signatures(tb, to, torch.zeros((256, 40, 1), dtype=torch.int32, device="cuda"))
