@@ -221,6 +221,60 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
     return out
 
 
+def bench_nfa(lib_mod, raw, torch, repeats: int, cpu: bool):
+    """Non-deterministic lexer: config 2's vocabulary against its automaton with a tenth of the
+    live transitions doubled; relations, then classes from the relation rows."""
+    import synthetic_inputs as si
+    from synthetic_inputs.nfa import make_lexer_nfa
+    cfg = si.make_config(2)
+    vocab, S = cfg["vocab"], cfg["S"]
+    nfa_np = make_lexer_nfa(cfg["seed"] + 500, S, 0.10)
+    V, W = vocab.V, nfa_np.shape[2]
+    stream = torch.cuda.current_stream()
+    tb = torch.from_numpy(vocab.tok_bytes).cuda()
+    to = torch.from_numpy(vocab.tok_off).cuda()
+    nfa = torch.from_numpy(nfa_np.view(np.int32)).cuda()
+    row_len = 2 * S * W
+    ws_bld = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, row_len), dtype=torch.uint8, device="cuda")
+    c = torch.empty((V,), dtype=torch.int32, device="cuda")
+    r = torch.empty((V,), dtype=torch.int32, device="cuda")
+    res = {}
+
+    def run_rel():
+        res["rel"] = lib_mod.cfgzip_nfa_signatures(tb, to, nfa)
+
+    def run_build():
+        rel, h = res["rel"]
+        res["cls"] = lib_mod.cfgzip_build_classes(tb, to, None, rel.view(torch.uint16).reshape(V, row_len), h,
+                                                  class_of_token=c, rep_of_class=r, workspace=ws_bld)
+
+    run_rel(); run_build(); torch.cuda.synchronize()
+    t_rel, t_all = [], []
+    for _ in range(repeats):
+        t_rel.append(event_ms(run_rel, stream))
+        t_all.append(event_ms(lambda: (run_rel(), run_build()), stream))
+    ms_rel, ms_all = min(t_rel), min(t_all)
+    C = res["cls"][2]
+    out = {
+        "workload": "config 2 vocabulary x its 256-state lexer with 10 % of the live transitions doubled",
+        "V": V, "S": S, "C": C, "V_over_C": round(V / C, 2),
+        "ms_relations": round(ms_rel, 4), "ms_total_with_classes": round(ms_all, 4),
+        "walks_per_s": V * S / (ms_all * 1e-3),
+        "relation_store_GBps": round(V * S * W * 4 / (ms_rel * 1e-3) / 1e9, 1),
+    }
+    log(f"nfa: V={V} S={S} C={C} relations {ms_rel:.3f} ms ({out['relation_store_GBps']} GB/s stored), "
+        f"with classes {ms_all:.3f} ms, {out['walks_per_s']:.3e} walks/s")
+    if cpu:
+        import oracle
+        t0 = time.perf_counter()
+        rel = oracle.nfa_signatures(vocab.tok_bytes, vocab.tok_off, nfa_np)
+        oracle.build_classes(np.ascontiguousarray(rel).view(np.uint16).reshape(V, row_len), vocab.tok_off)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": V * S / dt, "unit": "walks/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "the whole workload"}
+    return out
+
+
 def cpu_baseline_decode(c5, r5, d, budget_s: float = 10.0, max_steps: int = 2000):
     """The oracle's decode step (expand, apply, map) on full-size steps, timed on the host."""
     import oracle
@@ -272,7 +326,7 @@ def main() -> int:
     ap.add_argument("--build-repeats", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-displacement", action="store_true",
-                    help="skip the general-case (grammar) pre-computation workload")
+                    help="skip the grammar and non-deterministic automaton pre-computation workloads")
     ap.add_argument("--mask-variants", action="store_true",
                     help="also time the other forms of the mask path at the same shape")
     args = ap.parse_args()
@@ -491,6 +545,7 @@ def main() -> int:
         "engine": engine,
     }
     if not args.no_displacement:
+        result["nfa"] = bench_nfa(lib_mod, raw, torch, args.build_repeats, not args.no_cpu_baseline)
         result["displacement"] = bench_displacement(lib_mod, raw, torch, args.build_repeats,
                                                     0 if args.no_cpu_baseline else 30000)
     if mask_variants:

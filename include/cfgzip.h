@@ -283,7 +283,7 @@ int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32
  * the boolean product of the per-byte relations; R of the empty token is the identity.
  *
  *   nfa       int32 [256][S][W(S)]  bit q' of row nfa[b][q] <=> q' may follow q on byte b
- *                                   (pad bits must be 0)
+ *                                   (pad bits must be 0); 16-byte aligned, as is rel_out
  *   S         1 .. 256
  *   rel_out   int32 [V][S][W(S)]    bit q' of row rel_out[t][q] <=> (q, q') in R_t; pad bits 0
  *   hash_out  uint64 [V] or NULL    the hash of cfgzip_signatures taken over the relation read
