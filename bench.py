@@ -165,7 +165,7 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
     tb = torch.from_numpy(vocab.tok_bytes).cuda()
     to = torch.from_numpy(vocab.tok_off).cuda()
     gd = [torch.from_numpy(x).cuda() for x in (g.head, g.byte, g.length, g.body)]
-    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(g.N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(V, g.N), dtype=torch.uint8, device="cuda")
     ws_bld = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, lib_mod.DISP_ROW), dtype=torch.uint8,
                          device="cuda")
     c = torch.empty((V,), dtype=torch.int32, device="cuda")
@@ -205,6 +205,20 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
     }
     log(f"displacement: V={V} N={g.N} P={g.P} C={C} overflow={out['overflow_tokens']} adjacency "
         f"{min(t_adj):.3f} ms, displacements {min(t_disp):.3f} ms, with classes {ms_all:.3f} ms")
+    # the same with rows long enough for every set of this workload (no token left on its own)
+    ws_bld4 = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, 1024), dtype=torch.uint8, device="cuda")
+
+    def run_long():
+        rows, hashes, st = lib_mod.cfgzip_displacements(tb, to, *gd, g.N, row_len=1024, workspace=ws)
+        res["long"] = (lib_mod.cfgzip_build_classes(tb, to, None, rows, hashes, class_of_token=c,
+                                                    rep_of_class=r, workspace=ws_bld4), st)
+
+    run_long(); torch.cuda.synchronize()
+    ms_long = min(event_ms(run_long, stream) for _ in range(repeats))
+    out["row_len_1024"] = {"C": res["long"][0][2], "ms_total_with_classes": round(ms_long, 4),
+                           "overflow_tokens": int((res["long"][1].cpu().numpy() == lib_mod.DISP_OVERFLOW).sum())}
+    log(f"displacement, 1024-entry rows: C={out['row_len_1024']['C']} overflow="
+        f"{out['row_len_1024']['overflow_tokens']} with classes {ms_long:.3f} ms")
     if cpu_sample > 0:
         from oracle import displacement as D
         import oracle

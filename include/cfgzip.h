@@ -244,28 +244,33 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
  * stack-adjacent symbols): the displacement set of every token, i.e. the pairs (input queue,
  * output stack) with which the token can be read by the one-state pushdown automaton of the
  * grammar; the first backtrack may take any production of the first byte.  Each set is
- * written as a row of CFGZIP_DISP_ROW 16-bit values so that equal sets give equal rows:
- *     row[0] = number of pairs; then, per pair, in ascending order of the padded record
- *     (ni, no, queue padded with 0 to 8, stack padded with 0 to 12; stack top first):
- *     ni, no, the ni queue symbols, the no stack symbols; the rest of the row is 0.
- * hash_out[t] is the sum over the pairs of a 64-bit mix of the padded record and hash_seed
- * (a function of the set, for cfgzip_build_classes; never part of a result).
- * Bounds: queue <= 8 symbols, stack <= 12, successors of all live configurations per byte
- * <= 128 (counted before duplicates are dropped), row <= CFGZIP_DISP_ROW entries.  A token
- * that crosses one gets status CFGZIP_DISP_OVERFLOW and a row no other token has
- * (0xFFFF, id & 0xFFFF, id >> 16, 0 ..): it forms a class of its own.
- *     rows_out    uint16 [V][CFGZIP_DISP_ROW], 8-byte aligned
+ * written as a row of row_len 16-bit values so that equal sets give equal rows:
+ *     row[0] = number of pairs; then one record per pair,
+ *     ni, no, the ni queue symbols, the no stack symbols (top first),
+ *     in ascending order of (ni, no), then of the queue, then of the stack; the rest is 0.
+ * hash_out[t] is the sum over the pairs of a 64-bit mix of the record and hash_seed (a
+ * function of the set, for cfgzip_build_classes; never part of a result).
+ * Bounds.  Every token is first taken with queue <= 8, stack <= 12 and at most 128 successors
+ * of all live configurations per byte (counted before duplicates are dropped); a token that
+ * crosses one of these is taken again with queue <= 32, stack <= 32, successors <= 256.  A
+ * token that crosses those too, or whose set needs more than row_len entries, gets status
+ * CFGZIP_DISP_OVERFLOW and a row no other token has (0xFFFF, id & 0xFFFF, id >> 16, 0 ..):
+ * it forms a class of its own.  With status CFGZIP_DISP_OK the row holds exactly the set
+ * Algorithm 1 returns.
+ *     rows_out    uint16 [V][row_len], 8-byte aligned
+ *     row_len     a multiple of 256, 256 .. 4096 (CFGZIP_DISP_ROW is the usual choice)
  *     hash_out    uint64 [V]
  *     status_out  int32 [V] or NULL: CFGZIP_DISP_OK, CFGZIP_DISP_OVERFLOW, or
  *                 CFGZIP_DISP_BAD_GRAMMAR for every token (rows and hashes then 0)
- *     ws          cfgzip_displacements_workspace_bytes(N) bytes, 256-byte aligned (both calls)
- * Grouping: cfgzip_build_classes(tok_bytes, tok_off, V, NULL, CFGZIP_DISP_ROW, rows, hash, NULL, ..).
+ *     ws          cfgzip_displacements_workspace_bytes(V, N) bytes, 256-byte aligned
+ *                 (cfgzip_stack_adjacency alone: V = 0)
+ * Grouping: cfgzip_build_classes(tok_bytes, tok_off, V, NULL, row_len, rows, hash, NULL, ..).
  */
 #define CFGZIP_DISP_ROW 256
 #define CFGZIP_DISP_OK 0
 #define CFGZIP_DISP_OVERFLOW 1
 #define CFGZIP_DISP_BAD_GRAMMAR 2
-size_t cfgzip_displacements_workspace_bytes(int32_t N);
+size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N);
 int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
                            const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
                            int32_t N, int32_t *adj_out, int32_t *invalid_out,
@@ -273,8 +278,9 @@ int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
 int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                          const uint16_t *prod_head, const uint8_t *prod_byte,
                          const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
-                         int32_t N, uint16_t *rows_out, uint64_t *hash_out, int32_t *status_out,
-                         uint64_t hash_seed, void *ws, size_t ws_bytes, void *stream);
+                         int32_t N, uint16_t *rows_out, int32_t row_len, uint64_t *hash_out,
+                         int32_t *status_out, uint64_t hash_seed,
+                         void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Non-deterministic byte automata (paper Section 3.2.1 for a right-linear grammar with several

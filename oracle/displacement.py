@@ -175,20 +175,20 @@ def right_linear_grammar(table, accepting: Iterable[int], reject: int = 0) -> Li
 #   * symbols are integers 0 .. N-1 (N <= 4096), a production body has at most 4 of them;
 #   * a configuration is (input queue, output stack, A_prev); the frontier after p bytes is the
 #     SET of configurations Algorithm 1's recursion reaches at depth p;
-#   * the computation of a token OVERFLOWS when a successor would hold more than MAX_IN queue
-#     symbols or more than MAX_OUT stack symbols, when the successors of one frontier, counted
-#     with multiplicity (one per configuration and matching production), number more than
-#     MAX_FRONTIER, or when the encoded set does not fit a row;
-#   * an overflowing token is given a row and a hash that no other token has (it becomes a
-#     class of its own: a smaller compression, never a wrong one).
+#   * under caps (max_in, max_out, max_frontier) the computation of a token FAILS when a
+#     successor would hold more than max_in queue symbols or more than max_out stack symbols, or
+#     when the successors of one frontier, counted with multiplicity (one per configuration and
+#     matching production), number more than max_frontier;
+#   * a token is first taken under DISP_CAPS_FIRST; if that fails, once more under
+#     DISP_CAPS_SECOND; if that fails too, or if the encoded set does not fit the row, the token
+#     OVERFLOWS: it gets a row and a hash that no other token has (a class of its own: a smaller
+#     compression, never a wrong one).
 # Without overflow the result is the set Algorithm 1 returns; the tests pin that.
 # ---------------------------------------------------------------------------------------------
 
-DISP_MAX_IN = 8
-DISP_MAX_OUT = 12
-DISP_MAX_FRONTIER = 128
-DISP_ROW_LEN = 256
-DISP_REC_LEN = 2 + DISP_MAX_IN + DISP_MAX_OUT   # padded record: ni, no, queue, stack
+DISP_CAPS_FIRST = (8, 12, 128)
+DISP_CAPS_SECOND = (32, 32, 256)
+DISP_ROW_LEN = 256            # default row length; any multiple of 256 up to 4096
 DISP_OK = 0
 DISP_OVERFLOW = 1
 _M64 = (1 << 64) - 1
@@ -205,10 +205,11 @@ def index_productions(productions: Sequence[Production]):
 
 
 def displacement_bounded(token: Sequence[int], productions: Sequence[Production], adjacency,
-                         index=None):
+                         index=None, caps=DISP_CAPS_FIRST):
     """Algorithm 1 taken one byte at a time over the set of live configurations.  Returns the
-    frozenset of (queue, stack) pairs, or None on overflow (see above).  `adjacency` is a set of
-    (Y, Z) pairs; `index` = index_productions(productions) if the caller has it already."""
+    frozenset of (queue, stack) pairs, or None when `caps` are crossed (see above).  `adjacency`
+    is a set of (Y, Z) pairs; `index` = index_productions(productions) if the caller has it."""
+    max_in, max_out, max_frontier = caps
     by_terminal, by_pair = index if index is not None else index_productions(productions)
     frontier = {((), (), None)}
     for ch in token:
@@ -221,19 +222,33 @@ def displacement_bounded(token: Sequence[int], productions: Sequence[Production]
             else:                # pop the top, push the body
                 for beta in by_pair.get((ch, s[0]), ()):
                     successors.append((q, beta + s[1:], s[0]))
-        if len(successors) > DISP_MAX_FRONTIER:
+        if len(successors) > max_frontier:
             return None
         for (q, s, _p) in successors:
-            if len(q) > DISP_MAX_IN or len(s) > DISP_MAX_OUT:
+            if len(q) > max_in or len(s) > max_out:
                 return None
         frontier = set(successors)
     return frozenset((q, s) for (q, s, _p) in frontier)
 
 
+def displacement_two_passes(token, productions, adjacency, index=None):
+    """(pairs or None, pass that produced them: 1, 2, or 0 if both failed)."""
+    pairs = displacement_bounded(token, productions, adjacency, index, DISP_CAPS_FIRST)
+    if pairs is not None:
+        return pairs, 1
+    pairs = displacement_bounded(token, productions, adjacency, index, DISP_CAPS_SECOND)
+    return pairs, (2 if pairs is not None else 0)
+
+
 def displacement_record(pair) -> List[int]:
+    """ni, no, the queue, the stack (top first)."""
     q, s = pair
-    return ([len(q), len(s)] + list(q) + [0] * (DISP_MAX_IN - len(q))
-            + list(s) + [0] * (DISP_MAX_OUT - len(s)))
+    return [len(q), len(s)] + list(q) + list(s)
+
+
+def _record_key(rec: Sequence[int]):
+    """Canonical order: by (ni, no), then the queue, then the stack, entry by entry."""
+    return (rec[0], rec[1], tuple(rec[2:]))
 
 
 def _mix_record(rec: Sequence[int], seed: int) -> int:
@@ -249,24 +264,22 @@ def _mix_record(rec: Sequence[int], seed: int) -> int:
     return h
 
 
-def encode_displacement(pairs, token_id: int, seed: int):
-    """(row of DISP_ROW_LEN 16-bit values, 64-bit hash, status) of one token.
-    Row: [number of pairs, then per pair in ascending order of its padded record:
-    ni, no, queue symbols, stack symbols], zero filled.  Hash: the sum over pairs of
-    _mix_record(padded record).  Overflow: row [0xFFFF, id low 16, id high 16, 0 ..], hash the
-    mix of that row's first DISP_REC_LEN entries."""
-    row = None
+def encode_displacement(pairs, token_id: int, seed: int, row_len: int = DISP_ROW_LEN):
+    """(row of row_len 16-bit values, 64-bit hash, status) of one token.
+    Row: [number of pairs, then the records (ni, no, queue, stack) in canonical order], zero
+    filled.  Hash: the sum over pairs of _mix_record(record).  Overflow (pairs is None, or the
+    row is too short): row [0xFFFF, id low 16, id high 16, 0 ..], hash the mix of those three."""
     if pairs is not None:
-        recs = sorted(displacement_record(p) for p in pairs)
+        recs = sorted((displacement_record(p) for p in pairs), key=_record_key)
         flat = [len(recs)]
         for r in recs:
-            flat += r[:2] + r[2:2 + r[0]] + r[2 + DISP_MAX_IN:2 + DISP_MAX_IN + r[1]]
-        if len(flat) <= DISP_ROW_LEN:
-            row = flat + [0] * (DISP_ROW_LEN - len(flat))
+            flat += r
+        if len(flat) <= row_len:
+            row = flat + [0] * (row_len - len(flat))
             h = sum(_mix_record(r, seed) for r in recs) & _M64
             return row, h, DISP_OK
-    row = [0xFFFF, token_id & 0xFFFF, (token_id >> 16) & 0xFFFF] + [0] * (DISP_ROW_LEN - 3)
-    return row, _mix_record(row[:DISP_REC_LEN], seed), DISP_OVERFLOW
+    head = [0xFFFF, token_id & 0xFFFF, (token_id >> 16) & 0xFFFF]
+    return head + [0] * (row_len - 3), _mix_record(head, seed), DISP_OVERFLOW
 
 
 def decode_displacement(row: Sequence[int]):
@@ -282,20 +295,20 @@ def decode_displacement(row: Sequence[int]):
 
 
 def displacement_rows(tokens: Sequence[bytes], productions: Sequence[Production], seed: int,
-                      adjacency=None):
-    """Rows, hashes and status of a whole vocabulary: (uint16 [V][ROW], uint64 [V], int32 [V])."""
+                      adjacency=None, row_len: int = DISP_ROW_LEN):
+    """Rows, hashes and status of a whole vocabulary:
+    (uint16 [V][row_len], uint64 [V], int32 [V])."""
     import numpy as np
     if adjacency is None:
         adjacency = stack_adjacency(productions)
     V = len(tokens)
-    rows = np.zeros((V, DISP_ROW_LEN), np.uint16)
+    rows = np.zeros((V, row_len), np.uint16)
     hashes = np.zeros(V, np.uint64)
     status = np.zeros(V, np.int32)
     index = index_productions(productions)
     for t, tok in enumerate(tokens):
-        r, h, st = encode_displacement(
-            displacement_bounded(tuple(tok), productions, adjacency, index), t, seed)
-        rows[t], hashes[t], status[t] = r, h, st
+        pairs, _which = displacement_two_passes(tuple(tok), productions, adjacency, index)
+        rows[t], hashes[t], status[t] = encode_displacement(pairs, t, seed, row_len)
     return rows, hashes, status
 
 

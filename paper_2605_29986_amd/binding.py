@@ -80,11 +80,11 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_nfa_signatures.restype = ctypes.c_int
     lib.cfgzip_nfa_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp]
     lib.cfgzip_displacements_workspace_bytes.restype = sz
-    lib.cfgzip_displacements_workspace_bytes.argtypes = [i32]
+    lib.cfgzip_displacements_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_stack_adjacency.restype = ctypes.c_int
     lib.cfgzip_stack_adjacency.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.cfgzip_displacements.restype = ctypes.c_int
-    lib.cfgzip_displacements.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp, u64,
+    lib.cfgzip_displacements.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, u64,
                                          vp, sz, vp]
     _lib = lib
     return lib
@@ -331,7 +331,7 @@ def cfgzip_stack_adjacency(prod_head: torch.Tensor, prod_byte: torch.Tensor,
     adj = torch.empty((N, words_for(N)), dtype=torch.int32, device=dev)
     invalid = torch.empty((1,), dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(N), dev)
+        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(0, N), dev)
     h, b, ln, bd, P = _grammar_args(prod_head, prod_byte, prod_len, prod_body)
     rc = lib.cfgzip_stack_adjacency(h, b, ln, bd, P, N, adj.data_ptr(), invalid.data_ptr(),
                                     workspace.data_ptr(), workspace.numel(), _stream(stream))
@@ -341,22 +341,22 @@ def cfgzip_stack_adjacency(prod_head: torch.Tensor, prod_byte: torch.Tensor,
 
 def cfgzip_displacements(tok_bytes: torch.Tensor, tok_off: torch.Tensor, prod_head: torch.Tensor,
                          prod_byte: torch.Tensor, prod_len: torch.Tensor, prod_body: torch.Tensor,
-                         N: int, *, hash_seed: int = DEFAULT_HASH_SEED,
+                         N: int, *, row_len: int = DISP_ROW, hash_seed: int = DEFAULT_HASH_SEED,
                          workspace: Optional[torch.Tensor] = None, stream=None):
-    """(rows uint16 [V, DISP_ROW], hash int64 [V] holding uint64 bit patterns, status int32 [V])."""
+    """(rows uint16 [V, row_len], hash int64 [V] holding uint64 bit patterns, status int32 [V])."""
     lib = load_library()
     V = tok_off.numel() - 1
     dev = tok_off.device
-    rows = torch.empty((V, DISP_ROW), dtype=torch.uint16, device=dev)
+    rows = torch.empty((V, row_len), dtype=torch.uint16, device=dev)
     hashes = torch.empty((V,), dtype=torch.int64, device=dev)
     status = torch.empty((V,), dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(N), dev)
+        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(V, N), dev)
     h, b, ln, bd, P = _grammar_args(prod_head, prod_byte, prod_len, prod_body)
     rc = lib.cfgzip_displacements(
         _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
         _dev(tok_off, torch.int64, "tok_off"), V, h, b, ln, bd, P, N,
-        rows.data_ptr(), hashes.data_ptr(), status.data_ptr(),
+        rows.data_ptr(), row_len, hashes.data_ptr(), status.data_ptr(),
         ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF),
         workspace.data_ptr(), workspace.numel(), _stream(stream))
     _check("cfgzip_displacements", rc)

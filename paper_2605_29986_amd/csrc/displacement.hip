@@ -17,8 +17,11 @@
 // builder can group tokens by comparing rows.
 //
 // Everything is bounded: queue, stack, number of successors per byte and row length each have
-// a cap; a token that crosses one gets a row and hash of its own (its class is a singleton,
-// which costs compression and never correctness).
+// a cap.  All tokens are first taken under small caps (little LDS per token, many waves per
+// compute unit); the few that cross them are queued and taken again under larger ones by a
+// second, persistent kernel.  A token that crosses those too, or whose set does not fit the row,
+// gets a row and hash of its own (its class is a singleton, which costs compression and never
+// correctness).
 
 #include <algorithm>
 
@@ -28,24 +31,30 @@ namespace cfgzip {
 namespace {
 
 constexpr int kMaxBody = 4;
-constexpr int kMaxIn = 8;
-constexpr int kMaxOut = 12;
-constexpr int kMaxFrontier = 128;
-constexpr int kRowLen = 256;
-constexpr int kRecLen = 2 + kMaxIn + kMaxOut;  // ni, no, queue, stack
-constexpr int kPrevAt = kRecLen;               // symbol consumed last, "none" before any
+constexpr int kRowChunk = 256;                 // row entries staged in LDS at a time
+constexpr int kMaxRowLen = 4096;
 constexpr int kMaxSymbols = 4096;
 constexpr int kMaxByteSymbols = 255;           // up to here a symbol (and "none") fits a byte
 
-// A record in LDS: kRecLen entries, the symbol consumed last, zero padding up to an odd number
-// of 32-bit words (lanes that read one record each then hit different banks).  Grammars with
-// at most kMaxByteSymbols symbols use byte entries: half the LDS per token, twice the waves
-// per compute unit.
-template <typename Sym>
+// caps of the first pass over all tokens and of the second pass over those it could not finish
+constexpr int kIn1 = 8, kOut1 = 12, kFrontier1 = 128;
+constexpr int kIn2 = 32, kOut2 = 32, kFrontier2 = 256;
+// the second pass keeps the current byte's productions and the relation in LDS when they fit
+constexpr int kStageCap = 128;      // productions of one terminal
+constexpr int kAdjLdsWords = 512;   // N * W(N) words: N <= 128
+
+// A record in LDS: ni, no, MAX_IN queue entries, MAX_OUT stack entries (top first), the symbol
+// consumed last, zero padding up to an odd number of 32-bit words (lanes that read one record
+// each then hit different banks).  Grammars with at most kMaxByteSymbols symbols use byte
+// entries: half the LDS per token, twice the waves per compute unit.
+template <typename Sym, int MAX_IN, int MAX_OUT>
 struct Rec {
-    static constexpr int kStride = sizeof(Sym) == 1 ? 28 : 26;  // entries: 7 or 13 words
-    static constexpr int kWords = kStride * (int)sizeof(Sym) / 4;
-    static constexpr int kOrderWords = (kRecLen * (int)sizeof(Sym) + 3) / 4;
+    static constexpr int kLen = 2 + MAX_IN + MAX_OUT;
+    static constexpr int kStackAt = 2 + MAX_IN;
+    static constexpr int kPrevAt = kLen;  // "none" before anything was consumed
+    static constexpr int kWords = (((kLen + 1) * (int)sizeof(Sym) + 3) / 4) | 1;
+    static constexpr int kStride = kWords * 4 / (int)sizeof(Sym);
+    static constexpr int kOrderWords = (kLen * (int)sizeof(Sym) + 3) / 4;
     static constexpr int kBits = 8 * (int)sizeof(Sym);
     static constexpr int kNone = (1 << kBits) - 1;
 };
@@ -55,8 +64,10 @@ constexpr int kStatusOverflow = 1;
 constexpr int kStatusBadGrammar = 2;
 
 struct GrammarHeader {
-    int32_t invalid;  // set by the index kernel when the productions break a stated rule
-    int32_t pad[63];
+    int32_t invalid;      // set by the index kernel when the productions break a stated rule
+    int32_t retry_count;  // tokens the first pass handed to the second
+    int32_t retry_next;   // next entry of the retry list to be taken
+    int32_t pad[61];
 };
 
 struct Grammar {
@@ -74,11 +85,12 @@ struct GrammarWorkspace {
     uint32_t *reach[2]; // [N][W]: reachability over "right-most body symbol" edges
     uint32_t *adj;      // [N][W]: bit Y of row Z <=> (Y, Z) stack-adjacent
     int32_t *pair_first;  // [256][N]: 1 + index of the first production with (terminal, head), 0 = none
+    int32_t *retry_list;  // [V]: ids of the tokens for the second pass
     size_t clear_words; // words from hdr to the end that start at zero
     size_t bytes;
 };
 
-GrammarWorkspace carve_grammar_ws(void *ws, int N) {
+GrammarWorkspace carve_grammar_ws(void *ws, int N, int V) {
     GrammarWorkspace g{};
     const size_t W = (size_t)ceil_div(N, 32);
     size_t off = 0;
@@ -95,6 +107,7 @@ GrammarWorkspace carve_grammar_ws(void *ws, int N) {
     g.pair_first = reinterpret_cast<int32_t *>(take((size_t)256 * N * 4));
     g.clear_words = off / 4;
     g.reach[1] = reinterpret_cast<uint32_t *>(take((size_t)N * W * 4));  // fully written
+    g.retry_list = reinterpret_cast<int32_t *>(take((size_t)V * 4));
     g.bytes = off;
     return g;
 }
@@ -220,7 +233,7 @@ int enqueue_grammar_tables(const Grammar &g, const GrammarWorkspace &w, hipStrea
 
 struct DisplacementArgs {
     Grammar g;
-    const GrammarHeader *hdr;
+    GrammarHeader *hdr;
     const int32_t *byte_off;
     const int32_t *pair_first;
     const uint32_t *adj;
@@ -229,38 +242,46 @@ struct DisplacementArgs {
     uint16_t *rows;
     uint64_t *hash;
     int32_t *status;
+    int32_t *retry_list;
     uint64_t seed;
+    int V, row_len;
 };
 
-template <typename Sym>
-__device__ inline uint64_t mix_record(const Sym *rec, uint64_t seed) {
-    uint64_t h = seed ^ 0x9E3779B97F4A7C15ull;
-    for (int k = 0; k < kRecLen; ++k) h = (h ^ rec[k]) * 0x100000001B3ull;
-    h ^= h >> 30;
-    h *= 0xBF58476D1CE4E5B9ull;
-    h ^= h >> 27;
-    h *= 0x94D049BB133111EBull;
-    h ^= h >> 31;
-    return h;
-}
+// 64-bit mix of a record's entries ni, no, queue, stack (FNV-1a style pass, SplitMix64 finaliser)
+struct RecordMix {
+    uint64_t h;
+    __device__ explicit RecordMix(uint64_t seed) : h(seed ^ 0x9E3779B97F4A7C15ull) {}
+    __device__ void add(uint32_t x) { h = (h ^ x) * 0x100000001B3ull; }
+    __device__ uint64_t done() const {
+        uint64_t z = h;
+        z ^= z >> 30;
+        z *= 0xBF58476D1CE4E5B9ull;
+        z ^= z >> 27;
+        z *= 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        return z;
+    }
+};
 
-template <typename Sym>
+template <typename R>
 __device__ inline bool records_equal(const uint32_t *a, const uint32_t *b) {
-    for (int k = 0; k < Rec<Sym>::kWords; ++k)
+    for (int k = 0; k < R::kWords; ++k)
         if (a[k] != b[k]) return false;
     return true;
 }
 
-// ascending order of the entries: in the first word that differs, the lowest entry that
-// differs decides (entry e of a word sits at bits e * kBits and up).  Called once the symbol
-// consumed last has been cleared, so the words beyond entry kRecLen - 1 are equal.
-template <typename Sym>
+// Canonical order: by (ni, no), then the queue, then the stack.  With equal ni and no the
+// padding of two records sits at the same entries, so this is the ascending order of the padded
+// entries: in the first word that differs, the lowest entry that differs decides (entry e of a
+// word sits at bits e * kBits and up).  Called once the symbol consumed last has been cleared,
+// so the words beyond the last entry are equal.
+template <typename R>
 __device__ inline bool record_less(const uint32_t *a, const uint32_t *b) {
-    for (int k = 0; k < Rec<Sym>::kOrderWords; ++k) {
+    for (int k = 0; k < R::kOrderWords; ++k) {
         const uint32_t x = a[k], y = b[k];
         if (x != y) {
-            const int shift = (__ffs(x ^ y) - 1) & ~(Rec<Sym>::kBits - 1);
-            const uint32_t mask = (uint32_t)Rec<Sym>::kNone;
+            const int shift = (__ffs(x ^ y) - 1) & ~(R::kBits - 1);
+            const uint32_t mask = (uint32_t)R::kNone;
             return ((x >> shift) & mask) < ((y >> shift) & mask);
         }
     }
@@ -268,18 +289,17 @@ __device__ inline bool record_less(const uint32_t *a, const uint32_t *b) {
 }
 
 // Drops every record of src[0..m) that equals an earlier one and packs the rest into dst;
-// returns how many are left.  Called by the whole wave; m <= kMaxFrontier.
-template <typename Sym>
-__device__ int drop_duplicates(const Sym (*src)[Rec<Sym>::kStride], Sym (*dst)[Rec<Sym>::kStride],
-                               int m, int lane) {
+// returns how many are left.  Called by the whole wave; m <= FRONTIER.
+template <typename Sym, typename R, int FRONTIER>
+__device__ int drop_duplicates(const Sym (*src)[R::kStride], Sym (*dst)[R::kStride], int m, int lane) {
     int kept = 0;
-    for (int base = 0; base < kMaxFrontier; base += 64) {
+    for (int base = 0; base < FRONTIER; base += 64) {
         const int i = base + lane;
         bool keep = i < m;
         if (keep) {
             const uint32_t *mine = reinterpret_cast<const uint32_t *>(src[i]);
             for (int j = 0; j < i; ++j)
-                if (records_equal<Sym>(mine, reinterpret_cast<const uint32_t *>(src[j]))) {
+                if (records_equal<R>(mine, reinterpret_cast<const uint32_t *>(src[j]))) {
                     keep = false;
                     break;
                 }
@@ -289,79 +309,99 @@ __device__ int drop_duplicates(const Sym (*src)[Rec<Sym>::kStride], Sym (*dst)[R
             const int pos = kept + __popcll(mask & ((1ull << lane) - 1ull));
             const uint32_t *s = reinterpret_cast<const uint32_t *>(src[i]);
             uint32_t *d = reinterpret_cast<uint32_t *>(dst[pos]);
-            for (int k = 0; k < Rec<Sym>::kWords; ++k) d[k] = s[k];
+            for (int k = 0; k < R::kWords; ++k) d[k] = s[k];
         }
         kept += __popcll(mask);
     }
     return kept;
 }
 
-template <typename Sym>
-__global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
-    constexpr int kRecStride = Rec<Sym>::kStride;
-    constexpr int kNone = Rec<Sym>::kNone;
-    __shared__ __align__(8) Sym buf[2][kMaxFrontier][kRecStride];
-    __shared__ __align__(8) uint16_t row[kRowLen];
-    __shared__ int n_emit, crossed, total_len;
-    __shared__ unsigned long long hash_sum;
+__device__ __forceinline__ uint32_t body_at(uint2 body, int k) {
+    return ((k < 2 ? body.x : body.y) >> (16 * (k & 1))) & 0xFFFFu;
+}
 
-    const int t = blockIdx.x, lane = threadIdx.x;
+// LDS of one workgroup (one wave)
+template <typename Sym, typename R, int FRONTIER, bool STAGE>
+struct TokenLds {
+    __align__(8) Sym buf[2][FRONTIER][R::kStride];
+    __align__(8) uint16_t row[kRowChunk];
+    int n_emit, crossed, total_len, next_item;
+    unsigned long long hash_sum;
+    // STAGE only: the productions lo .. hi-1 of the byte being read, and the relation
+    __align__(8) uint2 sp_body[STAGE ? kStageCap : 1];
+    uint16_t sp_head[STAGE ? kStageCap : 1];
+    uint8_t sp_len[STAGE ? kStageCap : 1];
+    uint32_t adj[STAGE ? kAdjLdsWords : 1];
+};
+
+// The displacement of token t under the caps MAX_IN, MAX_OUT, FRONTIER, by the whole wave.
+// FIRST_PASS: a token that crosses a cap is appended to the retry list (and still gets the
+// overflow row, which the second pass overwrites if it gets through).
+template <typename Sym, int MAX_IN, int MAX_OUT, int FRONTIER, bool FIRST_PASS, bool STAGE>
+__device__ void token_displacement(const DisplacementArgs &a, int t,
+                                   TokenLds<Sym, Rec<Sym, MAX_IN, MAX_OUT>, FRONTIER, STAGE> &L,
+                                   bool adj_in_lds) {
+    using R = Rec<Sym, MAX_IN, MAX_OUT>;
+    constexpr int kStride = R::kStride;
+    constexpr int kNone = R::kNone;
+    constexpr int kPerLane = FRONTIER / 64;
+    const int lane = threadIdx.x;
     const Grammar &g = a.g;
-    uint16_t *out_row = a.rows + (size_t)t * kRowLen;
-    if (a.hdr->invalid) {  // the same value for every lane
-        reinterpret_cast<uint2 *>(out_row)[lane] = make_uint2(0, 0);
-        if (lane == 0) {
-            a.hash[t] = 0;
-            if (a.status) a.status[t] = kStatusBadGrammar;
-        }
-        return;
-    }
     const int64_t b0 = a.tok_off[t], b1 = a.tok_off[t + 1];
 
     // the start configuration: nothing consumed, nothing pushed
-    if (lane < kRecStride) buf[0][0][lane] = (Sym)(lane == kPrevAt ? kNone : 0);
-    if (lane == 0) crossed = 0;
-    int n = 1, cur = 0;
-    bool overflow = false;
+    for (int k = lane; k < kStride; k += 64) L.buf[0][0][k] = (Sym)(k == R::kPrevAt ? kNone : 0);
+    if (lane == 0) L.crossed = 0;
+    int n = 1;
+    bool caps_crossed = false;
     __syncthreads();
 
+    Sym(*src)[kStride] = L.buf[0];  // the live set is always handed back to buf[0]
+    Sym(*dst)[kStride] = L.buf[1];
     for (int64_t p = b0; p < b1 && n > 0; ++p) {
         const int ch = a.tok_bytes[p];
         const int lo = a.byte_off[ch], hi = a.byte_off[ch + 1];
-        if (lane == 0) n_emit = 0;
+        if (lane == 0) L.n_emit = 0;
+        const bool staged = STAGE && hi - lo <= kStageCap;  // the same for every lane
+        if (staged)
+            for (int i = lo + lane; i < hi; i += 64) {
+                L.sp_head[i - lo] = g.head[i];
+                L.sp_len[i - lo] = g.len[i];
+                L.sp_body[i - lo] = reinterpret_cast<const uint2 *>(g.body)[i];
+            }
         __syncthreads();
-        Sym(*src)[kRecStride] = buf[cur];
-        Sym(*dst)[kRecStride] = buf[cur ^ 1];
+        auto head_of = [&](int i) -> int { return staged ? L.sp_head[i - lo] : g.head[i]; };
+        auto len_of = [&](int i) -> int { return staged ? L.sp_len[i - lo] : g.len[i]; };
+        auto body_of = [&](int i) -> uint2 {
+            return staged ? L.sp_body[i - lo] : reinterpret_cast<const uint2 *>(g.body)[i];
+        };
 
         // pops: a lane per configuration (few productions per (terminal, head))
         for (int c = lane; c < n; c += 64) {
             const Sym *rec = src[c];
             const int no = rec[1];
             if (no == 0) continue;
-            const int top = rec[2 + kMaxIn];
+            const int top = rec[R::kStackAt];
             const int first = a.pair_first[(size_t)ch * g.N + top] - 1;
             if (first < 0) continue;
-            for (int i = first; i < hi && g.head[i] == top; ++i) {
-                const int len = g.len[i];
-                const uint2 body2 = reinterpret_cast<const uint2 *>(g.body)[i];
-                const uint16_t body[kMaxBody] = {(uint16_t)(body2.x & 0xFFFF), (uint16_t)(body2.x >> 16),
-                                                 (uint16_t)(body2.y & 0xFFFF), (uint16_t)(body2.y >> 16)};
-                const int slot = atomicAdd(&n_emit, 1);
-                if (no - 1 + len > kMaxOut) {
-                    crossed = 1;
-                } else if (slot < kMaxFrontier) {
+            for (int i = first; i < hi && head_of(i) == top; ++i) {
+                const int len = len_of(i);
+                const uint2 body = body_of(i);
+                const int slot = atomicAdd(&L.n_emit, 1);
+                if (no - 1 + len > MAX_OUT) {
+                    L.crossed = 1;
+                } else if (slot < FRONTIER) {
+                    // the old record, then the stack rewritten: the body on top of what was below
                     Sym *o = dst[slot];
-                    o[0] = rec[0];
-                    o[1] = (Sym)(no - 1 + len);
-                    for (int k = 0; k < kMaxIn; ++k) o[2 + k] = rec[2 + k];
-                    for (int k = 0; k < kMaxOut; ++k) {
-                        Sym v = 0;
-                        if (k < len) v = (Sym)body[k];
-                        else if (k - len + 1 < no) v = rec[2 + kMaxIn + k - len + 1];
-                        o[2 + kMaxIn + k] = v;
-                    }
-                    o[kPrevAt] = (Sym)top;
-                    for (int k = kPrevAt + 1; k < kRecStride; ++k) o[k] = 0;
+                    const uint32_t *rw = reinterpret_cast<const uint32_t *>(rec);
+                    uint32_t *ow = reinterpret_cast<uint32_t *>(o);
+                    for (int k = 0; k < R::kWords; ++k) ow[k] = rw[k];
+                    const int new_no = no - 1 + len;
+                    for (int k = 0; k < new_no; ++k)
+                        o[R::kStackAt + k] = k < len ? (Sym)body_at(body, k) : rec[R::kStackAt + k - len + 1];
+                    if (len == 0) o[R::kStackAt + new_no] = 0;  // the stack got shorter by one
+                    o[1] = (Sym)new_no;
+                    o[R::kPrevAt] = (Sym)top;
                 }
             }
         }
@@ -370,102 +410,183 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
             const Sym *rec = src[c];
             if (rec[1] != 0) continue;  // the same for every lane
             const int ni = rec[0];
-            const int prev = rec[kPrevAt];
+            const int prev = rec[R::kPrevAt];
             for (int i = lo + lane; i < hi; i += 64) {
-                const int A = g.head[i];
-                if (prev != kNone &&
-                    !((a.adj[(size_t)A * g.W + (prev >> 5)] >> (prev & 31)) & 1u))
-                    continue;
-                const int len = g.len[i];
-                const uint2 body2 = reinterpret_cast<const uint2 *>(g.body)[i];
-                const uint16_t body[kMaxBody] = {(uint16_t)(body2.x & 0xFFFF), (uint16_t)(body2.x >> 16),
-                                                 (uint16_t)(body2.y & 0xFFFF), (uint16_t)(body2.y >> 16)};
-                const int slot = atomicAdd(&n_emit, 1);
-                if (ni + 1 > kMaxIn) {
-                    crossed = 1;
-                } else if (slot < kMaxFrontier) {
+                const int A = head_of(i);
+                if (prev != kNone) {
+                    const size_t w = (size_t)A * g.W + (prev >> 5);
+                    const uint32_t bits = (STAGE && adj_in_lds) ? L.adj[w] : a.adj[w];
+                    if (!((bits >> (prev & 31)) & 1u)) continue;
+                }
+                const int len = len_of(i);
+                const uint2 body = body_of(i);
+                const int slot = atomicAdd(&L.n_emit, 1);
+                if (ni + 1 > MAX_IN) {
+                    L.crossed = 1;
+                } else if (slot < FRONTIER) {
+                    // the old record (its stack is empty) with A appended to the queue, the body
+                    // as the new stack
                     Sym *o = dst[slot];
+                    const uint32_t *rw = reinterpret_cast<const uint32_t *>(rec);
+                    uint32_t *ow = reinterpret_cast<uint32_t *>(o);
+                    for (int k = 0; k < R::kWords; ++k) ow[k] = rw[k];
                     o[0] = (Sym)(ni + 1);
                     o[1] = (Sym)len;
-                    for (int k = 0; k < kMaxIn; ++k)
-                        o[2 + k] = k < ni ? rec[2 + k] : (k == ni ? (Sym)A : (Sym)0);
-                    for (int k = 0; k < kMaxOut; ++k)
-                        o[2 + kMaxIn + k] = k < len ? (Sym)body[k] : (Sym)0;
-                    o[kPrevAt] = (Sym)A;
-                    for (int k = kPrevAt + 1; k < kRecStride; ++k) o[k] = 0;
+                    o[2 + ni] = (Sym)A;
+                    for (int k = 0; k < len; ++k) o[R::kStackAt + k] = (Sym)body_at(body, k);
+                    o[R::kPrevAt] = (Sym)A;
                 }
             }
         }
         __syncthreads();
-        const int m = n_emit;
-        if (m > kMaxFrontier || crossed) {
-            overflow = true;
+        const int m = L.n_emit;
+        if (m > FRONTIER || L.crossed) {
+            caps_crossed = true;
             break;
         }
-        n = drop_duplicates<Sym>(dst, src, m, lane);  // back into the buffer just read
+        n = drop_duplicates<Sym, R, FRONTIER>(dst, src, m, lane);  // back into the buffer just read
         __syncthreads();
     }
 
-    Sym(*front)[kRecStride] = buf[cur];
-    Sym(*other)[kRecStride] = buf[cur ^ 1];
-    int start0 = 0, start1 = 0;  // where this lane's records begin in the row
-    if (!overflow) {
+    int start[kPerLane];  // where this lane's records begin in the row
+    bool overflow = caps_crossed;
+    int total = 1;
+    if (!caps_crossed) {
         // the displacement forgets the symbol consumed last
-        for (int c = lane; c < n; c += 64) front[c][kPrevAt] = 0;
+        for (int c = lane; c < n; c += 64) src[c][R::kPrevAt] = 0;
         if (lane == 0) {
-            total_len = 1;
-            hash_sum = 0;
+            L.total_len = 1;
+            L.hash_sum = 0;
         }
         __syncthreads();
-        n = drop_duplicates<Sym>(front, other, n, lane);
+        n = drop_duplicates<Sym, R, FRONTIER>(src, dst, n, lane);
         __syncthreads();
         // canonical order by counting: a record starts behind all smaller ones
-        for (int c = lane, u = 0; c < n; c += 64, ++u) {
-            const uint32_t *mine = reinterpret_cast<const uint32_t *>(other[c]);
-            int start = 1;
-            for (int j = 0; j < n; ++j) {
-                const Sym *r = other[j];
-                if (j != c && record_less<Sym>(reinterpret_cast<const uint32_t *>(r), mine))
-                    start += 2 + r[0] + r[1];
+#pragma unroll
+        for (int u = 0; u < kPerLane; ++u) {
+            const int c = lane + 64 * u;
+            start[u] = 1;
+            if (c < n) {
+                const uint32_t *mine = reinterpret_cast<const uint32_t *>(dst[c]);
+                for (int j = 0; j < n; ++j) {
+                    const Sym *r = dst[j];
+                    if (j != c && record_less<R>(reinterpret_cast<const uint32_t *>(r), mine))
+                        start[u] += 2 + r[0] + r[1];
+                }
+                atomicAdd(&L.total_len, 2 + dst[c][0] + dst[c][1]);
             }
-            if (u == 0) start0 = start; else start1 = start;
-            atomicAdd(&total_len, 2 + other[c][0] + other[c][1]);
         }
         __syncthreads();
-        if (total_len > kRowLen) overflow = true;
+        total = L.total_len;
+        if (total > a.row_len) overflow = true;
     }
-    reinterpret_cast<uint2 *>(row)[lane] = make_uint2(0, 0);
-    __syncthreads();
+
     if (overflow) {
         if (lane == 0) {
-            row[0] = 0xFFFF;
-            row[1] = (uint16_t)(t & 0xFFFF);
-            row[2] = (uint16_t)((uint32_t)t >> 16);
-        }
-        __syncthreads();
-        if (lane == 0) {
-            a.hash[t] = mix_record(row, a.seed);
+            RecordMix mix(a.seed);
+            mix.add(0xFFFFu);
+            mix.add((uint32_t)t & 0xFFFFu);
+            mix.add((uint32_t)t >> 16);
+            a.hash[t] = mix.done();
             if (a.status) a.status[t] = kStatusOverflow;
+            if (FIRST_PASS && caps_crossed) a.retry_list[atomicAdd(&a.hdr->retry_count, 1)] = t;
         }
     } else {
-        if (lane == 0) row[0] = (uint16_t)n;
-        for (int c = lane, u = 0; c < n; c += 64, ++u) {
-            const Sym *r = other[c];
-            int pos = u == 0 ? start0 : start1;
-            const int ni = r[0], no = r[1];
-            row[pos++] = (uint16_t)ni;
-            row[pos++] = (uint16_t)no;
-            for (int k = 0; k < ni; ++k) row[pos++] = r[2 + k];
-            for (int k = 0; k < no; ++k) row[pos++] = r[2 + kMaxIn + k];
-            atomicAdd(&hash_sum, (unsigned long long)mix_record(r, a.seed));
+        uint64_t h = 0;
+#pragma unroll
+        for (int u = 0; u < kPerLane; ++u) {
+            const int c = lane + 64 * u;
+            if (c < n) {
+                const Sym *r = dst[c];
+                RecordMix mix(a.seed);
+                mix.add(r[0]);
+                mix.add(r[1]);
+                for (int k = 0; k < r[0]; ++k) mix.add(r[2 + k]);
+                for (int k = 0; k < r[1]; ++k) mix.add(r[R::kStackAt + k]);
+                h += mix.done();
+            }
+        }
+        if (h) atomicAdd(&L.hash_sum, (unsigned long long)h);
+    }
+
+    // the row, kRowChunk entries at a time through LDS; chunks behind the data are plain zeros
+    uint16_t *out_row = a.rows + (size_t)t * a.row_len;
+    const int used = overflow ? 3 : total;
+    for (int base = 0; base < a.row_len; base += kRowChunk) {
+        uint2 *out = reinterpret_cast<uint2 *>(out_row + base);
+        if (base >= used) {  // the same for every lane
+            out[lane] = make_uint2(0, 0);
+            continue;
+        }
+        reinterpret_cast<uint2 *>(L.row)[lane] = make_uint2(0, 0);
+        __syncthreads();
+        if (overflow) {
+            if (lane == 0) {
+                L.row[0] = 0xFFFF;
+                L.row[1] = (uint16_t)(t & 0xFFFF);
+                L.row[2] = (uint16_t)((uint32_t)t >> 16);
+            }
+        } else {
+            if (lane == 0 && base == 0) L.row[0] = (uint16_t)n;
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u) {
+                const int c = lane + 64 * u;
+                if (c >= n) continue;
+                const Sym *r = dst[c];
+                const int ni = r[0], no = r[1];
+                const int first = start[u] - base;  // position of the record's first entry in this chunk
+                if (first >= kRowChunk || first + 2 + ni + no <= 0) continue;
+                for (int e = max(0, -first); e < 2 + ni + no && first + e < kRowChunk; ++e) {
+                    const int v = e < 2 ? r[e] : (e < 2 + ni ? r[e] : r[R::kStackAt + e - 2 - ni]);
+                    L.row[first + e] = (uint16_t)v;
+                }
+            }
         }
         __syncthreads();
-        if (lane == 0) {
-            a.hash[t] = hash_sum;
-            if (a.status) a.status[t] = kStatusOk;
-        }
+        out[lane] = reinterpret_cast<const uint2 *>(L.row)[lane];
     }
-    reinterpret_cast<uint2 *>(out_row)[lane] = reinterpret_cast<const uint2 *>(row)[lane];
+    __syncthreads();
+    if (!overflow && lane == 0) {
+        a.hash[t] = L.hash_sum;
+        if (a.status) a.status[t] = kStatusOk;
+    }
+    __syncthreads();  // the next token of a persistent workgroup starts from settled LDS
+}
+
+// first pass: a workgroup of one wave per token
+template <typename Sym>
+__global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
+    __shared__ TokenLds<Sym, Rec<Sym, kIn1, kOut1>, kFrontier1, false> lds;
+    const int t = blockIdx.x;
+    if (a.hdr->invalid) {  // the same value for every lane
+        for (int base = 0; base < a.row_len; base += kRowChunk)
+            reinterpret_cast<uint2 *>(a.rows + (size_t)t * a.row_len + base)[threadIdx.x] = make_uint2(0, 0);
+        if (threadIdx.x == 0) {
+            a.hash[t] = 0;
+            if (a.status) a.status[t] = kStatusBadGrammar;
+        }
+        return;
+    }
+    token_displacement<Sym, kIn1, kOut1, kFrontier1, true, false>(a, t, lds, false);
+}
+
+// second pass: persistent workgroups of one wave take the retry list entry by entry
+template <typename Sym>
+__global__ __launch_bounds__(64) void displacement_retry_kernel(DisplacementArgs a) {
+    __shared__ TokenLds<Sym, Rec<Sym, kIn2, kOut2>, kFrontier2, true> lds;
+    const int count = min(a.hdr->retry_count, a.V);
+    if (count == 0) return;
+    const bool adj_in_lds = a.g.N * a.g.W <= kAdjLdsWords;
+    if (adj_in_lds)
+        for (int i = threadIdx.x; i < a.g.N * a.g.W; i += 64) lds.adj[i] = a.adj[i];
+    for (;;) {
+        if (threadIdx.x == 0) lds.next_item = atomicAdd(&a.hdr->retry_next, 1);
+        __syncthreads();
+        const int i = lds.next_item;
+        __syncthreads();
+        if (i >= count) break;  // the same for every lane
+        token_displacement<Sym, kIn2, kOut2, kFrontier2, false, true>(a, a.retry_list[i], lds, adj_in_lds);
+    }
 }
 
 int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, const uint8_t *prod_len,
@@ -481,9 +602,9 @@ int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, cons
 
 using namespace cfgzip;
 
-extern "C" size_t cfgzip_displacements_workspace_bytes(int32_t N) {
-    if (N <= 0 || N > kMaxSymbols) return 0;
-    return carve_grammar_ws(nullptr, N).bytes;
+extern "C" size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N) {
+    if (V < 0 || N <= 0 || N > kMaxSymbols) return 0;
+    return carve_grammar_ws(nullptr, N, V).bytes;
 }
 
 extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
@@ -493,7 +614,7 @@ extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *
     CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_len, prod_body, P, N));
     if (!adj_out || !aligned_to(adj_out, 4) || !aligned_to(invalid_out, 4)) return CFGZIP_E_INVALID;
     if (!ws || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
-    GrammarWorkspace w = carve_grammar_ws(ws, N);
+    GrammarWorkspace w = carve_grammar_ws(ws, N, 0);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     Grammar g{prod_head, prod_byte, prod_len, prod_body, P, N, (int)ceil_div(N, 32)};
@@ -514,16 +635,17 @@ extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *
 extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                                     const uint16_t *prod_head, const uint8_t *prod_byte,
                                     const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
-                                    int32_t N, uint16_t *rows_out, uint64_t *hash_out,
-                                    int32_t *status_out, uint64_t hash_seed, void *ws,
-                                    size_t ws_bytes, void *stream_) {
+                                    int32_t N, uint16_t *rows_out, int32_t row_len,
+                                    uint64_t *hash_out, int32_t *status_out, uint64_t hash_seed,
+                                    void *ws, size_t ws_bytes, void *stream_) {
     CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_len, prod_body, P, N));
     if (!tok_off || !rows_out || !hash_out || V <= 0) return CFGZIP_E_INVALID;
+    if (row_len < kRowChunk || row_len > kMaxRowLen || row_len % kRowChunk) return CFGZIP_E_INVALID;
     if (!aligned_to(tok_off, 8) || !aligned_to(rows_out, 8) || !aligned_to(hash_out, 8) ||
         !aligned_to(status_out, 4))
         return CFGZIP_E_INVALID;
     if (!ws || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
-    GrammarWorkspace w = carve_grammar_ws(ws, N);
+    GrammarWorkspace w = carve_grammar_ws(ws, N, V);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     Grammar g{prod_head, prod_byte, prod_len, prod_body, P, N, (int)ceil_div(N, 32)};
@@ -539,10 +661,30 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
     a.rows = rows_out;
     a.hash = hash_out;
     a.status = status_out;
+    a.retry_list = w.retry_list;
     a.seed = hash_seed;
-    if (N <= kMaxByteSymbols)
+    a.V = V;
+    a.row_len = row_len;
+    int n_cu = 256;
+    {
+        int dev = 0;
+        CFGZIP_TRY(check_hip(hipGetDevice(&dev)));
+        CFGZIP_TRY(check_hip(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)));
+        if (n_cu <= 0) n_cu = 256;
+    }
+    const bool bytes = N <= kMaxByteSymbols;
+    // second pass: as many one-wave workgroups as the LDS of all compute units holds at once
+    const size_t lds2 = bytes ? sizeof(TokenLds<uint8_t, Rec<uint8_t, kIn2, kOut2>, kFrontier2, true>)
+                              : sizeof(TokenLds<uint16_t, Rec<uint16_t, kIn2, kOut2>, kFrontier2, true>);
+    const unsigned grid2 = (unsigned)std::min<int64_t>(V, (int64_t)n_cu * std::max<size_t>(1, (160 * 1024) / lds2));
+    if (bytes) {
         hipLaunchKernelGGL(displacement_kernel<uint8_t>, dim3((unsigned)V), dim3(64), 0, stream, a);
-    else
+        CFGZIP_TRY(check_launch());
+        hipLaunchKernelGGL(displacement_retry_kernel<uint8_t>, dim3(grid2), dim3(64), 0, stream, a);
+    } else {
         hipLaunchKernelGGL(displacement_kernel<uint16_t>, dim3((unsigned)V), dim3(64), 0, stream, a);
+        CFGZIP_TRY(check_launch());
+        hipLaunchKernelGGL(displacement_retry_kernel<uint16_t>, dim3(grid2), dim3(64), 0, stream, a);
+    }
     return check_launch();
 }

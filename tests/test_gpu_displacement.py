@@ -42,13 +42,14 @@ def _check_adjacency(lib, g: Grammar):
     assert (adj.cpu().numpy().view(np.uint32) == want).all()
 
 
-def _check_rows(lib, g: Grammar, vocab, expect_overflow=None):
+def _check_rows(lib, g: Grammar, vocab, expect_overflow=None, row_len=256):
     from gpu_util import dev, hash_np
     prods = g.productions()
     toks = vocab.tokens()
-    want_rows, want_hash, want_status = D.displacement_rows(toks, prods, seed=SEED)
+    want_rows, want_hash, want_status = D.displacement_rows(toks, prods, seed=SEED, row_len=row_len)
     rows, hashes, status = lib.cfgzip_displacements(dev(vocab.tok_bytes), dev(vocab.tok_off),
-                                                    *_grammar_dev(g), g.N, hash_seed=SEED)
+                                                    *_grammar_dev(g), g.N, row_len=row_len,
+                                                    hash_seed=SEED)
     got_status = status.cpu().numpy()
     got_rows = rows.cpu().numpy()
     bad = np.nonzero(got_status != want_status)[0]
@@ -164,42 +165,80 @@ def test_long_tokens(lib):
     assert rows[1][0] > 0 and rows[3][0] > 0 and rows[4][0] == 0
 
 
-def test_each_bound_overflows_alone(lib):
-    print("case overflow bounds", flush=True)
+def _passes(g, toks):
+    prods = g.productions()
+    adj = D.stack_adjacency(prods)
+    return [D.displacement_two_passes(tuple(t), prods, adj)[1] for t in toks]
+
+
+def test_each_cap_of_both_passes(lib):
+    print("case caps", flush=True)
     a = ord("a")
-    # input queue
+    # input queue: 8 in the first pass, 32 in the second
     g = grammar_from_productions(2, [(0, ord("x"), (1, 1)), (1, a, ())])
     _check_adjacency(lib, g)
-    _check_rows(lib, g, vocab_from_tokens([b"a" * n for n in range(0, 12)]), expect_overflow=True)
-    # output stack
+    toks = [b"a" * n for n in range(0, 36)]
+    assert _passes(g, toks) == [1] * 9 + [2] * 24 + [0] * 3
+    rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks), expect_overflow=True)
+    assert status.tolist() == [0] * 33 + [1] * 3
+    assert D.decode_displacement(rows[32]) == frozenset({((1,) * 32, ())})
+    # output stack: 12 and 32
     g = grammar_from_productions(1, [(0, a, (0, 0, 0, 0))])
-    _check_rows(lib, g, vocab_from_tokens([b"a" * n for n in range(0, 7)]), expect_overflow=True)
-    # successors per byte: exactly at the bound, one above, and counted with multiplicity
-    n = D.DISP_MAX_FRONTIER
-    g = grammar_from_productions(n, [(i, a, ()) for i in range(n)])
-    _check_rows(lib, g, vocab_from_tokens([b"a", b"aa"]))
-    g = grammar_from_productions(n + 1, [(i, a, ()) for i in range(n + 1)])
-    _check_rows(lib, g, vocab_from_tokens([b"a", b"b", b""]), expect_overflow=True)
-    g = grammar_from_productions(n + 3, [(0, ord("s"), (1,))] + [(1, ord("b"), (2 + i,)) for i in range(n + 1)])
-    _check_rows(lib, g, vocab_from_tokens([b"s", b"sb", b"b"]), expect_overflow=True)
-    # row length: 63 pairs fit, 64 do not
-    for heads in (63, 64, 100):
+    toks = [b"a" * n for n in range(0, 13)]
+    assert _passes(g, toks) == [1] * 4 + [2] * 7 + [0] * 2
+    _check_rows(lib, g, vocab_from_tokens(toks), expect_overflow=True)
+    # successors per byte: 128 and 256, counted with multiplicity
+    for n, which in ((128, 1), (129, 2), (256, 2), (257, 0)):
+        g = grammar_from_productions(n, [(i, a, ()) for i in range(n)])
+        toks = [b"a", b"aa", b"b", b""]
+        assert _passes(g, toks)[0] == which
+        _check_rows(lib, g, vocab_from_tokens(toks), row_len=2048, expect_overflow=which == 0)
+        g = grammar_from_productions(n + 3, [(0, ord("s"), (1,))] + [(1, ord("b"), (2 + i,)) for i in range(n)])
+        toks = [b"s", b"sb", b"b"]
+        assert _passes(g, toks)[1] == which
+        _check_rows(lib, g, vocab_from_tokens(toks), row_len=2048, expect_overflow=which == 0)
+        # successors that fall together into one configuration still count one each
+        g = grammar_from_productions(n + 2, [(i, a, (n + 1,)) for i in range(n)] + [(n + 1, ord("b"), ())])
+        toks = [b"a", b"ab"]
+        assert _passes(g, toks)[0] == which
+        _check_rows(lib, g, vocab_from_tokens(toks), row_len=2048, expect_overflow=which == 0)
+
+
+@pytest.mark.parametrize("row_len", [256, 512, 1024, 4096])
+def test_row_lengths(lib, row_len):
+    print(f"case row_len={row_len}", flush=True)
+    a = ord("a")
+    # k pairs of 2 + 1 + 1 entries: fits while 1 + 4k <= row_len (and k <= 256 successors)
+    for heads in (63, 64, 127, 128, 200, 255, 256):
         g = grammar_from_productions(heads, [(i, a, (0,)) for i in range(heads)])
-        _check_rows(lib, g, vocab_from_tokens([b"a"]), expect_overflow=heads > 63)
+        rows, status, _ = _check_rows(lib, g, vocab_from_tokens([b"a", b"", b"b"]), row_len=row_len)
+        assert (status[0] == 0) == (1 + 4 * heads <= row_len)
+    # records that straddle the 256-entry chunks the kernel writes: long queues and stacks
+    prods = [(0, ord("x"), (1, 1)), (1, a, ()), (1, ord("b"), (2, 2, 2, 2)), (2, ord("c"), (2, 2, 2, 2)),
+             (2, ord("c"), (1, 2, 2)), (2, ord("c"), (2, 1)), (2, ord("d"), ()), (1, ord("c"), (2,))]
+    g = grammar_from_productions(3, prods)
+    toks = [b"a" * i + b"b" + b"c" * j for i in (0, 3, 7, 20, 31) for j in range(0, 8)]
+    rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks), row_len=row_len)
+    ok = status == 0
+    used = [1 + sum(2 + len(q) + len(o) for q, o in D.decode_displacement(r)) for r in rows[ok]]
+    assert max(used) > min(row_len, 2000) * 0.7, "some row must reach into the last chunk"
 
 
 def test_long_stacks_and_queues_at_their_bounds(lib):
     print("case bounds reached", flush=True)
-    # queue of exactly 8 with stacks, deep stack of exactly 12
+    # queue of exactly 8 with stacks, deep stack of exactly 12 (first pass), 32 and 32 (second)
     prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ()), (1, ord("b"), (2, 2, 2, 2)),
              (2, ord("c"), (2, 2, 2)), (2, ord("d"), ())]
     g = grammar_from_productions(3, prods)
     toks = [b"a" * 7 + b"b", b"a" * 7 + b"bc", b"a" * 7 + b"bcc", b"a" * 7 + b"bccc", b"a" * 7 + b"bccd",
-            b"bccdddd", b"a" * 8 + b"b", b"bdddd", b"bddddd", b"a" * 7 + b"bcccc", b"a" * 7 + b"bccccc"]
+            b"bccdddd", b"a" * 8 + b"b", b"bdddd", b"bddddd", b"a" * 7 + b"bcccc", b"a" * 7 + b"bccccc",
+            b"a" * 31 + b"b" + b"c" * 14, b"a" * 31 + b"b" + b"c" * 15, b"a" * 32 + b"b"]
+    assert _passes(g, toks) == [1, 1, 1, 1, 1, 1, 2, 1, 1, 1, 2, 2, 0, 0]
     rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks))
-    assert status.tolist() == [0, 0, 0, 0, 0, 0, 1, 0, 0, 0, 1]
+    assert status.tolist() == [0] * 12 + [1, 1]
     assert D.decode_displacement(rows[1]) == frozenset({((1,) * 8, (2,) * 6)})
     assert D.decode_displacement(rows[9]) == frozenset({((1,) * 8, (2,) * 12)})
+    assert D.decode_displacement(rows[11]) == frozenset({((1,) * 32, (2,) * 32)})
 
 
 def test_right_linear_grammar_gives_the_byte_walk_classes(lib, cfg1):
@@ -277,14 +316,16 @@ def test_json_grammar_full_vocabulary(lib):
     got_rows, got_hash, got_status = rows.cpu().numpy(), hash_np(hashes), status.cpu().numpy()
     adj = D.stack_adjacency(prods)
     index = D.index_productions(prods)
-    n_overflow = 0
+    n_overflow = n_second = 0
     for t in range(0, vocab.V, 8):
-        pairs = D.displacement_bounded(tuple(vocab.token(t)), prods, adj, index)
+        pairs, which = D.displacement_two_passes(tuple(vocab.token(t)), prods, adj, index)
+        n_second += which == 2
         row, h, st = D.encode_displacement(pairs, t, SEED)
         assert got_status[t] == st and got_hash[t] == h and (got_rows[t] == np.array(row, np.uint16)).all(), \
             (t, vocab.token(t))
         n_overflow += st == D.DISP_OVERFLOW
-    assert 0 < n_overflow < vocab.V // 8 // 10
+    # long digit runs: the second pass takes them, the longest need more than 256 entries
+    assert 0 < n_overflow < n_second and n_second > 100
     c, r, C, _coll = lib.cfgzip_build_classes(tb, to, None, rows, hashes)
     c, r = c.cpu().numpy(), r.cpu().numpy()
     _uniq, first, inverse = np.unique(got_rows, axis=0, return_index=True, return_inverse=True)

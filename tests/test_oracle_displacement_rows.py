@@ -57,47 +57,74 @@ def test_empty_token_and_dead_token():
     assert D.displacement_bounded((ord("z"),), prods, adj) == frozenset()
     row, h, st = D.encode_displacement(frozenset(), 5, seed=1)
     assert st == D.DISP_OK and row == [0] * D.DISP_ROW_LEN and h == 0
+    assert D.encode_displacement(frozenset({((), ())}), 5, seed=1)[0][:4] == [1, 0, 0, 0]
 
 
-def test_overflow_of_the_input_queue():
+@pytest.mark.parametrize("caps", [D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND])
+def test_the_input_queue_cap(caps):
     # X -> x A A makes (A, A) stack-adjacent; A -> a.  "a" * k keeps backtracking into A.
+    max_in = caps[0]
     prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ())]
     adj = D.stack_adjacency(prods)
     assert (1, 1) in adj
-    ok = D.displacement_bounded((ord("a"),) * D.DISP_MAX_IN, prods, adj)
-    assert ok == frozenset({((1,) * D.DISP_MAX_IN, ())})
-    assert D.displacement_bounded((ord("a"),) * (D.DISP_MAX_IN + 1), prods, adj) is None
+    ok = D.displacement_bounded((ord("a"),) * max_in, prods, adj, caps=caps)
+    assert ok == frozenset({((1,) * max_in, ())})
+    assert D.displacement_bounded((ord("a"),) * (max_in + 1), prods, adj, caps=caps) is None
     # the unbounded algorithm goes on
-    assert D.displacement((ord("a"),) * (D.DISP_MAX_IN + 1), prods) == \
-        frozenset({((1,) * (D.DISP_MAX_IN + 1), ())})
+    assert D.displacement((ord("a"),) * (max_in + 1), prods) == frozenset({((1,) * (max_in + 1), ())})
 
 
-def test_overflow_of_the_output_stack():
+@pytest.mark.parametrize("caps", [D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND])
+def test_the_output_stack_cap(caps):
+    max_out = caps[1]
     prods = [(0, ord("a"), (0, 0, 0, 0))]   # each byte: pop one, push four
     adj = D.stack_adjacency(prods)
-    for k in range(1, 6):
-        got = D.displacement_bounded((ord("a"),) * k, prods, adj)
+    seen_none = False
+    for k in range(1, 13):
+        got = D.displacement_bounded((ord("a"),) * k, prods, adj, caps=caps)
         depth = 4 + 3 * (k - 1)
-        if depth <= D.DISP_MAX_OUT:
+        if depth <= max_out:
             assert got == frozenset({((0,), (0,) * depth)})
         else:
             assert got is None
+            seen_none = True
+    assert seen_none
 
 
-def test_overflow_of_the_frontier_counts_successors_with_multiplicity():
-    n = D.DISP_MAX_FRONTIER
+@pytest.mark.parametrize("caps", [D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND])
+def test_the_frontier_cap_counts_successors_with_multiplicity(caps):
+    n = caps[2]
     prods = [(i, ord("a"), ()) for i in range(n)]
     adj = D.stack_adjacency(prods)
-    got = D.displacement_bounded((ord("a"),), prods, adj)
+    got = D.displacement_bounded((ord("a"),), prods, adj, caps=caps)
     assert got is not None and len(got) == n
     prods.append((n, ord("a"), ()))
-    assert D.displacement_bounded((ord("a"),), prods, D.stack_adjacency(prods)) is None
-    # two configurations that fall together after the next byte still count twice:
-    # 65 heads A_i -> a B, then B -> b C | b D gives 130 successors but only 130 distinct... use
-    # heads that all keep the same queue: S -> s B (one config), B -> b X_i for 129 bodies
+    assert D.displacement_bounded((ord("a"),), prods, D.stack_adjacency(prods), caps=caps) is None
+    # one configuration with n + 1 successors
     prods = [(0, ord("s"), (1,))] + [(1, ord("b"), (2 + i,)) for i in range(n + 1)]
-    assert D.displacement_bounded((ord("s"), ord("b")), prods, set()) is None
+    assert D.displacement_bounded((ord("s"), ord("b")), prods, set(), caps=caps) is None
     assert len(D.displacement((ord("s"), ord("b")), prods)) == n + 1
+    # n + 1 successors that fall together into one configuration still count n + 1
+    prods = [(i, ord("a"), (n + 1,)) for i in range(n + 1)] + [(n + 1, ord("b"), ())]
+    got = D.displacement_bounded((ord("a"),), prods, set(), caps=caps)
+    assert got is None and len(D.displacement((ord("a"),), prods)) == n + 1
+
+
+def test_second_pass_takes_what_the_first_cannot():
+    prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ())]
+    adj = D.stack_adjacency(prods)
+    assert D.displacement_two_passes((ord("a"),) * 8, prods, adj)[1] == 1
+    pairs, which = D.displacement_two_passes((ord("a"),) * 9, prods, adj)
+    assert which == 2 and pairs == D.displacement((ord("a"),) * 9, prods)
+    pairs, which = D.displacement_two_passes((ord("a"),) * 33, prods, adj)
+    assert which == 0 and pairs is None
+    rows, hashes, status = D.displacement_rows([b"a" * 8, b"a" * 9, b"a" * 32, b"a" * 33], prods, seed=4)
+    assert status.tolist() == [0, 0, 0, 1]
+    assert D.decode_displacement(rows[2]) == frozenset({((1,) * 32, ())})
+    # the same set found in either pass encodes alike
+    a = D.encode_displacement(D.displacement_bounded((ord("a"),) * 5, prods, adj), 0, 4)
+    b = D.encode_displacement(D.displacement_bounded((ord("a"),) * 5, prods, adj, caps=D.DISP_CAPS_SECOND), 0, 4)
+    assert a == b
 
 
 def test_overflow_of_the_row():
@@ -115,6 +142,21 @@ def test_overflow_of_the_row():
     assert st == D.DISP_OK and row[0] == 63
     _row, _h, st = D.encode_displacement(frozenset(list(pairs)[:64]), 0, seed=9)
     assert st == D.DISP_OVERFLOW   # 1 + 64 * 4 = 257
+    # a longer row takes it, and starts like the short one would
+    row512, h512, st = D.encode_displacement(pairs, 70000, seed=9, row_len=512)
+    assert st == D.DISP_OK and len(row512) == 512 and row512[0] == 100 and D.decode_displacement(row512) == pairs
+    short = D.encode_displacement(frozenset(list(pairs)[:63]), 0, seed=9)
+    long_ = D.encode_displacement(frozenset(list(pairs)[:63]), 0, seed=9, row_len=1024)
+    assert long_[0][:256] == short[0] and long_[1] == short[1] and not any(long_[0][256:])
+
+
+def test_canonical_order():
+    pairs = [((2,), (1, 1)), ((1, 5), ()), ((1,), (9,)), ((1,), (3, 0)), ((), ()), ((0, 0), ())]
+    row, _h, st = D.encode_displacement(pairs, 0, seed=1)
+    assert st == D.DISP_OK
+    # by (ni, no), then queue, then stack
+    want = [0, 0, 1, 1, 1, 9, 1, 2, 1, 3, 0, 1, 2, 2, 1, 1, 2, 0, 0, 0, 2, 0, 1, 5]
+    assert row[0] == 6 and row[1:1 + len(want)] == want
 
 
 @pytest.mark.parametrize("seed", range(4))
