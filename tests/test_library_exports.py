@@ -51,6 +51,34 @@ def test_host_only_queries(raw):
     assert raw.cfgzip_build_classes_workspace_bytes(10, 70000) == 0
 
 
+def test_widening_rows_queries_and_argument_checks(raw):
+    names = _declared_functions()
+    for fn in ("cfgzip_state_masks", "cfgzip_class_masks", "cfgzip_advance_states", "cfgzip_stack_adjacency",
+               "cfgzip_displacements", "cfgzip_displacements_workspace_bytes", "cfgzip_nfa_signatures"):
+        assert fn in names
+    q = raw.cfgzip_displacements_workspace_bytes
+    q.restype = ctypes.c_size_t
+    assert q(0, 4097) == 0 and q(-1, 10) == 0 and q(0, 0) == 0
+    small, large = q(0, 27), q(128256, 27)
+    assert small >= 256 * 27 * 4 + 257 * 4          # the (terminal, head) index and the byte offsets
+    assert large >= small + 128256 * 4              # plus the list of tokens for the second pass
+    assert q(0, 4096) >= 3 * 4096 * 128 * 4 + 256 * 4096 * 4   # three bit matrices and the index
+    u64, sz = ctypes.c_uint64(0), ctypes.c_size_t(0)
+    assert raw.cfgzip_displacements(None, None, 1, None, None, None, None, 1, 1, None, 256, None, None, u64,
+                                    None, sz, None) == -1
+    assert raw.cfgzip_stack_adjacency(None, None, None, None, 1, 1, None, None, None, sz, None) == -1
+    assert raw.cfgzip_nfa_signatures(None, None, 1, None, 1, None, None, u64, None) == -1
+    # sizes are checked before any pointer is used
+    buf = ctypes.create_string_buffer(4096)
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    assert raw.cfgzip_nfa_signatures(p, p, 1, p, 257, p, None, u64, None) == -1
+    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 1, 5000, p, 256, p, None, u64, p, sz, None) == -1
+    for bad_row_len in (0, 255, 300, 8192):
+        assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 1, 5, p, bad_row_len, p, None, u64, p, sz,
+                                        None) == -1
+    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 1, 5, p, 256, p, None, u64, None, sz, None) == -2
+
+
 def test_null_and_range_arguments_are_rejected_without_a_gpu(raw):
     assert raw.cfgzip_expand_mask(None, 1, 1, None, 1, None, None) == -1
     assert raw.cfgzip_apply_mask(None, 0, 1, 1, ctypes.c_int64(1), None, 0, None, 0, None, None) == -1
