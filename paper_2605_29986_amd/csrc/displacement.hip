@@ -289,29 +289,56 @@ __device__ inline bool record_less(const uint32_t *a, const uint32_t *b) {
 }
 
 // Drops every record of src[0..m) that equals an earlier one and packs the rest into dst;
-// returns how many are left.  Called by the whole wave; m <= FRONTIER.
+// returns how many are left.  Called by the whole wave; m <= FRONTIER.  A 16-bit fingerprint of
+// every record goes to `fp` first: a lane then scans the fingerprints before its own without
+// branching (independent LDS reads) and compares whole records only where one matches.
+// `empty_list` receives the positions (in dst) of the records whose stack is empty, `n_empty`
+// how many there are: the next byte's backtrack visits only those.
 template <typename Sym, typename R, int FRONTIER>
-__device__ int drop_duplicates(const Sym (*src)[R::kStride], Sym (*dst)[R::kStride], int m, int lane) {
+__device__ int drop_duplicates(const Sym (*src)[R::kStride], Sym (*dst)[R::kStride], int m, int lane,
+                               uint16_t *fp, uint8_t *empty_list, int &n_empty) {
+    for (int i = lane; i < m; i += 64) {
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(src[i]);
+        uint32_t h = 0;
+#pragma unroll
+        for (int k = 0; k < R::kWords; ++k) h = h * 0x9E3779B1u + w[k];
+        fp[i] = (uint16_t)((h >> 16) ^ h);
+    }
+    __syncthreads();
     int kept = 0;
+    n_empty = 0;
     for (int base = 0; base < FRONTIER; base += 64) {
+        if (base >= m) break;  // the same for every lane
         const int i = base + lane;
         bool keep = i < m;
         if (keep) {
-            const uint32_t *mine = reinterpret_cast<const uint32_t *>(src[i]);
-            for (int j = 0; j < i; ++j)
-                if (records_equal<R>(mine, reinterpret_cast<const uint32_t *>(src[j]))) {
-                    keep = false;
-                    break;
-                }
+            const uint32_t mine_fp = fp[i];
+            bool candidate = false;
+#pragma unroll 8
+            for (int j = 0; j < i; ++j) candidate |= fp[j] == mine_fp;
+            if (candidate) {
+                const uint32_t *mine = reinterpret_cast<const uint32_t *>(src[i]);
+                for (int j = 0; j < i; ++j)
+                    if (fp[j] == mine_fp &&
+                        records_equal<R>(mine, reinterpret_cast<const uint32_t *>(src[j]))) {
+                        keep = false;
+                        break;
+                    }
+            }
         }
         const uint64_t mask = __ballot(keep);
+        const bool empty = keep && src[i][1] == 0;
+        const uint64_t empty_mask = __ballot(empty);
+        const uint64_t below = (1ull << lane) - 1ull;
         if (keep) {
-            const int pos = kept + __popcll(mask & ((1ull << lane) - 1ull));
+            const int pos = kept + __popcll(mask & below);
             const uint32_t *s = reinterpret_cast<const uint32_t *>(src[i]);
             uint32_t *d = reinterpret_cast<uint32_t *>(dst[pos]);
             for (int k = 0; k < R::kWords; ++k) d[k] = s[k];
+            if (empty) empty_list[n_empty + __popcll(empty_mask & below)] = (uint8_t)pos;
         }
         kept += __popcll(mask);
+        n_empty += __popcll(empty_mask);
     }
     return kept;
 }
@@ -327,6 +354,8 @@ struct TokenLds {
     __align__(8) uint16_t row[kRowChunk];
     int n_emit, crossed, total_len, next_item;
     unsigned long long hash_sum;
+    uint16_t fingerprint[FRONTIER];
+    uint8_t empty_list[FRONTIER];  // positions of the live configurations with an empty stack
     // STAGE only: the productions lo .. hi-1 of the byte being read, and the relation
     __align__(8) uint2 sp_body[STAGE ? kStageCap : 1];
     uint16_t sp_head[STAGE ? kStageCap : 1];
@@ -351,8 +380,11 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
 
     // the start configuration: nothing consumed, nothing pushed
     for (int k = lane; k < kStride; k += 64) L.buf[0][0][k] = (Sym)(k == R::kPrevAt ? kNone : 0);
-    if (lane == 0) L.crossed = 0;
-    int n = 1;
+    if (lane == 0) {
+        L.crossed = 0;
+        L.empty_list[0] = 0;
+    }
+    int n = 1, n_empty = 1;
     bool caps_crossed = false;
     __syncthreads();
 
@@ -405,10 +437,10 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
                 }
             }
         }
-        // stack backtracks: the wave per configuration (every production of the terminal)
-        for (int c = 0; c < n; ++c) {
-            const Sym *rec = src[c];
-            if (rec[1] != 0) continue;  // the same for every lane
+        // stack backtracks: the wave per configuration with an empty stack (every production of
+        // the terminal)
+        for (int e = 0; e < n_empty; ++e) {
+            const Sym *rec = src[L.empty_list[e]];
             const int ni = rec[0];
             const int prev = rec[R::kPrevAt];
             for (int i = lo + lane; i < hi; i += 64) {
@@ -444,7 +476,8 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
             caps_crossed = true;
             break;
         }
-        n = drop_duplicates<Sym, R, FRONTIER>(dst, src, m, lane);  // back into the buffer just read
+        // back into the buffer just read
+        n = drop_duplicates<Sym, R, FRONTIER>(dst, src, m, lane, L.fingerprint, L.empty_list, n_empty);
         __syncthreads();
     }
 
@@ -459,7 +492,7 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
             L.hash_sum = 0;
         }
         __syncthreads();
-        n = drop_duplicates<Sym, R, FRONTIER>(src, dst, n, lane);
+        n = drop_duplicates<Sym, R, FRONTIER>(src, dst, n, lane, L.fingerprint, L.empty_list, n_empty);
         __syncthreads();
         // canonical order by counting: a record starts behind all smaller ones
 #pragma unroll
