@@ -373,6 +373,7 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
     using R = Rec<Sym, MAX_IN, MAX_OUT>;
     constexpr int kStride = R::kStride;
     constexpr int kNone = R::kNone;
+    static_assert(FRONTIER % 64 == 0 && FRONTIER <= 256, "whole waves of records; positions fit a byte");
     constexpr int kPerLane = FRONTIER / 64;
     const int lane = threadIdx.x;
     const Grammar &g = a.g;
