@@ -214,6 +214,21 @@ int cfgzip_map_to_rep(const int32_t *tok, int32_t B,
  *     states[b] <- sig_rep[class_of_token[tok[b]]][states[b]]     int32 [B], in place;
  *     a token id, class id or state out of range gives -1
  */
+/*
+ * The vocabulary E the engine is initialised with (paper Section 3.1 "Inference"): the byte
+ * strings of the representatives, in class order, in the same CSR form as the token vocabulary:
+ *     rep_off[k] .. rep_off[k+1]  =  position of bytes(r[k]) in rep_bytes,  rep_off[0] = 0.
+ *   rep_of_class  int32 [C]; an id outside [0, V) gives an empty string
+ *   rep_off       out, int64 [C + 1]
+ *   rep_bytes     out, uint8 [capacity]; bytes that would fall beyond `capacity` are not written
+ *                 (rep_off[C] still tells how many there are).  tok_off[V] bytes always suffice,
+ *                 since representatives are distinct tokens.  capacity = 0: offsets only.
+ */
+int cfgzip_representative_vocabulary(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                                     const int32_t *rep_of_class, int32_t C,
+                                     int64_t *rep_off, uint8_t *rep_bytes, int64_t capacity,
+                                     void *stream);
+
 int cfgzip_state_masks(const uint16_t *sig_rep, int32_t C, int32_t S, const uint8_t *live,
                        int32_t *state_mask, void *stream);
 int cfgzip_class_masks(const int32_t *state_mask, int32_t S, int32_t C, const int32_t *states,

@@ -189,6 +189,21 @@ def signature_hash(sig, seed: int) -> np.ndarray:
     return out
 
 
+def representative_vocabulary(tok_bytes, tok_off, rep):
+    """(rep_bytes uint8 [total], rep_off int64 [C + 1]): the representatives' byte strings."""
+    tok_bytes = _c(tok_bytes, np.uint8)
+    tok_off = _c(tok_off, np.int64)
+    rep = _c(rep, np.int32)
+    V, C = tok_off.shape[0] - 1, rep.shape[0]
+    rep_off = np.empty(C + 1, dtype=np.int64)
+    fn = _load().oracle_representative_vocabulary
+    fn.restype = ctypes.c_int64
+    total = fn(_p(tok_bytes), _p(tok_off), ctypes.c_int32(V), _p(rep), ctypes.c_int32(C), _p(rep_off), None)
+    rep_bytes = np.empty(max(int(total), 1), dtype=np.uint8)
+    fn(_p(tok_bytes), _p(tok_off), ctypes.c_int32(V), _p(rep), ctypes.c_int32(C), _p(rep_off), _p(rep_bytes))
+    return rep_bytes[:total], rep_off
+
+
 def nfa_signatures(tok_bytes, tok_off, nfa) -> np.ndarray:
     """uint32 [V, S, W]: bit row of the states reachable from q on the bytes of token t, for a
     non-deterministic byte automaton nfa[b][q] = bit row of successors (uint32 [256, S, W])."""

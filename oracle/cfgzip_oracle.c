@@ -40,6 +40,8 @@
  *                         of its current state).
  *   oracle_advance_states Section 3.1 "Inference": the engine's state is updated with the
  *                         representative r[c[t]] of the sampled token t.
+ *   oracle_representative_vocabulary  Section 3.1 "Inference": the engine is initialised with
+ *                         the vocabulary E of the representatives' byte strings.
  *   oracle_nfa_signatures Section 3.2.1 for a right-linear grammar that is NOT deterministic
  *                         (several productions q -> a q' per state and byte): the
  *                         displacement of t is the relation {(q, q') : q' reachable from q
@@ -327,4 +329,24 @@ void oracle_nfa_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int
         free(cur);
         free(nxt);
     }
+}
+
+/* Byte strings of the representatives, class after class: rep_off[k] .. rep_off[k+1] delimit
+ * bytes(r[k]) in rep_bytes; an id outside [0, V) stands for the empty string.  Returns the total
+ * number of bytes; with rep_bytes == NULL only the offsets are written. */
+int64_t oracle_representative_vocabulary(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                                         const int32_t *rep, int32_t C, int64_t *rep_off,
+                                         uint8_t *rep_bytes) {
+    int64_t at = 0;
+    for (int32_t k = 0; k < C; ++k) {
+        rep_off[k] = at;
+        int32_t t = rep[k];
+        if (t < 0 || t >= V) continue;
+        for (int64_t p = tok_off[t]; p < tok_off[t + 1]; ++p) {
+            if (rep_bytes) rep_bytes[at] = tok_bytes[p];
+            ++at;
+        }
+    }
+    rep_off[C] = at;
+    return at;
 }

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     cfgzip_expand_mask,
     cfgzip_map_to_rep,
     cfgzip_nfa_signatures,
+    cfgzip_representative_vocabulary,
     cfgzip_signatures,
     cfgzip_stack_adjacency,
     cfgzip_state_masks,

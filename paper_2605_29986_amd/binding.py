@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_class_masks.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.cfgzip_advance_states.restype = ctypes.c_int
     lib.cfgzip_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_representative_vocabulary.restype = ctypes.c_int
+    lib.cfgzip_representative_vocabulary.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp]
     lib.cfgzip_nfa_signatures.restype = ctypes.c_int
     lib.cfgzip_nfa_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp]
     lib.cfgzip_displacements_workspace_bytes.restype = sz
@@ -381,3 +383,23 @@ def cfgzip_nfa_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, nfa: t
         ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF), _stream(stream))
     _check("cfgzip_nfa_signatures", rc)
     return rel, hashes
+
+
+def cfgzip_representative_vocabulary(tok_bytes: torch.Tensor, tok_off: torch.Tensor,
+                                     rep_of_class: torch.Tensor, *, stream=None):
+    """(rep_bytes uint8 [capacity], rep_off int64 [C + 1]): the representatives' byte strings in
+    class order, CSR like the vocabulary.  rep_off[C] bytes of rep_bytes are meaningful."""
+    lib = load_library()
+    V = tok_off.numel() - 1
+    C = rep_of_class.numel()
+    dev = tok_off.device
+    capacity = tok_bytes.numel()
+    rep_off = torch.empty((C + 1,), dtype=torch.int64, device=dev)
+    rep_bytes = torch.empty((max(capacity, 1),), dtype=torch.uint8, device=dev)
+    rc = lib.cfgzip_representative_vocabulary(
+        _dev(tok_bytes, torch.uint8, "tok_bytes") if capacity else None,
+        _dev(tok_off, torch.int64, "tok_off"), V,
+        _dev(rep_of_class, torch.int32, "rep_of_class"), C, rep_off.data_ptr(),
+        rep_bytes.data_ptr(), capacity, _stream(stream))
+    _check("cfgzip_representative_vocabulary", rc)
+    return rep_bytes, rep_off

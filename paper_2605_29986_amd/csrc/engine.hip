@@ -80,10 +80,76 @@ __global__ void advance_states_kernel(const uint16_t *__restrict__ sig_rep, int 
     states[b] = next;
 }
 
+// Offsets of the representatives' byte strings: one workgroup; thread i sums the lengths of a
+// contiguous run of classes, the runs' totals are scanned in LDS, and the thread writes its run's
+// offsets.  An id outside [0, V) counts as an empty string.
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void rep_offsets_kernel(const int64_t *__restrict__ tok_off,
+                                                                   int V,
+                                                                   const int32_t *__restrict__ rep,
+                                                                   int C, int64_t *__restrict__ rep_off) {
+    __shared__ int64_t partial[kScanThreads];
+    const int i = threadIdx.x;
+    const int per = (C + kScanThreads - 1) / kScanThreads;
+    const int k0 = min(C, i * per), k1 = min(C, k0 + per);
+    auto length = [&](int k) -> int64_t {
+        const int32_t t = rep[k];
+        return (t >= 0 && t < V) ? tok_off[t + 1] - tok_off[t] : 0;
+    };
+    int64_t sum = 0;
+    for (int k = k0; k < k1; ++k) sum += length(k);
+    partial[i] = sum;
+    __syncthreads();
+    for (int off = 1; off < kScanThreads; off <<= 1) {  // inclusive scan of the run totals
+        const int64_t add = i >= off ? partial[i - off] : 0;
+        __syncthreads();
+        partial[i] += add;
+        __syncthreads();
+    }
+    int64_t at = partial[i] - sum;
+    for (int k = k0; k < k1; ++k) {
+        rep_off[k] = at;
+        at += length(k);
+    }
+    if (i == kScanThreads - 1) rep_off[C] = partial[i];
+}
+
+// A thread per class copies its representative's bytes; bytes beyond the capacity are dropped.
+__global__ void rep_bytes_kernel(const uint8_t *__restrict__ tok_bytes,
+                                 const int64_t *__restrict__ tok_off, int V,
+                                 const int32_t *__restrict__ rep, int C,
+                                 const int64_t *__restrict__ rep_off, uint8_t *__restrict__ rep_bytes,
+                                 int64_t capacity) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= C) return;
+    const int32_t t = rep[k];
+    if (t < 0 || t >= V) return;
+    const int64_t src = tok_off[t], n = tok_off[t + 1] - src, dst = rep_off[k];
+    for (int64_t j = 0; j < n && dst + j < capacity; ++j) rep_bytes[dst + j] = tok_bytes[src + j];
+}
+
 }  // namespace
 }  // namespace cfgzip
 
 using namespace cfgzip;
+
+extern "C" int cfgzip_representative_vocabulary(const uint8_t *tok_bytes, const int64_t *tok_off,
+                                                int32_t V, const int32_t *rep_of_class, int32_t C,
+                                                int64_t *rep_off, uint8_t *rep_bytes,
+                                                int64_t capacity, void *stream) {
+    if (!tok_off || !rep_of_class || !rep_off || V <= 0 || C <= 0 || capacity < 0) return CFGZIP_E_INVALID;
+    if (capacity > 0 && (!rep_bytes || !tok_bytes)) return CFGZIP_E_INVALID;
+    if (!aligned_to(tok_off, 8) || !aligned_to(rep_off, 8) || !aligned_to(rep_of_class, 4))
+        return CFGZIP_E_INVALID;
+    hipLaunchKernelGGL(rep_offsets_kernel, dim3(1), dim3(kScanThreads), 0,
+                       static_cast<hipStream_t>(stream), tok_off, V, rep_of_class, C, rep_off);
+    CFGZIP_TRY(check_launch());
+    if (capacity == 0) return CFGZIP_OK;
+    hipLaunchKernelGGL(rep_bytes_kernel, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), tok_bytes, tok_off, V, rep_of_class, C,
+                       rep_off, rep_bytes, capacity);
+    return check_launch();
+}
 
 extern "C" int cfgzip_state_masks(const uint16_t *sig_rep, int32_t C, int32_t S, const uint8_t *live,
                                   int32_t *state_mask, void *stream) {

@@ -127,3 +127,56 @@ def test_engine_argument_errors(lib):
     assert raw.cfgzip_state_masks(t.data_ptr(), 1, 70000, t.data_ptr(), t.data_ptr(), None) == -1
     assert raw.cfgzip_class_masks(t.data_ptr(), 1, 1, t.data_ptr(), 0, t.data_ptr(), None) == -1
     assert raw.cfgzip_advance_states(t.data_ptr(), 1, 1, None, 1, t.data_ptr(), 1, t.data_ptr(), None) == -1
+
+
+@pytest.mark.parametrize("which", ["cfg1", "cfg2_small"])
+def test_representative_vocabulary(lib, which, request):
+    print(f"case representative vocabulary {which}", flush=True)
+    from gpu_util import dev, vocab_dev
+    cfg = request.getfixturevalue(which)
+    vocab, table = cfg["vocab"], cfg["table"]
+    tb, to, tt = vocab_dev(vocab, table)
+    sig, h = lib.cfgzip_signatures(tb, to, tt)
+    c, r, C, _ = lib.cfgzip_build_classes(tb, to, tt, sig, h)
+    rep_bytes, rep_off = lib.cfgzip_representative_vocabulary(tb, to, r.contiguous())
+    want_bytes, want_off = oracle.representative_vocabulary(vocab.tok_bytes, vocab.tok_off, r.cpu().numpy())
+    got_off = rep_off.cpu().numpy()
+    assert (got_off == want_off).all()
+    assert (rep_bytes.cpu().numpy()[:got_off[-1]] == want_bytes).all()
+    # the engine's view: signatures of that vocabulary are the representatives' rows
+    sig_rep, _ = lib.cfgzip_signatures(rep_bytes[:max(int(got_off[-1]), 1)].contiguous(), rep_off, tt,
+                                       want_hash=False)
+    assert (sig_rep.cpu().numpy() == sig.cpu().numpy()[r.cpu().numpy()]).all()
+
+
+def test_representative_vocabulary_edge_cases(lib, cfg1):
+    print("case representative vocabulary edges", flush=True)
+    from gpu_util import dev
+    vocab = cfg1["vocab"]
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+    rng = np.random.default_rng(1)
+    for n in (1, 2, 1023, 1024, 1025, 5000, 70001):
+        ids = rng.integers(-3, vocab.V + 3, size=n).astype(np.int32)
+        want_bytes, want_off = oracle.representative_vocabulary(vocab.tok_bytes, vocab.tok_off, ids)
+        raw = lib.load_library()
+        ids_dev = dev(ids)
+        rep_off = torch.empty(n + 1, dtype=torch.int64, device="cuda")
+        cap = int(want_off[-1])
+        rep_bytes = torch.full((cap + 64,), 0xAB, dtype=torch.uint8, device="cuda")
+        rc = raw.cfgzip_representative_vocabulary(tb.data_ptr(), to.data_ptr(), vocab.V, ids_dev.data_ptr(), n,
+                                                  rep_off.data_ptr(), rep_bytes.data_ptr(), cap, None)
+        assert rc == 0
+        torch.cuda.synchronize()
+        assert (rep_off.cpu().numpy() == want_off).all()
+        got = rep_bytes.cpu().numpy()
+        assert (got[:cap] == want_bytes).all() and (got[cap:] == 0xAB).all()
+        # a capacity that is too small: nothing is written beyond it, the offsets still tell the need
+        small = cap // 2
+        rep_bytes.fill_(0xCD)
+        rc = raw.cfgzip_representative_vocabulary(tb.data_ptr(), to.data_ptr(), vocab.V, ids_dev.data_ptr(), n,
+                                                  rep_off.data_ptr(), rep_bytes.data_ptr(), small, None)
+        assert rc == 0
+        torch.cuda.synchronize()
+        got = rep_bytes.cpu().numpy()
+        assert (got[:small] == want_bytes[:small]).all() and (got[small:] == 0xCD).all()
+        assert int(rep_off[-1].item()) == cap

@@ -145,3 +145,19 @@ def test_advance_states_range_checks():
     tok = np.array([0, 1, 4, -1, 3, 2], dtype=np.int32)
     states = np.array([1, 2, 1, 1, 3, -1], dtype=np.int32)
     assert list(oracle.advance_states(sig_rep, c, tok, states)) == [2, 2, -1, -1, -1, -1]
+
+
+def test_representative_vocabulary_is_the_list_of_their_byte_strings(cfg1):
+    """The vocabulary E the engine is given: token r[k]'s bytes for every class k, in class order."""
+    from synthetic_inputs.vocab import vocab_from_tokens
+    vocab = cfg1["vocab"]
+    sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, cfg1["table"])
+    _c, r = oracle.build_classes(sig, vocab.tok_off)
+    rep_bytes, rep_off = oracle.representative_vocabulary(vocab.tok_bytes, vocab.tok_off, r)
+    want = vocab_from_tokens([vocab.token(int(t)) for t in r])
+    assert (rep_off == want.tok_off).all() and (rep_bytes == want.tok_bytes).all()
+    # ids may repeat, be out of range (an empty string), or select nothing
+    ids = np.array([5, 5, -1, vocab.V, 0, 7], dtype=np.int32)
+    b, o = oracle.representative_vocabulary(vocab.tok_bytes, vocab.tok_off, ids)
+    toks = [vocab.token(5), vocab.token(5), b"", b"", vocab.token(0), vocab.token(7)]
+    assert o.tolist() == np.cumsum([0] + [len(t) for t in toks]).tolist() and b.tobytes() == b"".join(toks)
