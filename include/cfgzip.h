@@ -16,11 +16,17 @@
  *
  * Signature.  The paper's relation is equality of displacement sets over the
  * one-state pushdown automaton of a grammar in Greibach normal form (Section
- * 3.2.1, Algorithm 1).  This library covers grammars given as a deterministic
- * byte automaton (a right-linear grammar): the stack then holds one symbol, no
- * stack backtrack can follow the first one, and the displacement of token t is
- * the map  q -> delta*(q, bytes(t))  over all automaton states q.  That vector
- * is the signature: sig[t][q], S entries of uint16.
+ * 3.2.1, Algorithm 1).  Three forms of it are covered:
+ *   - a deterministic byte automaton (a right-linear grammar): the stack holds one
+ *     symbol, no stack backtrack can follow the first one, and the displacement of
+ *     token t is the map  q -> delta*(q, bytes(t))  over all automaton states q;
+ *     that vector is the signature sig[t][q], S entries of uint16
+ *     (cfgzip_signatures);
+ *   - a non-deterministic byte automaton: the relation R_t of the state pairs that
+ *     bytes(t) connects, S bit rows (cfgzip_nfa_signatures);
+ *   - a grammar in Greibach normal form: the displacement set itself, written as a
+ *     fixed-length row (cfgzip_stack_adjacency, cfgzip_displacements).
+ * cfgzip_build_classes groups tokens by any of the three.
  *
  * Conventions for every call
  *   - Every pointer is a DEVICE pointer owned by the caller unless the comment
