@@ -152,13 +152,15 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
     return out
 
 
-def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
-    """General case: displacement sets of config 3's vocabulary over the JSON grammar in
-    Greibach normal form, then the classes from the rows.  cpu_sample > 0 also times the
-    oracle (pure Python, one core) on that many leading tokens."""
+def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, grammar: str = "json"):
+    """General case: displacement sets of config 3's vocabulary over a grammar in Greibach normal
+    form (the JSON value language, or the C-flavoured statement language), then the classes from
+    the rows.  cpu_sample > 0 also times the oracle (pure Python, one core) on that many leading
+    tokens."""
     import synthetic_inputs as si
-    from synthetic_inputs.grammar import make_json_gnf
-    g = make_json_gnf()
+    from synthetic_inputs.grammar import make_clike_gnf, make_json_gnf
+    g = make_json_gnf() if grammar == "json" else make_clike_gnf()
+    name = "JSON grammar" if grammar == "json" else "C-flavoured statement grammar"
     vocab = si.make_config(3)["vocab"]
     V = vocab.V
     stream = torch.cuda.current_stream()
@@ -193,8 +195,8 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
     C = res["cls"][2]
     ms_all = min(t_all)
     out = {
-        "workload": "JSON grammar in Greibach normal form (%d non-terminals, %d productions) x "
-                    "config 3 vocabulary" % (g.N, g.P),
+        "workload": "%s in Greibach normal form (%d non-terminals, %d productions) x "
+                    "config 3 vocabulary" % (name, g.N, g.P),
         "V": V, "N": g.N, "P": g.P, "C": C, "V_over_C": round(V / C, 2),
         "overflow_tokens": int((status == lib_mod.DISP_OVERFLOW).sum()),
         "ms_stack_adjacency": round(min(t_adj), 4),
@@ -203,7 +205,7 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int):
         "tokens_per_s": V / (ms_all * 1e-3),
         "token_bytes_per_s": int(vocab.tok_off[-1]) / (min(t_disp) * 1e-3),
     }
-    log(f"displacement: V={V} N={g.N} P={g.P} C={C} overflow={out['overflow_tokens']} adjacency "
+    log(f"displacement ({name}): V={V} N={g.N} P={g.P} C={C} overflow={out['overflow_tokens']} adjacency "
         f"{min(t_adj):.3f} ms, displacements {min(t_disp):.3f} ms, with classes {ms_all:.3f} ms")
     # the same with rows long enough for every set of this workload (no token left on its own)
     ws_bld4 = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, 1024), dtype=torch.uint8, device="cuda")
@@ -562,6 +564,8 @@ def main() -> int:
         result["nfa"] = bench_nfa(lib_mod, raw, torch, args.build_repeats, not args.no_cpu_baseline)
         result["displacement"] = bench_displacement(lib_mod, raw, torch, args.build_repeats,
                                                     0 if args.no_cpu_baseline else 30000)
+        result["displacement_clike"] = bench_displacement(lib_mod, raw, torch, args.build_repeats,
+                                                          0 if args.no_cpu_baseline else 30000, "clike")
     if mask_variants:
         result["mask_variants"] = mask_variants
     if not args.no_cpu_baseline:

@@ -172,3 +172,93 @@ def make_json_gnf() -> Grammar:
     add("FA", "a", "FL"), add("FL", "l", "FS"), add("FS", "s", "TE")
     add("NU", "u", "NL"), add("NL", "l", "NL2"), add("NL2", "l")
     return grammar_from_productions(len(JSON_NONTERMINALS), P)
+
+
+CLIKE_NONTERMINALS = ["PROG", "EXPR", "IDT", "NUMT", "FRAC", "ETL", "ARGS", "ARGT", "RP", "RB", "RBR", "STR",
+                      "ESC", "K_F", "IFR", "K_H", "K_HI", "K_HIL", "K_HILE", "K_E", "K_ET", "K_ETU", "K_ETUR",
+                      "K_ETURN", "RETR"]
+
+
+def make_clike_gnf() -> Grammar:
+    """A C-flavoured statement and expression language over bytes, written directly in Greibach
+    normal form: identifiers, numbers, string literals, prefix and binary operators, calls,
+    indexing, parentheses, ';'-separated statements, nested blocks, `if (..)`, `while (..)` and
+    `return`.  Single blanks may precede operands and tails (so tokens with a leading blank stay
+    alive).  It accepts a superset of what a C parser would (two-character operators are read as
+    a binary operator followed by a prefix one); what matters here is its shape: nesting on the
+    stack, keywords that compete with identifiers, a few hundred productions.  Stands in for
+    the paper's C++ and Bython grammars, which are not available."""
+    nt = {name: i for i, name in enumerate(CLIKE_NONTERMINALS)}
+    P: List[Tuple[int, int, Tuple[int, ...]]] = []
+
+    def add(head: str, byte, *body: str):
+        b = byte if isinstance(byte, int) else ord(byte)
+        assert len(body) <= MAX_BODY, (head, byte, body)
+        P.append((nt[head], b, tuple(nt[x] for x in body)))
+
+    id_start = b"abcdefghijklmnopqrstuvwxyzABCDEFGHIJKLMNOPQRSTUVWXYZ_"
+    digits = b"0123456789"
+    binary = b"+-*/%<>=&|^.,?:"
+    prefix = b"-!~*&"
+
+    # an operand and what may follow it; every list entry is (first byte, body)
+    expr: List[Tuple[int, Tuple[str, ...]]] = []
+    for c in id_start:
+        expr += [(c, ()), (c, ("IDT",))]
+    for d in digits:
+        expr += [(d, ()), (d, ("NUMT",))]
+    for p in prefix:
+        expr.append((p, ("EXPR",)))
+    expr += [(ord("("), ("EXPR", "RP")), (ord("("), ("EXPR", "RP", "ETL")),
+             (ord('"'), ("STR",)), (ord('"'), ("STR", "ETL")), (ord(" "), ("EXPR",))]
+    for b, body in expr:
+        add("EXPR", b, *body)
+        add("ARGS", b, *body, "ARGT")          # first argument of a call
+        add("PROG", b, *body)                  # an expression statement (its tail takes the ';')
+    add("ARGS", ")"), add("ARGS", ")", "ETL")
+    add("ARGT", ")"), add("ARGT", ")", "ETL")
+    add("ARGT", ",", "EXPR", "ARGT")
+    add("RP", ")"), add("RB", "]"), add("RBR", "}")
+    add("RP", " ", "RP"), add("RB", " ", "RB"), add("RBR", " ", "RBR"), add("RBR", "\n", "RBR")
+
+    # tails: after an identifier, after a number, after any complete operand
+    def tails(head: str):
+        for op in binary:
+            add(head, op, "EXPR")
+        add(head, "(", "ARGS")
+        add(head, "[", "EXPR", "RB"), add(head, "[", "EXPR", "RB", "ETL")
+        add(head, ";"), add(head, ";", "PROG")
+        add(head, " ", "ETL")
+
+    for c in id_start + digits:
+        add("IDT", c), add("IDT", c, "IDT")
+    tails("IDT")
+    for d in digits:
+        add("NUMT", d), add("NUMT", d, "NUMT")
+        add("FRAC", d), add("FRAC", d, "FRAC"), add("FRAC", d, "ETL")
+    add("NUMT", ".", "FRAC")
+    tails("NUMT")
+    tails("ETL")
+
+    # string literals
+    add("STR", '"')
+    add("STR", "\\", "ESC", "STR")
+    for c in range(0x20, 0x7F):
+        if c not in (ord('"'), ord("\\")):
+            add("STR", c, "STR")
+    for c in '"\\nt0':
+        add("ESC", c)
+
+    # statements that are not expressions
+    add("PROG", ";"), add("PROG", ";", "PROG")
+    add("PROG", "{", "PROG", "RBR"), add("PROG", "{", "PROG", "RBR", "PROG")
+    add("PROG", "{", "RBR"), add("PROG", "{", "RBR", "PROG")
+    add("PROG", "\n", "PROG"), add("PROG", " ", "PROG")
+    add("PROG", "i", "K_F"), add("K_F", "f", "IFR")
+    add("IFR", " ", "IFR"), add("IFR", "(", "EXPR", "RP", "PROG")
+    add("PROG", "w", "K_H"), add("K_H", "h", "K_HI"), add("K_HI", "i", "K_HIL"), add("K_HIL", "l", "K_HILE")
+    add("K_HILE", "e", "IFR")
+    add("PROG", "r", "K_E"), add("K_E", "e", "K_ET"), add("K_ET", "t", "K_ETU"), add("K_ETU", "u", "K_ETUR")
+    add("K_ETUR", "r", "K_ETURN"), add("K_ETURN", "n", "RETR")
+    add("RETR", ";"), add("RETR", ";", "PROG"), add("RETR", " ", "EXPR")
+    return grammar_from_productions(len(CLIKE_NONTERMINALS), P)

@@ -341,3 +341,29 @@ def test_json_grammar_full_vocabulary(lib):
     best = np.full(C, np.iinfo(np.int64).max)
     np.minimum.at(best, c, lens * vocab.V + np.arange(vocab.V))
     assert (best % vocab.V == r).all()
+
+
+def test_clike_grammar_full_vocabulary(lib):
+    """The second measured grammar: statements and expressions with nesting and keywords, against
+    config 3's vocabulary; every 16th token against the oracle, classes against numpy."""
+    print("case c-like grammar, full vocabulary", flush=True)
+    from gpu_util import dev, hash_np
+    from synthetic_inputs.grammar import make_clike_gnf
+    g = make_clike_gnf()
+    vocab = si.make_config(3)["vocab"]
+    prods = g.productions()
+    _check_adjacency(lib, g)
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+    rows, hashes, status = lib.cfgzip_displacements(tb, to, *_grammar_dev(g), g.N, hash_seed=SEED)
+    got_rows, got_hash, got_status = rows.cpu().numpy(), hash_np(hashes), status.cpu().numpy()
+    adj = D.stack_adjacency(prods)
+    index = D.index_productions(prods)
+    for t in range(0, vocab.V, 16):
+        pairs, _which = D.displacement_two_passes(tuple(vocab.token(t)), prods, adj, index)
+        row, h, st = D.encode_displacement(pairs, t, SEED)
+        assert got_status[t] == st and got_hash[t] == h and (got_rows[t] == np.array(row, np.uint16)).all(), \
+            (t, vocab.token(t))
+    assert (got_status == D.DISP_OK).all()
+    c, r, C, _coll = lib.cfgzip_build_classes(tb, to, None, rows, hashes)
+    _uniq, first = np.unique(got_rows, axis=0, return_index=True)
+    assert C == len(first) and C < vocab.V // 50

@@ -230,3 +230,26 @@ def test_adjacency_bit_matrix_layout():
     assert bits.shape == (41, 2)
     assert bits[1, 0] == 1 << 3 and bits[1, 1] == 1 << 8 and bits[2, 0] == 1
     assert int(bits.sum()) == (1 << 3) + (1 << 8) + 1
+
+
+def test_json_and_clike_grammars_accept_what_they_should():
+    """The hand-written grammars are in normal form, sorted, and their one-state pushdown automaton
+    (Equation 2) accepts well-formed texts and rejects broken ones."""
+    from synthetic_inputs.grammar import make_clike_gnf, make_json_gnf
+    cases = {
+        make_json_gnf: ([b'{"a": [1,2.5e-3,true,null], "b":{"c":"x\\n\\u00e9"}}', b'[]', b'-0.5', b'"s"'],
+                        [b'[1,]', b'{"a" 1}', b'tru', b'{"a":}', b'01x']),
+        make_clike_gnf: ([b'x = foo(a, b[3]) + 2.5;', b'if (x<1) { return y; }',
+                          b'while (i) { i = i - 1; s = "a\\n"; }', b'{ f(); { g(1,2); } }'],
+                         [b'x = (1;', b'if x;', b'{ x; ', b'x = );', b'f(;']),
+    }
+    for make, (good, bad) in cases.items():
+        g = make()
+        prods = g.productions()
+        assert prods == sorted(set(prods), key=lambda p: (p[1], p[0], p[2])) and len(prods) == g.P
+        assert all(0 <= A < g.N and len(beta) <= 4 and all(0 <= b < g.N for b in beta) for A, _a, beta in prods)
+        d = D.delta(prods)
+        for text in good:
+            assert () in D.pi(tuple(text), (0,), d), text
+        for text in bad:
+            assert () not in D.pi(tuple(text), (0,), d), text
