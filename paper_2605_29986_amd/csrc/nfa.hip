@@ -13,6 +13,7 @@
 #include <algorithm>
 
 #include "common.hpp"
+#include "walk_device.hpp"  // splitmix64_at: the multipliers of the signature hash
 
 namespace cfgzip {
 namespace {
@@ -20,14 +21,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxNfaStates = 256;
 constexpr int kStagedBytes = 64;  // token bytes read once into LDS; longer tokens go on from global
-
-__device__ __forceinline__ uint64_t splitmix64_at(uint64_t seed, uint32_t index) {
-    // index-th output (0-based) of the SplitMix64 generator seeded with `seed`
-    uint64_t z = seed + (uint64_t)(index + 1u) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
 
 struct NfaArgs {
     const uint8_t *tok_bytes;
