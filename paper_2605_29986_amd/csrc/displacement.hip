@@ -314,8 +314,9 @@ __device__ int drop_duplicates(const Sym (*src)[R::kStride], Sym (*dst)[R::kStri
         if (keep) {
             const uint32_t mine_fp = fp[i];
             bool candidate = false;
-#pragma unroll 8
-            for (int j = 0; j < i; ++j) candidate |= fp[j] == mine_fp;
+            const int last = min(m, base + 64) - 1;  // the same bound for every lane: no divergence
+#pragma unroll 4
+            for (int j = 0; j < last; ++j) candidate |= (j < i) & (fp[j] == mine_fp);
             if (candidate) {
                 const uint32_t *mine = reinterpret_cast<const uint32_t *>(src[i]);
                 for (int j = 0; j < i; ++j)
