@@ -367,3 +367,26 @@ def test_clike_grammar_full_vocabulary(lib):
     c, r, C, _coll = lib.cfgzip_build_classes(tb, to, None, rows, hashes)
     _uniq, first = np.unique(got_rows, axis=0, return_index=True)
     assert C == len(first) and C < vocab.V // 50
+
+
+def test_many_random_grammars(lib):
+    """Sixty grammars of random shape (1-40 symbols, 1-6 terminals, bodies up to 1-4, sparse to
+    dense), 300 random tokens each, random row length: relation, rows, hashes, status, classes."""
+    rng = np.random.default_rng(2024)
+    seen_overflow = seen_ok = 0
+    for case in range(60):
+        n_nt, asz = int(rng.integers(1, 40)), int(rng.integers(1, 7))
+        alphabet = bytes(rng.choice(np.arange(97, 123), size=asz, replace=False).astype(np.uint8))
+        max_body = int(rng.integers(1, 5))
+        possible = n_nt * asz * sum(n_nt ** k for k in range(0, max_body + 1))
+        n_prod = max(n_nt, min(int(rng.integers(n_nt, min(n_nt * asz * 6, 400) + n_nt)), possible // 2))
+        seed = int(rng.integers(1 << 30))
+        print(f"case {case}: N={n_nt} terminals={asz} P={n_prod} body<={max_body} seed={seed}", flush=True)
+        g = make_random_gnf(seed, n_nt=n_nt, alphabet=alphabet, n_prod=n_prod, max_body=max_body,
+                            unary_fraction=float(rng.uniform(0.1, 0.7)))
+        vocab = make_token_strings(seed + 1, 300, alphabet + b"z", int(rng.integers(1, 12)))
+        _check_adjacency(lib, g)
+        _rows, status, _c = _check_rows(lib, g, vocab, row_len=int(rng.choice([256, 512, 1024])))
+        seen_overflow += int((status == D.DISP_OVERFLOW).sum())
+        seen_ok += int((status == D.DISP_OK).sum())
+    assert seen_overflow > 1000 and seen_ok > 5000
