@@ -271,7 +271,7 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
  *     in ascending order of (ni, no), then of the queue, then of the stack; the rest is 0.
  * hash_out[t] is the sum over the pairs of a 64-bit mix of the record and hash_seed (a
  * function of the set, for cfgzip_build_classes; never part of a result).
- * Bounds.  Every token is first taken with queue <= 8, stack <= 12 and at most 128 successors
+ * Bounds.  Every token is first taken with queue <= 12, stack <= 12 and at most 128 successors
  * of all live configurations per byte (counted before duplicates are dropped); a token that
  * crosses one of these is taken again with queue <= 32, stack <= 32, successors <= 256.  A
  * token that crosses those too, or whose set needs more than row_len entries, gets status

@@ -186,7 +186,7 @@ def right_linear_grammar(table, accepting: Iterable[int], reject: int = 0) -> Li
 # Without overflow the result is the set Algorithm 1 returns; the tests pin that.
 # ---------------------------------------------------------------------------------------------
 
-DISP_CAPS_FIRST = (8, 12, 128)
+DISP_CAPS_FIRST = (12, 12, 128)
 DISP_CAPS_SECOND = (32, 32, 256)
 DISP_ROW_LEN = 256            # default row length; any multiple of 256 up to 4096
 DISP_OK = 0

@@ -37,7 +37,7 @@ constexpr int kMaxSymbols = 4096;
 constexpr int kMaxByteSymbols = 255;           // up to here a symbol (and "none") fits a byte
 
 // caps of the first pass over all tokens and of the second pass over those it could not finish
-constexpr int kIn1 = 8, kOut1 = 12, kFrontier1 = 128;
+constexpr int kIn1 = 12, kOut1 = 12, kFrontier1 = 128;
 constexpr int kIn2 = 32, kOut2 = 32, kFrontier2 = 256;
 // the second pass keeps the current byte's productions and the relation in LDS when they fit
 constexpr int kStageCap = 128;      // productions of one terminal

@@ -174,18 +174,22 @@ def _passes(g, toks):
 def test_each_cap_of_both_passes(lib):
     print("case caps", flush=True)
     a = ord("a")
-    # input queue: 8 in the first pass, 32 in the second
+    # input queue: the first pass's cap, then the second's
+    in1, in2 = D.DISP_CAPS_FIRST[0], D.DISP_CAPS_SECOND[0]
     g = grammar_from_productions(2, [(0, ord("x"), (1, 1)), (1, a, ())])
     _check_adjacency(lib, g)
-    toks = [b"a" * n for n in range(0, 36)]
-    assert _passes(g, toks) == [1] * 9 + [2] * 24 + [0] * 3
+    toks = [b"a" * n for n in range(0, in2 + 4)]
+    assert _passes(g, toks) == [1] * (in1 + 1) + [2] * (in2 - in1) + [0] * 3
     rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks), expect_overflow=True)
-    assert status.tolist() == [0] * 33 + [1] * 3
-    assert D.decode_displacement(rows[32]) == frozenset({((1,) * 32, ())})
-    # output stack: 12 and 32
+    assert status.tolist() == [0] * (in2 + 1) + [1] * 3
+    assert D.decode_displacement(rows[in2]) == frozenset({((1,) * in2, ())})
+    # output stack: each byte pops one symbol and pushes four
+    out1, out2 = D.DISP_CAPS_FIRST[1], D.DISP_CAPS_SECOND[1]
     g = grammar_from_productions(1, [(0, a, (0, 0, 0, 0))])
     toks = [b"a" * n for n in range(0, 13)]
-    assert _passes(g, toks) == [1] * 4 + [2] * 7 + [0] * 2
+    depth = [0] + [4 + 3 * (n - 1) for n in range(1, 13)]
+    assert _passes(g, toks) == [1 if d <= out1 else (2 if d <= out2 else 0) for d in depth]
+    assert 0 in _passes(g, toks) and 2 in _passes(g, toks)
     _check_rows(lib, g, vocab_from_tokens(toks), expect_overflow=True)
     # successors per byte: 128 and 256, counted with multiplicity
     for n, which in ((128, 1), (129, 2), (256, 2), (257, 0)):
@@ -226,19 +230,23 @@ def test_row_lengths(lib, row_len):
 
 def test_long_stacks_and_queues_at_their_bounds(lib):
     print("case bounds reached", flush=True)
-    # queue of exactly 8 with stacks, deep stack of exactly 12 (first pass), 32 and 32 (second)
+    # queue and stack exactly at the caps of the first pass and of the second, and one beyond
+    (in1, out1, _f1), (in2, out2, _f2) = D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND
     prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ()), (1, ord("b"), (2, 2, 2, 2)),
-             (2, ord("c"), (2, 2, 2)), (2, ord("d"), ())]
+             (2, ord("c"), (2, 2, 2)), (2, ord("d"), ())]     # b: stack 4; each c: +2; each d: -1
     g = grammar_from_productions(3, prods)
-    toks = [b"a" * 7 + b"b", b"a" * 7 + b"bc", b"a" * 7 + b"bcc", b"a" * 7 + b"bccc", b"a" * 7 + b"bccd",
-            b"bccdddd", b"a" * 8 + b"b", b"bdddd", b"bddddd", b"a" * 7 + b"bcccc", b"a" * 7 + b"bccccc",
-            b"a" * 31 + b"b" + b"c" * 14, b"a" * 31 + b"b" + b"c" * 15, b"a" * 32 + b"b"]
-    assert _passes(g, toks) == [1, 1, 1, 1, 1, 1, 2, 1, 1, 1, 2, 2, 0, 0]
+
+    def tok(queue, stack):     # a token whose only pair has that queue length and stack depth
+        assert queue >= 1 and stack >= 4 and stack % 2 == 0
+        return b"a" * (queue - 1) + b"b" + b"c" * ((stack - 4) // 2)
+
+    toks = [tok(in1, 4), tok(in1, out1), tok(in1, out1 + 2), tok(in1 + 1, 4), tok(in2, out2), tok(in2, out2 + 2),
+            tok(in2 + 1, 4), b"bccdddd", b"bdddd", b"bddddd"]
+    assert _passes(g, toks) == [1, 1, 2, 2, 2, 0, 0, 1, 1, 1]
     rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks))
-    assert status.tolist() == [0] * 12 + [1, 1]
-    assert D.decode_displacement(rows[1]) == frozenset({((1,) * 8, (2,) * 6)})
-    assert D.decode_displacement(rows[9]) == frozenset({((1,) * 8, (2,) * 12)})
-    assert D.decode_displacement(rows[11]) == frozenset({((1,) * 32, (2,) * 32)})
+    assert status.tolist() == [0, 0, 0, 0, 0, 1, 1, 0, 0, 0]
+    assert D.decode_displacement(rows[1]) == frozenset({((1,) * in1, (2,) * out1)})
+    assert D.decode_displacement(rows[4]) == frozenset({((1,) * in2, (2,) * out2)})
 
 
 def test_right_linear_grammar_gives_the_byte_walk_classes(lib, cfg1):

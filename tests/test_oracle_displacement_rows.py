@@ -113,14 +113,17 @@ def test_the_frontier_cap_counts_successors_with_multiplicity(caps):
 def test_second_pass_takes_what_the_first_cannot():
     prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ())]
     adj = D.stack_adjacency(prods)
-    assert D.displacement_two_passes((ord("a"),) * 8, prods, adj)[1] == 1
-    pairs, which = D.displacement_two_passes((ord("a"),) * 9, prods, adj)
-    assert which == 2 and pairs == D.displacement((ord("a"),) * 9, prods)
-    pairs, which = D.displacement_two_passes((ord("a"),) * 33, prods, adj)
+    first_in, second_in = D.DISP_CAPS_FIRST[0], D.DISP_CAPS_SECOND[0]
+    assert first_in < second_in
+    assert D.displacement_two_passes((ord("a"),) * first_in, prods, adj)[1] == 1
+    pairs, which = D.displacement_two_passes((ord("a"),) * (first_in + 1), prods, adj)
+    assert which == 2 and pairs == D.displacement((ord("a"),) * (first_in + 1), prods)
+    pairs, which = D.displacement_two_passes((ord("a"),) * (second_in + 1), prods, adj)
     assert which == 0 and pairs is None
-    rows, hashes, status = D.displacement_rows([b"a" * 8, b"a" * 9, b"a" * 32, b"a" * 33], prods, seed=4)
+    toks = [b"a" * first_in, b"a" * (first_in + 1), b"a" * second_in, b"a" * (second_in + 1)]
+    rows, hashes, status = D.displacement_rows(toks, prods, seed=4)
     assert status.tolist() == [0, 0, 0, 1]
-    assert D.decode_displacement(rows[2]) == frozenset({((1,) * 32, ())})
+    assert D.decode_displacement(rows[2]) == frozenset({((1,) * second_in, ())})
     # the same set found in either pass encodes alike
     a = D.encode_displacement(D.displacement_bounded((ord("a"),) * 5, prods, adj), 0, 4)
     b = D.encode_displacement(D.displacement_bounded((ord("a"),) * 5, prods, adj, caps=D.DISP_CAPS_SECOND), 0, 4)
