@@ -19,6 +19,9 @@
 namespace cfgzip {
 namespace {
 
+// native 16-byte vector (the nontemporal builtins do not take HIP's uint4 struct)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 struct WalkArgs {
     const uint8_t *tok_bytes;
     const int64_t *tok_off;
@@ -197,7 +200,11 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
                         o.y = (uint32_t)wm[id.y & 0xFFFFu] | ((uint32_t)wm[id.y >> 16] << 16);
                         o.z = (uint32_t)wm[id.z & 0xFFFFu] | ((uint32_t)wm[id.z >> 16] << 16);
                         o.w = (uint32_t)wm[id.w & 0xFFFFu] | ((uint32_t)wm[id.w >> 16] << 16);
-                        *reinterpret_cast<uint4 *>(a.sig_out + (size_t)(tcur + m) * S + q0) = o;
+                        // written once, not read again by this call: keep it out of the caches
+                        // that hold the table
+                        const u32x4 ov = {o.x, o.y, o.z, o.w};
+                        __builtin_nontemporal_store(
+                            ov, reinterpret_cast<u32x4 *>(a.sig_out + (size_t)(tcur + m) * S + q0));
                     }
                 } else {
                     const uint32_t items = (uint32_t)k * (uint32_t)S;
