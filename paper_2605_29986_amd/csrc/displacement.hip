@@ -10,8 +10,8 @@
 //   - one with an empty output stack backtracks: every production A -> a beta with that
 //     terminal, whose head A is stack-adjacent to the symbol consumed last (any head at the
 //     very first byte), appends A to the input queue and starts the output stack with beta.
-// Successors are appended to a second LDS buffer through one LDS counter, duplicates are
-// dropped, and the buffers swap.  What is left after the last byte, without the third
+// Successors are appended to a second LDS buffer through one LDS counter; duplicates are
+// dropped while the survivors are packed back into the first.  What is left after the last byte, without the third
 // component, is the displacement; it is written as a fixed-length row in a canonical order
 // together with an order-free 64-bit hash, so that equal sets give equal rows and the class
 // builder can group tokens by comparing rows.
