@@ -398,3 +398,27 @@ def test_many_random_grammars(lib):
         seen_overflow += int((status == D.DISP_OVERFLOW).sum())
         seen_ok += int((status == D.DISP_OK).sum())
     assert seen_overflow > 1000 and seen_ok > 5000
+
+
+def test_status_pointer_is_optional(lib):
+    """status_out = NULL: rows and hashes are the same, nothing else is written."""
+    print("case no status array", flush=True)
+    import ctypes
+    from gpu_util import dev, hash_np
+    g, atoms = make_bracket_gnf(5)
+    vocab = make_token_strings(6, 700, atoms + b"()[]{},+-*", 6)
+    tb, to = dev(vocab.tok_bytes), dev(vocab.tok_off)
+    gd = _grammar_dev(g)
+    rows, hashes, _status = lib.cfgzip_displacements(tb, to, *gd, g.N, hash_seed=SEED)
+    raw = lib.load_library()
+    rows2 = torch.zeros_like(rows)
+    hashes2 = torch.zeros_like(hashes)
+    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(vocab.V, g.N), dtype=torch.uint8, device="cuda")
+    rc = raw.cfgzip_displacements(tb.data_ptr(), to.data_ptr(), vocab.V, gd[0].data_ptr(), gd[1].data_ptr(),
+                                  gd[2].data_ptr(), gd[3].data_ptr(), g.P, g.N, rows2.data_ptr(), 256,
+                                  hashes2.data_ptr(), None, ctypes.c_uint64(SEED), ws.data_ptr(), ws.numel(),
+                                  None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert (rows2.cpu().numpy() == rows.cpu().numpy()).all()
+    assert (hash_np(hashes2) == hash_np(hashes)).all()

@@ -100,6 +100,18 @@ def test_lexer_nfa_full_vocabulary(lib):
     assert len(set(c.tolist())) != len(set(c_det.tolist()))
 
 
+def test_hash_is_optional(lib, cfg1):
+    from gpu_util import dev
+    vocab = cfg1["vocab"]
+    nfa = add_transitions(nfa_from_dfa(cfg1["table"]), 3, 0.3)
+    tb, to, nd = dev(vocab.tok_bytes), dev(vocab.tok_off), dev(nfa)
+    rel, h = lib.cfgzip_nfa_signatures(tb, to, nd)
+    rel2, h2 = lib.cfgzip_nfa_signatures(tb, to, nd, want_hash=False)
+    assert h2 is None and h is not None
+    assert (rel.cpu().numpy() == rel2.cpu().numpy()).all()
+    assert (rel.cpu().numpy().view(np.uint32) == oracle.nfa_signatures(vocab.tok_bytes, vocab.tok_off, nfa)).all()
+
+
 def test_argument_errors(lib):
     from gpu_util import dev
     v = vocab_from_tokens([b"a", b"b"])
