@@ -422,3 +422,20 @@ def test_status_pointer_is_optional(lib):
     torch.cuda.synchronize()
     assert (rows2.cpu().numpy() == rows.cpu().numpy()).all()
     assert (hash_np(hashes2) == hash_np(hashes)).all()
+
+
+def test_second_pass_with_sixteen_bit_symbols(lib):
+    """More than 255 symbols and queues beyond the first pass's cap: the second pass's 16-bit
+    records (its largest LDS footprint)."""
+    print("case second pass, 300 symbols", flush=True)
+    a, in1, in2 = ord("a"), D.DISP_CAPS_FIRST[0], D.DISP_CAPS_SECOND[0]
+    prods = [(0, ord("x"), (299, 299)), (299, a, ()), (299, ord("b"), (298, 297, 296, 295)),
+             (298, ord("c"), ()), (297, ord("c"), (298,)), (296, ord("c"), ()), (295, ord("c"), (296, 296))]
+    prods += [(i, ord("z"), (i + 1,)) for i in range(1, 290)]      # fillers: 300 symbols in use
+    g = grammar_from_productions(300, prods)
+    toks = [b"a" * n for n in (1, in1, in1 + 1, 20, in2, in2 + 1)] + [b"a" * 15 + b"b" + b"c" * k for k in range(6)]
+    which = _passes(g, toks)
+    assert which[:6] == [1, 1, 2, 2, 2, 0] and set(which[6:]) == {2}
+    rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks))
+    assert status.tolist() == [0, 0, 0, 0, 0, 1] + [0] * 6
+    assert D.decode_displacement(rows[4]) == frozenset({((299,) * in2, ())})
