@@ -55,7 +55,7 @@ def _random_nfa(rng, S, n_sym, per_row):
     return nfa
 
 
-@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 64, 65, 100, 128, 129, 160, 200, 255, 256])
+@pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 64, 65, 100, 128, 129, 160, 190, 200, 255, 256])
 def test_random_relations(lib, S):
     print(f"case S={S}", flush=True)
     rng = np.random.default_rng(S)
