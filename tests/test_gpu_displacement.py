@@ -75,8 +75,8 @@ def _all_tokens(alphabet: bytes, max_len: int):
 
 
 def _figure3_grammar():
-    from test_oracle_displacement import _read_fig3
-    token, prods, _steps, res_i, res_o = _read_fig3()
+    from golden_fixtures import read_fig3
+    token, prods, _steps, res_i, res_o = read_fig3()
     names = sorted({p[0] for p in prods} | {b for p in prods for b in p[2]})
     num = {n: i for i, n in enumerate(names)}
     g = grammar_from_productions(len(names), [(num[A], ord(a), tuple(num[b] for b in beta))

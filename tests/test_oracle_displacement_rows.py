@@ -39,8 +39,8 @@ def test_bounded_form_equals_algorithm_1(seed):
 
 
 def test_bounded_form_on_figure_3():
-    from tests.test_oracle_displacement import _read_fig3
-    token, prods, _steps, res_i, res_o = _read_fig3()
+    from golden_fixtures import read_fig3
+    token, prods, _steps, res_i, res_o = read_fig3()
     names = sorted({p[0] for p in prods} | {b for p in prods for b in p[2]})
     num = {n: i for i, n in enumerate(names)}
     iprods = [(num[A], ord(a), tuple(num[b] for b in beta)) for (A, a, beta) in prods]
