@@ -483,13 +483,33 @@ def main() -> int:
     engine_steps()
     torch.cuda.synchronize()
     engine_us = (time.perf_counter() - t0) * 1e6 / args.steps
+    # the same step in one launch: states alternate between two arrays
+    states2 = [states, torch.empty_like(states)]
+    one_args = [(vp(lb.data_ptr()), i32(1), i32(B), i32(V), i64(V), vp(state_mask.data_ptr()), i32(S5), i32(C),
+                 vp(c5.data_ptr()), vp(sig_rep.data_ptr()), vp(tok.data_ptr()), vp(states2[i % 2].data_ptr()),
+                 vp(states2[(i + 1) % 2].data_ptr()), vp(tok_bits.data_ptr()), sptr)
+                for i, lb in enumerate(logit_bufs)]
+
+    def engine_steps_one_launch():
+        for i in range(args.steps):
+            rc = raw.cfgzip_engine_step(*one_args[i % N_LOGIT_BUFFERS])
+            if rc != 0:
+                raise RuntimeError(f"engine step failed, rc={rc}")
+    engine_steps_one_launch()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    engine_steps_one_launch()
+    torch.cuda.synchronize()
+    engine_one_us = (time.perf_counter() - t0) * 1e6 / args.steps
     engine = {"workload": f"closed step: class masks from {B} automaton states (S={S5}, C={C}), fused "
                           "expand + apply on bf16 logits, state advance on representatives",
               "us_per_step": round(engine_us, 2),
               "GBps": round(nbytes["mask_kernel"] / (engine_us * 1e-6) / 1e9, 1),
+              "us_per_step_one_launch": round(engine_one_us, 2),
+              "GBps_one_launch": round(nbytes["mask_kernel"] / (engine_one_us * 1e-6) / 1e9, 1),
               "ms_state_masks_once": round(ms_state_masks, 4)}
-    log(f"engine step (class masks + fused mask + advance): {engine_us:.2f} us/step; "
-        f"state masks [S={S5}][C={C}] once: {ms_state_masks * 1e3:.1f} us")
+    log(f"engine step (class masks + fused mask + advance): {engine_us:.2f} us/step, in one launch "
+        f"{engine_one_us:.2f} us/step; state masks [S={S5}][C={C}] once: {ms_state_masks * 1e3:.1f} us")
 
     # ---- optional: the other forms of the mask path at the same shape (kernel alone, rotating buffers)
     mask_variants = {}

@@ -237,6 +237,23 @@ int cfgzip_representative_vocabulary(const uint8_t *tok_bytes, const int64_t *to
 
 int cfgzip_state_masks(const uint16_t *sig_rep, int32_t C, int32_t S, const uint8_t *live,
                        int32_t *state_mask, void *stream);
+/*
+ * cfgzip_engine_step: one decode step of that engine in a single launch (the three calls below
+ * followed by cfgzip_apply_mask, without the class masks going through memory):
+ *     q[b] = tok_prev ? sig_rep[class_of_token[tok_prev[b]]][states_in[b]] : states_in[b]
+ *            (-1 if the token id, its class id or the state is out of range)
+ *     states_out[b] = q[b]
+ *     logits row b masked with the class mask state_mask[q[b]] gathered through class_of_token
+ *     (all of row b becomes -inf if q[b] is not a state); tok_bits_out as for cfgzip_apply_mask.
+ *   tok_prev    int32 [B] tokens sampled in the previous step, or NULL (first step: no advance)
+ *   states_in   int32 [B];  states_out  int32 [B], a different array (callers alternate two)
+ *   logits, dtype, row_stride, tok_bits_out   as for cfgzip_apply_mask
+ */
+int cfgzip_engine_step(void *logits, int32_t dtype, int32_t B, int32_t V, int64_t row_stride,
+                       const int32_t *state_mask, int32_t S, int32_t C,
+                       const int32_t *class_of_token, const uint16_t *sig_rep,
+                       const int32_t *tok_prev, const int32_t *states_in, int32_t *states_out,
+                       int32_t *tok_bits_out, void *stream);
 int cfgzip_class_masks(const int32_t *state_mask, int32_t S, int32_t C, const int32_t *states,
                        int32_t B, int32_t *cls_bits, void *stream);
 int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,

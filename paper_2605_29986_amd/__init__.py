@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     cfgzip_build_classes,
     cfgzip_class_masks,
     cfgzip_displacements,
+    cfgzip_engine_step,
     cfgzip_expand_mask,
     cfgzip_map_to_rep,
     cfgzip_nfa_signatures,

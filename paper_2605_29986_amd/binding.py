@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_class_masks.argtypes = [vp, i32, i32, vp, i32, vp, vp]
     lib.cfgzip_advance_states.restype = ctypes.c_int
     lib.cfgzip_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_engine_step.restype = ctypes.c_int
+    lib.cfgzip_engine_step.argtypes = [vp, i32, i32, i32, i64, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.cfgzip_representative_vocabulary.restype = ctypes.c_int
     lib.cfgzip_representative_vocabulary.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp]
     lib.cfgzip_nfa_signatures.restype = ctypes.c_int
@@ -403,3 +405,38 @@ def cfgzip_representative_vocabulary(tok_bytes: torch.Tensor, tok_off: torch.Ten
         rep_bytes.data_ptr(), capacity, _stream(stream))
     _check("cfgzip_representative_vocabulary", rc)
     return rep_bytes, rep_off
+
+
+def cfgzip_engine_step(logits: torch.Tensor, state_mask: torch.Tensor, C: int,
+                       class_of_token: torch.Tensor, sig_rep: Optional[torch.Tensor],
+                       tok_prev: Optional[torch.Tensor], states_in: torch.Tensor, *,
+                       states_out: Optional[torch.Tensor] = None,
+                       tok_bits_out: Optional[torch.Tensor] = None, V: Optional[int] = None,
+                       stream=None) -> torch.Tensor:
+    """One decode step of the byte-automaton engine in one launch: advances the states on the
+    tokens sampled last (tok_prev, or None at the first step), masks `logits` in place with each
+    sequence's class mask, returns the new states (int32 [B], a tensor other than states_in)."""
+    lib = load_library()
+    if logits.dtype == torch.float32:
+        dtype = 0
+    elif logits.dtype == torch.bfloat16:
+        dtype = 1
+    else:
+        raise TypeError("logits must be float32 or bfloat16")
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be a 2-D GPU tensor with unit column stride")
+    B = logits.shape[0]
+    V = int(V) if V is not None else logits.shape[1]
+    S = state_mask.shape[0]
+    if states_out is None:
+        states_out = torch.empty_like(states_in)
+    rc = lib.cfgzip_engine_step(
+        logits.data_ptr(), dtype, B, V, logits.stride(0), _dev(state_mask, torch.int32, "state_mask"), S, C,
+        _dev(class_of_token, torch.int32, "class_of_token"),
+        _dev(sig_rep, torch.uint16, "sig_rep") if sig_rep is not None else None,
+        _dev(tok_prev, torch.int32, "tok_prev") if tok_prev is not None else None,
+        _dev(states_in, torch.int32, "states_in"), _dev(states_out, torch.int32, "states_out"),
+        _dev(tok_bits_out, torch.int32, "tok_bits_out") if tok_bits_out is not None else None,
+        _stream(stream))
+    _check("cfgzip_engine_step", rc)
+    return states_out

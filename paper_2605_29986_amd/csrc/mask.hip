@@ -24,6 +24,7 @@ constexpr int kTileCols = kThreads * kCols;    // 2048 columns per workgroup
 constexpr int kUnroll = 2;                     // rows in flight per thread
 constexpr int kRowsStream = 4;                 // rows per workgroup when logits are streamed
 constexpr int kRowsExpand = 16;                // rows per workgroup for mask expansion alone
+constexpr int kMaxRowsPerBlock = 16;           // the larger of the two
 
 enum : int { LOGITS_NONE = 0, LOGITS_BF16 = 1, LOGITS_F32 = 2 };
 
@@ -48,6 +49,14 @@ struct MaskArgs {
     int32_t *tok_bits_out;
     int32_t rows_per_block;
     int32_t col_tiles;
+    // engine step (all null otherwise): the class-mask row of sequence b is row q[b] of
+    // state_mask, q[b] the sequence's automaton state after the token sampled last
+    const int32_t *state_mask;  // [S][Wc]
+    const uint16_t *sig_rep;    // [C][S]
+    const int32_t *tok_prev;    // [B] or null: no advance
+    const int32_t *states_in;   // [B]
+    int32_t *states_out;        // [B]
+    int32_t S, C;
 };
 
 __device__ __forceinline__ uint32_t select_bf16_pair(uint32_t x, uint32_t two_bits) {
@@ -72,8 +81,35 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(MaskArgs a) {
 
     if (FROM_CLASS) {
         const int n = nrows * a.Wc;
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.bits_in) + (int64_t)r0 * a.Wc;
-        for (int i = threadIdx.x; i < n; i += kThreads) cls_lds[i] = src[i];
+        if (a.state_mask) {
+            // engine step: advance the rows' automaton states on the representative of the token
+            // sampled last, then take each row's class mask from the table of per-state masks
+            __shared__ int32_t q_s[kMaxRowsPerBlock];
+            if ((int)threadIdx.x < nrows) {
+                const int b = r0 + threadIdx.x;
+                int32_t q = a.states_in[b];
+                if (a.tok_prev) {
+                    const int32_t t = a.tok_prev[b];
+                    int32_t next = -1;
+                    if (t >= 0 && t < a.V && q >= 0 && q < a.S) {
+                        const int32_t k = a.class_of_token[t];
+                        if (k >= 0 && k < a.C) next = (int32_t)a.sig_rep[(size_t)k * a.S + q];
+                    }
+                    q = next;
+                }
+                q_s[threadIdx.x] = (q >= 0 && q < a.S) ? q : -1;
+                if (ct == 0) a.states_out[b] = q;  // one column tile writes the new states
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < n; i += kThreads) {
+                const int r = i / a.Wc, w = i - r * a.Wc;
+                const int32_t q = q_s[r];
+                cls_lds[i] = q >= 0 ? (uint32_t)a.state_mask[(size_t)q * a.Wc + w] : 0u;
+            }
+        } else {
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(a.bits_in) + (int64_t)r0 * a.Wc;
+            for (int i = threadIdx.x; i < n; i += kThreads) cls_lds[i] = src[i];
+        }
         __syncthreads();
     }
     if (col0 >= a.Wv * 32) return;  // past the padded end of a mask row: nothing to do
@@ -246,10 +282,28 @@ int dispatch_mask(const MaskArgs &args, bool write_bits, bool vec, int grid, siz
 }
 
 // Shared host path of cfgzip_expand_mask and cfgzip_apply_mask.
+struct EngineStep {
+    const int32_t *state_mask;
+    const uint16_t *sig_rep;
+    const int32_t *tok_prev;
+    const int32_t *states_in;
+    int32_t *states_out;
+    int32_t S;
+};
+
 int run_mask(void *logits, int logits_kind, int32_t B, int32_t V, int64_t row_stride,
              const int32_t *bits, bool from_class, const int32_t *class_of_token, int32_t C,
-             int32_t *tok_bits_out, hipStream_t stream) {
+             int32_t *tok_bits_out, hipStream_t stream, const EngineStep *engine = nullptr) {
     MaskArgs a{};
+    if (engine) {
+        a.state_mask = engine->state_mask;
+        a.sig_rep = engine->sig_rep;
+        a.tok_prev = engine->tok_prev;
+        a.states_in = engine->states_in;
+        a.states_out = engine->states_out;
+        a.S = engine->S;
+        a.C = C;
+    }
     a.logits = logits;
     a.row_stride = row_stride;
     a.B = B;
@@ -333,6 +387,27 @@ extern "C" int cfgzip_apply_mask(void *logits, int32_t dtype, int32_t B, int32_t
     return run_mask(logits, dtype == CFGZIP_DTYPE_BF16 ? LOGITS_BF16 : LOGITS_F32, B, V, row_stride,
                     bits, from_class, class_of_token, C, tok_bits_out,
                     static_cast<hipStream_t>(stream));
+}
+
+extern "C" int cfgzip_engine_step(void *logits, int32_t dtype, int32_t B, int32_t V,
+                                  int64_t row_stride, const int32_t *state_mask, int32_t S, int32_t C,
+                                  const int32_t *class_of_token, const uint16_t *sig_rep,
+                                  const int32_t *tok_prev, const int32_t *states_in,
+                                  int32_t *states_out, int32_t *tok_bits_out, void *stream) {
+    if (!logits || !state_mask || !class_of_token || !states_in || !states_out) return CFGZIP_E_INVALID;
+    if (B <= 0 || V <= 0 || S <= 0 || S > 65536 || C <= 0 || row_stride < V) return CFGZIP_E_INVALID;
+    if (tok_prev && !sig_rep) return CFGZIP_E_INVALID;
+    if (states_in == states_out) return CFGZIP_E_INVALID;  // every column tile reads the old states
+    if (dtype != CFGZIP_DTYPE_F32 && dtype != CFGZIP_DTYPE_BF16) return CFGZIP_E_INVALID;
+    const size_t esz = dtype == CFGZIP_DTYPE_BF16 ? 2 : 4;
+    if (!aligned_to(logits, esz) || !aligned_to(state_mask, 4) || !aligned_to(class_of_token, 4) ||
+        !aligned_to(sig_rep, 2) || !aligned_to(tok_prev, 4) || !aligned_to(states_in, 4) ||
+        !aligned_to(states_out, 4) || !aligned_to(tok_bits_out, 4))
+        return CFGZIP_E_INVALID;
+    EngineStep e{state_mask, sig_rep, tok_prev, states_in, states_out, S};
+    return run_mask(logits, dtype == CFGZIP_DTYPE_BF16 ? LOGITS_BF16 : LOGITS_F32, B, V, row_stride,
+                    state_mask, true, class_of_token, C, tok_bits_out,
+                    static_cast<hipStream_t>(stream), &e);
 }
 
 extern "C" int cfgzip_map_to_rep(const int32_t *tok, int32_t B, const int32_t *class_of_token,

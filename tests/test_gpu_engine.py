@@ -180,3 +180,77 @@ def test_representative_vocabulary_edge_cases(lib, cfg1):
         got = rep_bytes.cpu().numpy()
         assert (got[:small] == want_bytes[:small]).all() and (got[small:] == 0xCD).all()
         assert int(rep_off[-1].item()) == cap
+
+
+@pytest.mark.parametrize("config,dtype", [(1, "f32"), (2, "bf16")])
+def test_closed_decode_loop_in_one_launch_per_step(lib, config, dtype):
+    """cfgzip_engine_step (advance on the last sampled tokens, class masks, fused expand + apply
+    in one launch) against the definition, step by step, including sequences that fall into the
+    reject state, an invalid state and out-of-range token ids."""
+    from gpu_util import dev, vocab_dev, logits_dev, logits_bits
+    cfg = si.make_config(config, V=4096 if config == 1 else 6000)
+    vocab, table = cfg["vocab"], cfg["table"]
+    V, S = vocab.V, cfg["S"]
+    tb, to, tt = vocab_dev(vocab, table)
+    sig, h = lib.cfgzip_signatures(tb, to, tt)
+    c_d, r_d, C, _ = lib.cfgzip_build_classes(tb, to, tt, sig, h)
+    want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+    want_c, want_r = oracle.build_classes(want_sig, vocab.tok_off)
+    rng = np.random.default_rng(cfg["seed"] + 6)
+    live = oracle.live_states(table, _accepting(rng, S))
+    sig_rep = _rep_signatures_on_gpu(lib, vocab, table, want_r)
+    state_mask = lib.cfgzip_state_masks(sig_rep, dev(live))
+    want_sm = oracle.state_masks(want_sig[want_r], live)
+
+    B, steps = 19, 8         # 19 rows: a ragged last row chunk
+    states_np = rng.integers(1, S, size=B).astype(np.int32)
+    states_np[3] = S + 5     # not a state: everything is masked, the state stays invalid
+    states = [dev(states_np), torch.empty(B, dtype=torch.int32, device="cuda")]
+    tok_prev = None
+    ninf = np.uint32(0xFF800000) if dtype == "f32" else np.uint16(0xFF80)
+    for step in range(steps):
+        if dtype == "f32":
+            x = rng.standard_normal((B, V)).astype(np.float32).view(np.uint32)
+        else:
+            x = si.make_decode_inputs(step, B, V, C, "bf16")["logits"]
+        lg = logits_dev(x, dtype)
+        tok_bits = torch.full((B, words_for(V)), -1, dtype=torch.int32, device="cuda")
+        src, dst = states[step % 2], states[(step + 1) % 2]
+        out = lib.cfgzip_engine_step(lg, state_mask, C, c_d, sig_rep, None if tok_prev is None else dev(tok_prev),
+                                     src, states_out=dst, tok_bits_out=tok_bits)
+        assert out.data_ptr() == dst.data_ptr()
+        # the definition: advance, then the class mask of the new state, expanded and applied
+        if tok_prev is not None:
+            states_np = oracle.advance_states(want_sig[want_r], want_c, tok_prev, states_np)
+        assert (dst.cpu().numpy() == states_np).all(), step
+        want_bits = oracle.expand_mask(oracle.class_masks(want_sm, C, states_np), want_c, C)
+        assert (tok_bits.cpu().numpy() == want_bits).all(), step
+        assert (logits_bits(lg) == oracle.apply_mask(x, want_bits, dtype)).all(), step
+        allowed = np.unpackbits(want_bits.view(np.uint8), axis=1, bitorder="little")[:, :V].astype(bool)
+        assert (logits_bits(lg)[~allowed] == ninf).all()
+        assert not allowed[3].any()
+        # the separate calls give the same
+        cls = lib.cfgzip_class_masks(state_mask, C, dst)
+        lg2 = logits_dev(x, dtype)
+        lib.cfgzip_apply_mask(lg2, cls, class_of_token=c_d, C=C)
+        assert (logits_bits(lg2) == logits_bits(lg)).all()
+        tok_prev = rng.integers(0, V, size=B).astype(np.int32)
+        tok_prev[5] = V + 1 if step == 2 else tok_prev[5]   # once: an id out of range -> state -1
+    assert (states_np[[3, 5]] == -1).all()
+
+
+def test_engine_step_argument_errors(lib):
+    raw = lib.load_library()
+    t = torch.zeros(256, dtype=torch.int32, device="cuda")
+    p = t.data_ptr()
+    ok = dict(logits=p, dtype=0, B=1, V=8, stride=8, sm=p, S=1, C=1, c=p, sr=p, tp=p, si=p, so=p + 64, tb=None)
+
+    def call(**kw):
+        a = dict(ok); a.update(kw)
+        return raw.cfgzip_engine_step(a["logits"], a["dtype"], a["B"], a["V"], a["stride"], a["sm"], a["S"], a["C"],
+                                      a["c"], a["sr"], a["tp"], a["si"], a["so"], a["tb"], None)
+    assert call(so=p) == -1            # states_out must differ from states_in
+    assert call(sr=None) == -1         # an advance needs the representatives' signatures
+    assert call(S=70000) == -1 and call(stride=4) == -1 and call(dtype=7) == -1 and call(sm=None) == -1
+    assert call(sr=None, tp=None) == 0
+    torch.cuda.synchronize()
