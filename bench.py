@@ -33,7 +33,7 @@ N_LOGIT_BUFFERS = 8    # 8 x 65.7 MB = 525 MB > 256 MB memory-side cache
 # HBM bytes per launch of the mask kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a plain copy of known size (profiles/mask_kernel_config5_hbm_counters.md);
 # set to None whenever the bf16 mask kernel changes until the counters are taken again
-MASK_KERNEL_TRAFFIC_BYTES = 141_630_000
+MASK_KERNEL_TRAFFIC_BYTES = 141_270_000
 
 
 def log(msg: str) -> None:
