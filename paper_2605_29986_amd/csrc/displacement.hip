@@ -36,9 +36,14 @@ constexpr int kMaxRowLen = 4096;
 constexpr int kMaxSymbols = 4096;
 constexpr int kMaxByteSymbols = 255;           // up to here a symbol (and "none") fits a byte
 
-// caps of the first pass over all tokens and of the second pass over those it could not finish
+// caps of the first pass over all tokens and of the second pass over those it could not finish.
+// The second pass runs in two steps: with the first pass's frontier capacity (half the LDS, twice
+// the waves per compute unit; enough for most of what the first pass hands on), then with the full
+// one for what is still left.  A token that gets through the narrower step would have got through
+// the wider one with the same result, so the two steps together are one pass under kFrontier2.
 constexpr int kIn1 = 12, kOut1 = 12, kFrontier1 = 128;
 constexpr int kIn2 = 32, kOut2 = 32, kFrontier2 = 256;
+constexpr int kFrontier2Narrow = 128;
 // the second pass keeps the current byte's productions and the relation in LDS when they fit
 constexpr int kStageCap = 128;      // productions of one terminal
 constexpr int kAdjLdsWords = 512;   // N * W(N) words: N <= 128
@@ -65,9 +70,10 @@ constexpr int kStatusBadGrammar = 2;
 
 struct GrammarHeader {
     int32_t invalid;      // set by the index kernel when the productions break a stated rule
-    int32_t retry_count;  // tokens the first pass handed to the second
-    int32_t retry_next;   // next entry of the retry list to be taken
-    int32_t pad[61];
+    // two lists of tokens handed on: by the first pass, and by the pass after it
+    int32_t retry_count[2];
+    int32_t retry_next[2];  // next entry of each list to be taken
+    int32_t pad[59];
 };
 
 struct Grammar {
@@ -85,7 +91,7 @@ struct GrammarWorkspace {
     uint32_t *reach[2]; // [N][W]: reachability over "right-most body symbol" edges
     uint32_t *adj;      // [N][W]: bit Y of row Z <=> (Y, Z) stack-adjacent
     int32_t *pair_first;  // [256][N]: 1 + index of the first production with (terminal, head), 0 = none
-    int32_t *retry_list;  // [V]: ids of the tokens for the second pass
+    int32_t *retry_list[2];  // [V] each: ids of the tokens handed on
     size_t clear_words; // words from hdr to the end that start at zero
     size_t bytes;
 };
@@ -107,7 +113,8 @@ GrammarWorkspace carve_grammar_ws(void *ws, int N, int V) {
     g.pair_first = reinterpret_cast<int32_t *>(take((size_t)256 * N * 4));
     g.clear_words = off / 4;
     g.reach[1] = reinterpret_cast<uint32_t *>(take((size_t)N * W * 4));  // fully written
-    g.retry_list = reinterpret_cast<int32_t *>(take((size_t)V * 4));
+    g.retry_list[0] = reinterpret_cast<int32_t *>(take((size_t)V * 4));
+    g.retry_list[1] = reinterpret_cast<int32_t *>(take((size_t)V * 4));
     g.bytes = off;
     return g;
 }
@@ -242,7 +249,7 @@ struct DisplacementArgs {
     uint16_t *rows;
     uint64_t *hash;
     int32_t *status;
-    int32_t *retry_list;
+    int32_t *retry_list[2];
     uint64_t seed;
     int V, row_len;
 };
@@ -365,9 +372,9 @@ struct TokenLds {
 };
 
 // The displacement of token t under the caps MAX_IN, MAX_OUT, FRONTIER, by the whole wave.
-// FIRST_PASS: a token that crosses a cap is appended to the retry list (and still gets the
-// overflow row, which the second pass overwrites if it gets through).
-template <typename Sym, int MAX_IN, int MAX_OUT, int FRONTIER, bool FIRST_PASS, bool STAGE>
+// HAND_ON >= 0: a token that crosses a cap is appended to that retry list (and still gets the
+// overflow row, which a later pass overwrites if it gets through).
+template <typename Sym, int MAX_IN, int MAX_OUT, int FRONTIER, int HAND_ON, bool STAGE>
 __device__ void token_displacement(const DisplacementArgs &a, int t,
                                    TokenLds<Sym, Rec<Sym, MAX_IN, MAX_OUT>, FRONTIER, STAGE> &L,
                                    bool adj_in_lds) {
@@ -524,7 +531,8 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
             mix.add((uint32_t)t >> 16);
             a.hash[t] = mix.done();
             if (a.status) a.status[t] = kStatusOverflow;
-            if (FIRST_PASS && caps_crossed) a.retry_list[atomicAdd(&a.hdr->retry_count, 1)] = t;
+            if (HAND_ON >= 0 && caps_crossed)
+                a.retry_list[HAND_ON < 0 ? 0 : HAND_ON][atomicAdd(&a.hdr->retry_count[HAND_ON < 0 ? 0 : HAND_ON], 1)] = t;
         }
     } else {
         uint64_t h = 0;
@@ -602,26 +610,45 @@ __global__ __launch_bounds__(64) void displacement_kernel(DisplacementArgs a) {
         }
         return;
     }
-    token_displacement<Sym, kIn1, kOut1, kFrontier1, true, false>(a, t, lds, false);
+    token_displacement<Sym, kIn1, kOut1, kFrontier1, 0, false>(a, t, lds, false);
 }
 
-// second pass: persistent workgroups of one wave take the retry list entry by entry
-template <typename Sym>
+// second pass: persistent workgroups of one wave take retry list LIST entry by entry; what they
+// cannot finish goes to list HAND_ON (none if negative)
+template <typename Sym, int FRONTIER, int LIST, int HAND_ON>
 __global__ __launch_bounds__(64) void displacement_retry_kernel(DisplacementArgs a) {
-    __shared__ TokenLds<Sym, Rec<Sym, kIn2, kOut2>, kFrontier2, true> lds;
-    const int count = min(a.hdr->retry_count, a.V);
+    __shared__ TokenLds<Sym, Rec<Sym, kIn2, kOut2>, FRONTIER, true> lds;
+    const int count = min(a.hdr->retry_count[LIST], a.V);
     if (count == 0) return;
     const bool adj_in_lds = a.g.N * a.g.W <= kAdjLdsWords;
     if (adj_in_lds)
         for (int i = threadIdx.x; i < a.g.N * a.g.W; i += 64) lds.adj[i] = a.adj[i];
     for (;;) {
-        if (threadIdx.x == 0) lds.next_item = atomicAdd(&a.hdr->retry_next, 1);
+        if (threadIdx.x == 0) lds.next_item = atomicAdd(&a.hdr->retry_next[LIST], 1);
         __syncthreads();
         const int i = lds.next_item;
         __syncthreads();
         if (i >= count) break;  // the same for every lane
-        token_displacement<Sym, kIn2, kOut2, kFrontier2, false, true>(a, a.retry_list[i], lds, adj_in_lds);
+        token_displacement<Sym, kIn2, kOut2, FRONTIER, HAND_ON, true>(a, a.retry_list[LIST][i], lds, adj_in_lds);
     }
+}
+
+template <typename Sym>
+int launch_displacements(const DisplacementArgs &a, int n_cu, hipStream_t stream) {
+    hipLaunchKernelGGL(displacement_kernel<Sym>, dim3((unsigned)a.V), dim3(64), 0, stream, a);
+    CFGZIP_TRY(check_launch());
+    // as many one-wave workgroups as the LDS of all compute units holds at once
+    auto grid_for_lds = [&](size_t lds) {
+        return (unsigned)std::min<int64_t>(a.V, (int64_t)n_cu * std::max<size_t>(1, (160 * 1024) / lds));
+    };
+    hipLaunchKernelGGL((displacement_retry_kernel<Sym, kFrontier2Narrow, 0, 1>),
+                       dim3(grid_for_lds(sizeof(TokenLds<Sym, Rec<Sym, kIn2, kOut2>, kFrontier2Narrow, true>))),
+                       dim3(64), 0, stream, a);
+    CFGZIP_TRY(check_launch());
+    hipLaunchKernelGGL((displacement_retry_kernel<Sym, kFrontier2, 1, -1>),
+                       dim3(grid_for_lds(sizeof(TokenLds<Sym, Rec<Sym, kIn2, kOut2>, kFrontier2, true>))),
+                       dim3(64), 0, stream, a);
+    return check_launch();
 }
 
 int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, const uint8_t *prod_len,
@@ -696,7 +723,8 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
     a.rows = rows_out;
     a.hash = hash_out;
     a.status = status_out;
-    a.retry_list = w.retry_list;
+    a.retry_list[0] = w.retry_list[0];
+    a.retry_list[1] = w.retry_list[1];
     a.seed = hash_seed;
     a.V = V;
     a.row_len = row_len;
@@ -707,19 +735,6 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
         CFGZIP_TRY(check_hip(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)));
         if (n_cu <= 0) n_cu = 256;
     }
-    const bool bytes = N <= kMaxByteSymbols;
-    // second pass: as many one-wave workgroups as the LDS of all compute units holds at once
-    const size_t lds2 = bytes ? sizeof(TokenLds<uint8_t, Rec<uint8_t, kIn2, kOut2>, kFrontier2, true>)
-                              : sizeof(TokenLds<uint16_t, Rec<uint16_t, kIn2, kOut2>, kFrontier2, true>);
-    const unsigned grid2 = (unsigned)std::min<int64_t>(V, (int64_t)n_cu * std::max<size_t>(1, (160 * 1024) / lds2));
-    if (bytes) {
-        hipLaunchKernelGGL(displacement_kernel<uint8_t>, dim3((unsigned)V), dim3(64), 0, stream, a);
-        CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(displacement_retry_kernel<uint8_t>, dim3(grid2), dim3(64), 0, stream, a);
-    } else {
-        hipLaunchKernelGGL(displacement_kernel<uint16_t>, dim3((unsigned)V), dim3(64), 0, stream, a);
-        CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(displacement_retry_kernel<uint16_t>, dim3(grid2), dim3(64), 0, stream, a);
-    }
-    return check_launch();
+    return N <= kMaxByteSymbols ? launch_displacements<uint8_t>(a, n_cu, stream)
+                                : launch_displacements<uint16_t>(a, n_cu, stream);
 }
