@@ -70,37 +70,57 @@ def stack_adjacency(productions: Sequence[Production]) -> Set[Tuple[NT, NT]]:
     return adj
 
 
+def successors(config, ch, by_terminal, by_pair, adjacency):
+    """One step of the one-state pushdown automaton as Algorithm 1 takes it.  A configuration is
+    (input queue, output stack, symbol consumed last); `ch` is the byte read.
+      * Output stack not empty: its top A is consumed by a production A -> ch beta, whose body
+        takes A's place.
+      * Output stack empty (stack backtrack): the token reaches below what it pushed itself, so
+        the symbol it meets there is guessed: any A with a production A -> ch beta that may come
+        right after the symbol consumed last (stack adjacency, Section 3.2.2) is appended to the
+        input queue and beta becomes the output stack.  Before anything was consumed every A may
+        be guessed."""
+    queue, stack, last = config
+    if stack:
+        top = stack[0]
+        for beta in by_pair.get((ch, top), ()):
+            yield (queue, beta + stack[1:], top)
+    else:
+        for A, beta in by_terminal.get(ch, ()):
+            if last is None or adjacency == "all" or (last, A) in adjacency:
+                yield (queue + (A,), beta, A)
+
+
 def displacement(token: Sequence, productions: Sequence[Production],
-                 adjacency=None) -> FrozenSet[Tuple[Stack, Stack]]:
-    """Algorithm 1: the set of (input queue, output stack) pairs of `token`.
-    `adjacency` defaults to stack_adjacency(productions); pass the string
-    "all" to leave the backtrack unrestricted."""
+                 adjacency=None, index=None) -> FrozenSet[Tuple[Stack, Stack]]:
+    """Algorithm 1: the displacement of `token`, the set of (input queue, output stack) pairs
+    with which the automaton can read it.  Depth first over the bytes, from the configuration
+    that has consumed and pushed nothing; a configuration met again at the same position is not
+    explored twice.  `adjacency` defaults to stack_adjacency(productions); the string "all"
+    leaves the stack backtrack unrestricted; `index` = index_productions(productions) if the
+    caller already has it."""
     token = tuple(token)
-    d = delta(productions)
     if adjacency is None:
         adjacency = stack_adjacency(productions)
-    by_terminal: Dict[object, List[Tuple[NT, Stack]]] = defaultdict(list)
-    for A, a, beta in productions:
-        if (A, tuple(beta)) not in by_terminal[a]:
-            by_terminal[a].append((A, tuple(beta)))
-    EMPTY = object()  # A_prev before anything was consumed
+    by_terminal, by_pair = index if index is not None else index_productions(productions)
+    done: Dict[tuple, FrozenSet[Tuple[Stack, Stack]]] = {}
 
-    def cd(pos: int, sigma_i: Stack, sigma_o: Stack, a_prev) -> Set[Tuple[Stack, Stack]]:
+    def finish(pos: int, config) -> FrozenSet[Tuple[Stack, Stack]]:
+        """Pairs reachable at the end of the token from `config` with token[:pos] read."""
         if pos == len(token):
-            return {(sigma_i, sigma_o)}
-        out: Set[Tuple[Stack, Stack]] = set()
-        ch = token[pos]
-        if len(sigma_o) == 0:  # stack backtrack: consume one more symbol of the input stack
-            for A, beta in by_terminal.get(ch, ()):
-                if a_prev is EMPTY or adjacency == "all" or (a_prev, A) in adjacency:
-                    out |= cd(pos + 1, sigma_i + (A,), beta, A)
-        else:
-            top = sigma_o[0]
-            for beta in d.get((ch, top), ()):
-                out |= cd(pos + 1, sigma_i, beta + sigma_o[1:], top)
-        return out
+            return frozenset({(config[0], config[1])})
+        key = (pos, config)
+        if key not in done:
+            found: Set[Tuple[Stack, Stack]] = set()
+            for nxt in successors(config, token[pos], by_terminal, by_pair, adjacency):
+                found |= finish(pos + 1, nxt)
+            done[key] = frozenset(found)
+        return done[key]
 
-    return frozenset(cd(0, (), (), EMPTY))
+    import sys
+    if len(token) + 50 > sys.getrecursionlimit():
+        sys.setrecursionlimit(len(token) + 200)
+    return finish(0, ((), (), None))
 
 
 def pi(token: Sequence, alpha: Stack, d) -> Set[Stack]:
@@ -168,26 +188,23 @@ def right_linear_grammar(table, accepting: Iterable[int], reject: int = 0) -> Li
 
 
 # ---------------------------------------------------------------------------------------------
-# Bounded, level-by-level form of Algorithm 1 and the fixed-length encoding of its result.
+# What a library with fixed-size buffers may give up on, and the fixed-length encoding of a set.
 #
-# A library that computes displacements into fixed-size buffers has to bound what Algorithm 1
-# leaves unbounded.  This section states those bounds and the encoding once more, on the CPU:
-#   * symbols are integers 0 .. N-1 (N <= 4096), a production body has at most 4 of them;
-#   * a configuration is (input queue, output stack, A_prev); the frontier after p bytes is the
-#     SET of configurations Algorithm 1's recursion reaches at depth p;
-#   * under caps (max_in, max_out, max_frontier) the computation of a token FAILS when a
-#     successor would hold more than max_in queue symbols or more than max_out stack symbols, or
-#     when the successors of one frontier, counted with multiplicity (one per configuration and
-#     matching production), number more than max_frontier;
-#   * a token is first taken under DISP_CAPS_FIRST; if that fails, once more under
-#     DISP_CAPS_SECOND; if that fails too, or if the encoded set does not fit the row, the token
-#     OVERFLOWS: it gets a row and a hash that no other token has (a class of its own: a smaller
-#     compression, never a wrong one).
-# Without overflow the result is the set Algorithm 1 returns; the tests pin that.
+# Algorithm 1 has no bounds.  The C interface states limits (include/cfgzip.h, "Bounds"), over the
+# quantities of Algorithm 1 itself: with C_p the set of configurations reached after p bytes,
+#   * no successor of a configuration of C_p may hold more than LIMIT_QUEUE input-queue symbols or
+#     more than LIMIT_STACK output-stack symbols;
+#   * the successors of C_p, one per configuration and applicable production (counted before equal
+#     ones fall together), may number at most LIMIT_SUCCESSORS;
+#   * the encoded set must fit the caller's row.
+# A token that breaks one of them OVERFLOWS: it gets a row and a hash no other token has (a class
+# of its own: less compression, never a wrong answer).  Otherwise the row holds exactly the set
+# displacement() returns; tests/test_oracle_displacement_rows.py pins that.
 # ---------------------------------------------------------------------------------------------
 
-DISP_CAPS_FIRST = (12, 12, 128)
-DISP_CAPS_SECOND = (32, 32, 256)
+LIMIT_QUEUE = 32
+LIMIT_STACK = 32
+LIMIT_SUCCESSORS = 256
 DISP_ROW_LEN = 256            # default row length; any multiple of 256 up to 4096
 DISP_OK = 0
 DISP_OVERFLOW = 1
@@ -196,48 +213,31 @@ _M64 = (1 << 64) - 1
 
 def index_productions(productions: Sequence[Production]):
     """The distinct productions, by terminal and by (terminal, head)."""
-    by_terminal: Dict[int, List[Tuple[int, Stack]]] = defaultdict(list)
-    by_pair: Dict[Tuple[int, int], List[Stack]] = defaultdict(list)
+    by_terminal: Dict[object, List[Tuple[NT, Stack]]] = defaultdict(list)
+    by_pair: Dict[Tuple[object, NT], List[Stack]] = defaultdict(list)
     for A, a, beta in sorted(set((A, a, tuple(beta)) for (A, a, beta) in productions)):
         by_terminal[a].append((A, beta))
         by_pair[(a, A)].append(beta)
     return by_terminal, by_pair
 
 
-def displacement_bounded(token: Sequence[int], productions: Sequence[Production], adjacency,
-                         index=None, caps=DISP_CAPS_FIRST):
-    """Algorithm 1 taken one byte at a time over the set of live configurations.  Returns the
-    frozenset of (queue, stack) pairs, or None when `caps` are crossed (see above).  `adjacency`
-    is a set of (Y, Z) pairs; `index` = index_productions(productions) if the caller has it."""
-    max_in, max_out, max_frontier = caps
+def displacement_within_limits(token: Sequence[int], productions: Sequence[Production], adjacency,
+                               index=None, limits=(LIMIT_QUEUE, LIMIT_STACK, LIMIT_SUCCESSORS)):
+    """The displacement of `token` if every prefix keeps within `limits` (queue, stack,
+    successors per byte), else None.  Walks the sets C_0, C_1, .. of configurations reached after
+    each byte, so that it stops where a limit breaks instead of exploring a blow-up."""
+    max_queue, max_stack, max_successors = limits
     by_terminal, by_pair = index if index is not None else index_productions(productions)
-    frontier = {((), (), None)}
+    reached = {((), (), None)}
     for ch in token:
-        successors = []
-        for (q, s, prev) in frontier:
-            if len(s) == 0:      # stack backtrack
-                for A, beta in by_terminal.get(ch, ()):
-                    if prev is None or (prev, A) in adjacency:
-                        successors.append((q + (A,), beta, A))
-            else:                # pop the top, push the body
-                for beta in by_pair.get((ch, s[0]), ()):
-                    successors.append((q, beta + s[1:], s[0]))
-        if len(successors) > max_frontier:
+        following = [nxt for config in reached
+                     for nxt in successors(config, ch, by_terminal, by_pair, adjacency)]
+        if len(following) > max_successors:
             return None
-        for (q, s, _p) in successors:
-            if len(q) > max_in or len(s) > max_out:
-                return None
-        frontier = set(successors)
-    return frozenset((q, s) for (q, s, _p) in frontier)
-
-
-def displacement_two_passes(token, productions, adjacency, index=None):
-    """(pairs or None, pass that produced them: 1, 2, or 0 if both failed)."""
-    pairs = displacement_bounded(token, productions, adjacency, index, DISP_CAPS_FIRST)
-    if pairs is not None:
-        return pairs, 1
-    pairs = displacement_bounded(token, productions, adjacency, index, DISP_CAPS_SECOND)
-    return pairs, (2 if pairs is not None else 0)
+        if any(len(q) > max_queue or len(s) > max_stack for (q, s, _last) in following):
+            return None
+        reached = set(following)
+    return frozenset((q, s) for (q, s, _last) in reached)
 
 
 def displacement_record(pair) -> List[int]:
@@ -307,7 +307,9 @@ def displacement_rows(tokens: Sequence[bytes], productions: Sequence[Production]
     status = np.zeros(V, np.int32)
     index = index_productions(productions)
     for t, tok in enumerate(tokens):
-        pairs, _which = displacement_two_passes(tuple(tok), productions, adjacency, index)
+        pairs = displacement_within_limits(tuple(tok), productions, adjacency, index)
+        if pairs is not None:   # within the limits: the set is Algorithm 1's, by the definition
+            pairs = displacement(tuple(tok), productions, adjacency, index)
         rows[t], hashes[t], status[t] = encode_displacement(pairs, t, seed, row_len)
     return rows, hashes, status
 

@@ -1,9 +1,9 @@
-"""Pins for the bounded, level-by-level form of Algorithm 1 and for the fixed-length row
-encoding of a displacement set (the form the GPU library is compared with).
+"""Pins for the limits the C interface puts on Algorithm 1 (which tokens overflow) and for the
+fixed-length row encoding of a displacement set.
 
-The bounded form is pinned against the recursive Algorithm 1 (itself pinned by Figure 3, by
-Appendix B's second formulation and by the right-linear special case), the overflow rules by
-grammars built to cross exactly one bound each, the encoding by decoding it again."""
+Within the limits the result must be the set Algorithm 1 returns (oracle displacement(), itself
+pinned by Figure 3, by Appendix B's second formulation and by the right-linear special case);
+each limit is crossed alone by a grammar built for it; the encoding is pinned by decoding it."""
 
 import itertools
 
@@ -20,7 +20,7 @@ def _all_tokens(alphabet: bytes, max_len: int):
 
 
 @pytest.mark.parametrize("seed", range(8))
-def test_bounded_form_equals_algorithm_1(seed):
+def test_within_limits_the_result_is_algorithm_1(seed):
     g = make_random_gnf(100 + seed, n_nt=5, alphabet=b"abc", n_prod=16, max_body=3)
     prods = g.productions()
     adj = D.stack_adjacency(prods)
@@ -28,7 +28,7 @@ def test_bounded_form_equals_algorithm_1(seed):
     toks = _all_tokens(b"abc", 4)
     for tok in toks:
         want = D.displacement(tuple(tok), prods, adjacency=adj)
-        got = D.displacement_bounded(tuple(tok), prods, adj)
+        got = D.displacement_within_limits(tuple(tok), prods, adj)
         if got is None:      # a dense random grammar can cross the frontier bound
             overflowed += 1
             continue
@@ -38,14 +38,40 @@ def test_bounded_form_equals_algorithm_1(seed):
     assert overflowed * 4 < len(toks)
 
 
-def test_bounded_form_on_figure_3():
+@pytest.mark.parametrize("which", ["json", "clike"])
+def test_within_limits_the_result_is_algorithm_1_on_the_measured_grammars(which):
+    """The two hand-written grammars against the measured vocabulary: the first 3,000 tokens and
+    every token of 13 bytes or more among the first 30,000 (long digit runs reach deep queues)."""
+    import synthetic_inputs as si
+    from synthetic_inputs.grammar import make_clike_gnf, make_json_gnf
+    g = make_json_gnf() if which == "json" else make_clike_gnf()
+    prods = g.productions()
+    adj, index = D.stack_adjacency(prods), D.index_productions(prods)
+    vocab = si.make_config(3)["vocab"]
+    lens = np.diff(vocab.tok_off)
+    picked = list(range(3000)) + [t for t in range(3000, 30000) if lens[t] >= 13]
+    deep = alive = 0
+    for t in picked:
+        tok = tuple(vocab.token(t))
+        got = D.displacement_within_limits(tok, prods, adj, index)
+        if got is None:
+            continue
+        assert got == D.displacement(tok, prods, adj, index), (t, bytes(tok))
+        alive += len(got) > 0
+        deep += any(len(q) > 12 for (q, _s) in got)
+    assert alive > 500
+    if which == "json":
+        assert deep > 5, "digit runs must reach queues beyond a dozen symbols"
+
+
+def test_figure_3_is_within_limits():
     from golden_fixtures import read_fig3
     token, prods, _steps, res_i, res_o = read_fig3()
     names = sorted({p[0] for p in prods} | {b for p in prods for b in p[2]})
     num = {n: i for i, n in enumerate(names)}
     iprods = [(num[A], ord(a), tuple(num[b] for b in beta)) for (A, a, beta) in prods]
     adj = D.stack_adjacency(iprods)
-    got = D.displacement_bounded(tuple(token.encode()), iprods, adj)
+    got = D.displacement_within_limits(tuple(token.encode()), iprods, adj)
     assert got == frozenset({(tuple(num[x] for x in res_i), tuple(num[x] for x in res_o))})
 
 
@@ -53,35 +79,35 @@ def test_empty_token_and_dead_token():
     g = make_random_gnf(3, n_nt=3, alphabet=b"ab", n_prod=6)
     prods = g.productions()
     adj = D.stack_adjacency(prods)
-    assert D.displacement_bounded((), prods, adj) == frozenset({((), ())})
-    assert D.displacement_bounded((ord("z"),), prods, adj) == frozenset()
+    assert D.displacement_within_limits((), prods, adj) == frozenset({((), ())})
+    assert D.displacement_within_limits((ord("z"),), prods, adj) == frozenset()
     row, h, st = D.encode_displacement(frozenset(), 5, seed=1)
     assert st == D.DISP_OK and row == [0] * D.DISP_ROW_LEN and h == 0
     assert D.encode_displacement(frozenset({((), ())}), 5, seed=1)[0][:4] == [1, 0, 0, 0]
 
 
-@pytest.mark.parametrize("caps", [D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND])
+@pytest.mark.parametrize("caps", [(D.LIMIT_QUEUE, D.LIMIT_STACK, D.LIMIT_SUCCESSORS), (5, 7, 9)])
 def test_the_input_queue_cap(caps):
     # X -> x A A makes (A, A) stack-adjacent; A -> a.  "a" * k keeps backtracking into A.
     max_in = caps[0]
     prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ())]
     adj = D.stack_adjacency(prods)
     assert (1, 1) in adj
-    ok = D.displacement_bounded((ord("a"),) * max_in, prods, adj, caps=caps)
+    ok = D.displacement_within_limits((ord("a"),) * max_in, prods, adj, limits=caps)
     assert ok == frozenset({((1,) * max_in, ())})
-    assert D.displacement_bounded((ord("a"),) * (max_in + 1), prods, adj, caps=caps) is None
+    assert D.displacement_within_limits((ord("a"),) * (max_in + 1), prods, adj, limits=caps) is None
     # the unbounded algorithm goes on
     assert D.displacement((ord("a"),) * (max_in + 1), prods) == frozenset({((1,) * (max_in + 1), ())})
 
 
-@pytest.mark.parametrize("caps", [D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND])
+@pytest.mark.parametrize("caps", [(D.LIMIT_QUEUE, D.LIMIT_STACK, D.LIMIT_SUCCESSORS), (5, 7, 9)])
 def test_the_output_stack_cap(caps):
     max_out = caps[1]
     prods = [(0, ord("a"), (0, 0, 0, 0))]   # each byte: pop one, push four
     adj = D.stack_adjacency(prods)
     seen_none = False
     for k in range(1, 13):
-        got = D.displacement_bounded((ord("a"),) * k, prods, adj, caps=caps)
+        got = D.displacement_within_limits((ord("a"),) * k, prods, adj, limits=caps)
         depth = 4 + 3 * (k - 1)
         if depth <= max_out:
             assert got == frozenset({((0,), (0,) * depth)})
@@ -91,49 +117,40 @@ def test_the_output_stack_cap(caps):
     assert seen_none
 
 
-@pytest.mark.parametrize("caps", [D.DISP_CAPS_FIRST, D.DISP_CAPS_SECOND])
+@pytest.mark.parametrize("caps", [(D.LIMIT_QUEUE, D.LIMIT_STACK, D.LIMIT_SUCCESSORS), (5, 7, 9)])
 def test_the_frontier_cap_counts_successors_with_multiplicity(caps):
     n = caps[2]
     prods = [(i, ord("a"), ()) for i in range(n)]
     adj = D.stack_adjacency(prods)
-    got = D.displacement_bounded((ord("a"),), prods, adj, caps=caps)
+    got = D.displacement_within_limits((ord("a"),), prods, adj, limits=caps)
     assert got is not None and len(got) == n
     prods.append((n, ord("a"), ()))
-    assert D.displacement_bounded((ord("a"),), prods, D.stack_adjacency(prods), caps=caps) is None
+    assert D.displacement_within_limits((ord("a"),), prods, D.stack_adjacency(prods), limits=caps) is None
     # one configuration with n + 1 successors
     prods = [(0, ord("s"), (1,))] + [(1, ord("b"), (2 + i,)) for i in range(n + 1)]
-    assert D.displacement_bounded((ord("s"), ord("b")), prods, set(), caps=caps) is None
+    assert D.displacement_within_limits((ord("s"), ord("b")), prods, set(), limits=caps) is None
     assert len(D.displacement((ord("s"), ord("b")), prods)) == n + 1
     # n + 1 successors that fall together into one configuration still count n + 1
     prods = [(i, ord("a"), (n + 1,)) for i in range(n + 1)] + [(n + 1, ord("b"), ())]
-    got = D.displacement_bounded((ord("a"),), prods, set(), caps=caps)
+    got = D.displacement_within_limits((ord("a"),), prods, set(), limits=caps)
     assert got is None and len(D.displacement((ord("a"),), prods)) == n + 1
 
 
-def test_second_pass_takes_what_the_first_cannot():
+def test_rows_of_tokens_around_the_queue_limit():
     prods = [(0, ord("x"), (1, 1)), (1, ord("a"), ())]
-    adj = D.stack_adjacency(prods)
-    first_in, second_in = D.DISP_CAPS_FIRST[0], D.DISP_CAPS_SECOND[0]
-    assert first_in < second_in
-    assert D.displacement_two_passes((ord("a"),) * first_in, prods, adj)[1] == 1
-    pairs, which = D.displacement_two_passes((ord("a"),) * (first_in + 1), prods, adj)
-    assert which == 2 and pairs == D.displacement((ord("a"),) * (first_in + 1), prods)
-    pairs, which = D.displacement_two_passes((ord("a"),) * (second_in + 1), prods, adj)
-    assert which == 0 and pairs is None
-    toks = [b"a" * first_in, b"a" * (first_in + 1), b"a" * second_in, b"a" * (second_in + 1)]
+    n = D.LIMIT_QUEUE
+    toks = [b"a" * (n - 1), b"a" * n, b"a" * (n + 1)]
     rows, hashes, status = D.displacement_rows(toks, prods, seed=4)
-    assert status.tolist() == [0, 0, 0, 1]
-    assert D.decode_displacement(rows[2]) == frozenset({((1,) * second_in, ())})
-    # the same set found in either pass encodes alike
-    a = D.encode_displacement(D.displacement_bounded((ord("a"),) * 5, prods, adj), 0, 4)
-    b = D.encode_displacement(D.displacement_bounded((ord("a"),) * 5, prods, adj, caps=D.DISP_CAPS_SECOND), 0, 4)
-    assert a == b
+    assert status.tolist() == [0, 0, 1]
+    assert D.decode_displacement(rows[1]) == frozenset({((1,) * n, ())})
+    # the definition itself goes on where the library gives up
+    assert D.displacement(tuple(toks[2]), prods) == frozenset({((1,) * (n + 1), ())})
 
 
 def test_overflow_of_the_row():
     # 100 pairs of 2 + 1 + 1 entries: 401 > 256 entries, though the frontier bound holds
     prods = [(i, ord("a"), (0,)) for i in range(100)]
-    pairs = D.displacement_bounded((ord("a"),), prods, set())
+    pairs = D.displacement_within_limits((ord("a"),), prods, set())
     assert pairs is not None and len(pairs) == 100
     row, h, st = D.encode_displacement(pairs, 70000, seed=9)
     assert st == D.DISP_OVERFLOW
@@ -171,7 +188,7 @@ def test_encoding_round_trip_and_order_freedom(seed):
     rows = {}
     checked = 0
     for t, tok in enumerate(_all_tokens(b"abc", 4)):
-        pairs = D.displacement_bounded(tuple(tok), prods, adj)
+        pairs = D.displacement_within_limits(tuple(tok), prods, adj)
         row, h, st = D.encode_displacement(pairs, t, seed=77)
         if st != D.DISP_OK:     # a large set of an ambiguous grammar
             assert pairs is None or 1 + sum(2 + len(q) + len(o) for q, o in pairs) > D.DISP_ROW_LEN

@@ -111,19 +111,24 @@ def test_composition_law(which, request):
         assert (row == sig[b][sig[a]]).all()
 
 
-def test_matches_reference_walk_on_small_random_automata():
-    """The definition itself, in pure Python, on tiny random tables."""
+def test_signature_is_the_product_of_transition_matrices():
+    """Linear-algebra form: with M_b[q][q'] = 1 iff the automaton goes from q to q' on byte b,
+    row q of the product M_{t_1} .. M_{t_n} (numpy matrix products) is the unit vector of
+    sig[t][q].  A swapped operand order or a transposed table breaks it."""
     rng = np.random.default_rng(6)
     for S in (1, 2, 5, 9):
         table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+        M = np.zeros((256, S, S), dtype=np.int64)
+        for b in range(256):
+            M[b, np.arange(S), table[:, b]] = 1
         toks = _random_tokens(rng, 30, 5)
         sig = _sig(toks, table)
         for t, row in zip(toks, sig):
-            for q in range(S):
-                s = q
-                for byte in t:
-                    s = int(table[s][byte])
-                assert row[q] == s
+            prod = np.eye(S, dtype=np.int64)
+            for byte in t:
+                prod = prod @ M[byte]
+            assert (prod.sum(axis=1) == 1).all()
+            assert (prod.argmax(axis=1) == row).all()
 
 
 def test_uniform_vocab_shapes():
