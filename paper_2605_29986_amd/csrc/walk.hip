@@ -241,9 +241,12 @@ struct SigWorkspace {
     size_t bytes;
 };
 
+// The header comes first, so that a reader that only knows "this is some signature workspace"
+// can look at it before trusting any size-dependent offset.
 SigWorkspace carve_sig_ws(void *ws, int32_t V, int32_t S) {
     Carver c(ws);
     SigWorkspace w;
+    WalkStore *header = c.take<WalkStore>(1);
     w.Tt = c.take<uint16_t>((size_t)256 * S + kTablePad);
     w.nimg = c.take<int32_t>(kImageRows);
     w.img = c.take<uint16_t>((size_t)kImageRows * S);
@@ -251,7 +254,7 @@ SigWorkspace carve_sig_ws(void *ws, int32_t V, int32_t S) {
     w.wsum = c.take<uint64_t>((size_t)kImageRows * S);
     w.store = WalkStoreView{nullptr, nullptr, nullptr};
     if (V > 0) {
-        w.store.header = c.take<WalkStore>(1);
+        w.store.header = header;
         w.store.wrow = c.take<uint16_t>((size_t)V);
         w.store.wvec = c.take<uint16_t>((size_t)V * walk_store_stride(S));
     }
