@@ -4,8 +4,8 @@
     python bench.py --gpus 1 --steps K --warmup W
 
 Timed step = one decode step of the per-step path at batch 256, V = 128,256,
-C = 8,000 (fused expand + -inf apply with the token mask as by-product, then the
-map to representatives).  The same run also times the offline class build
+C = 8,000 (cfgzip_decode_step: fused expand + -inf apply with the token mask as
+by-product and the map to representatives, one launch).  The same run also times the offline class build
 (signatures + grouping) on the class-build workloads and the CPU oracle on a
 bounded sample.  Prints ONE JSON line.
 
@@ -30,10 +30,27 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E peak
 N_LOGIT_BUFFERS = 8    # 8 x 65.7 MB = 525 MB > 256 MB memory-side cache
-# HBM bytes per launch of the mask kernel on this workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE scaled by a plain copy of known size (profiles/mask_kernel_config5_hbm_counters.md);
-# set to None whenever the bf16 mask kernel changes until the counters are taken again
-MASK_KERNEL_TRAFFIC_BYTES = 141_270_000
+MASK_SOURCE = os.path.join(ROOT, "paper_2605_29986_amd", "csrc", "mask.hip")
+MASK_COUNTERS = os.path.join(ROOT, "profiles", "mask_kernel_config5_hbm_counters.md")
+
+
+def mask_kernel_traffic_bytes():
+    """HBM bytes per launch of the mask kernel on this workload, as counted by rocprofv3 --pmc
+    FETCH_SIZE and WRITE_SIZE (scaled by a plain copy of known size).  The summary of that
+    measurement names the kernel source it was taken on by its SHA-256; if the source has changed
+    since, the figure no longer describes the kernel and None is returned."""
+    import hashlib
+    import re
+    try:
+        text = open(MASK_COUNTERS).read()
+        digest = hashlib.sha256(open(MASK_SOURCE, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    nbytes = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", text, re.M)
+    source = re.search(r"^kernel_source_sha256:\s*([0-9a-f]{64})", text, re.M)
+    if not nbytes or not source or source.group(1) != digest:
+        return None
+    return int(nbytes.group(1))
 
 
 def log(msg: str) -> None:
@@ -401,8 +418,18 @@ def main() -> int:
     map_args = (vp(tok.data_ptr()), i32(B), vp(c5.data_ptr()), i32(V), vp(r5.data_ptr()), i32(C),
                 vp(rep_out.data_ptr()), sptr)
     apply_mask, map_to_rep = raw.cfgzip_apply_mask, raw.cfgzip_map_to_rep
+    # the timed step: mask and map in one launch (cfgzip_decode_step)
+    step_args = [(vp(lb.data_ptr()), i32(1), i32(B), i32(V), i64(V), vp(cb.data_ptr()), vp(c5.data_ptr()),
+                  i32(C), vp(tok_bits.data_ptr()), vp(tok.data_ptr()), vp(r5.data_ptr()),
+                  vp(rep_out.data_ptr()), sptr) for lb, cb in zip(logit_bufs, cls_bufs)]
+    decode_step = raw.cfgzip_decode_step
 
     def step(i: int) -> None:
+        rc = decode_step(*step_args[i % N_LOGIT_BUFFERS])
+        if rc != 0:
+            raise RuntimeError(f"decode step failed, rc={rc}")
+
+    def step_two_calls(i: int) -> None:
         rc = apply_mask(*mask_args[i % N_LOGIT_BUFFERS])
         rc |= map_to_rep(*map_args)
         if rc != 0:
@@ -417,6 +444,15 @@ def main() -> int:
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = wall_ms / args.steps
+    # the same step as two calls (cfgzip_apply_mask, then cfgzip_map_to_rep): context
+    for i in range(args.warmup):
+        step_two_calls(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step_two_calls(i)
+    torch.cuda.synchronize()
+    ms_per_step_two_calls = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # dominant kernel alone, HIP events on its stream
     def mask_only():
@@ -572,11 +608,12 @@ def main() -> int:
                                % (args.p_allowed, N_LOGIT_BUFFERS),
                    "B": B, "V": V, "C": C, "bytes_per_step": nbytes["step"]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MASK_KERNEL_TRAFFIC_BYTES,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": mask_kernel_traffic_bytes(),
                      "kernel": "mask_kernel<bf16, class bits, token bits out, 16-byte accesses>",
                      "bytes_per_launch": nbytes["mask_kernel"],
                      "us_per_launch": round(mask_ms * 1e3, 3),
                      "us_per_launch_cache_resident": round(mask_cached_ms * 1e3, 3)},
+        "ms_per_step_two_calls": round(ms_per_step_two_calls, 6),
         "class_build": class_build,
         "engine": engine,
     }

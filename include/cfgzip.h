@@ -198,6 +198,21 @@ int cfgzip_map_to_rep(const int32_t *tok, int32_t B,
                       int32_t *out, void *stream);
 
 /*
+ * One decode step of the per-step path in a single launch (paper Section 3.1 "Inference",
+ * Figure 1, both halves): cfgzip_apply_mask with CFGZIP_BITS_CLASS on `logits`, and
+ * cfgzip_map_to_rep on the tokens sampled in the step before,
+ *     rep_out[b] = rep_of_class[class_of_token[tok[b]]]   (-1 when out of range).
+ * The two are independent (the mask does not depend on `tok`); one workgroup of the masking
+ * kernel does the B look-ups once its own rows are done.  Arguments as for the two calls;
+ * tok_bits_out may be NULL.
+ */
+int cfgzip_decode_step(void *logits, int32_t dtype, int32_t B, int32_t V, int64_t row_stride,
+                       const int32_t *cls_bits, const int32_t *class_of_token, int32_t C,
+                       int32_t *tok_bits_out,
+                       const int32_t *tok, const int32_t *rep_of_class, int32_t *rep_out,
+                       void *stream);
+
+/*
  * Engine side for grammars given as a deterministic byte automaton.  The paper's engine works
  * on the vocabulary E of class representatives (Section 3.1 "Inference"); for a byte
  * automaton with accepting states that engine is a table look-up, and these three calls are

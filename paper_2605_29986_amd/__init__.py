@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     cfgzip_apply_mask,
     cfgzip_build_classes,
     cfgzip_class_masks,
+    cfgzip_decode_step,
     cfgzip_displacements,
     cfgzip_engine_step,
     cfgzip_expand_mask,

@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_apply_mask.argtypes = [vp, i32, i32, i32, i64, vp, i32, vp, i32, vp, vp]
     lib.cfgzip_map_to_rep.restype = ctypes.c_int
     lib.cfgzip_map_to_rep.argtypes = [vp, i32, vp, i32, vp, i32, vp, vp]
+    lib.cfgzip_decode_step.restype = ctypes.c_int
+    lib.cfgzip_decode_step.argtypes = [vp, i32, i32, i32, i64, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.cfgzip_state_masks.restype = ctypes.c_int
     lib.cfgzip_state_masks.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.cfgzip_class_masks.restype = ctypes.c_int
@@ -266,6 +268,40 @@ def cfgzip_map_to_rep(tok: torch.Tensor, class_of_token: torch.Tensor, rep_of_cl
                                rep_of_class.numel(), _dev(out, torch.int32, "out"), _stream(stream))
     _check("cfgzip_map_to_rep", rc)
     return out
+
+
+def cfgzip_decode_step(logits: torch.Tensor, cls_bits: torch.Tensor, class_of_token: torch.Tensor,
+                       C: int, tok: torch.Tensor, rep_of_class: torch.Tensor, *,
+                       tok_bits_out: Optional[torch.Tensor] = None,
+                       rep_out: Optional[torch.Tensor] = None, V: Optional[int] = None,
+                       stream=None) -> torch.Tensor:
+    """Fused expand + apply on `logits` (in place) and the map of `tok` to representatives, in
+    one launch.  Returns rep_out (int32 [B])."""
+    lib = load_library()
+    if logits.dim() != 2 or logits.stride(1) != 1 or not logits.is_cuda:
+        raise ValueError("logits must be a 2-D GPU tensor with unit column stride")
+    if logits.dtype == torch.float32:
+        dt = CFGZIP_DTYPE_F32
+    elif logits.dtype == torch.bfloat16:
+        dt = CFGZIP_DTYPE_BF16
+    else:
+        raise TypeError("logits must be float32 or bfloat16")
+    B = logits.shape[0]
+    V = logits.shape[1] if V is None else int(V)
+    if cls_bits.shape[0] != B or cls_bits.shape[1] != words_for(C) or tok.numel() != B:
+        raise ValueError("cls_bits must be [B, ceil(C/32)] and tok [B]")
+    if rep_of_class.numel() != C or class_of_token.numel() != V:
+        raise ValueError("class_of_token must be [V] and rep_of_class [C]")
+    if rep_out is None:
+        rep_out = torch.empty((B,), dtype=torch.int32, device=tok.device)
+    rc = lib.cfgzip_decode_step(
+        logits.data_ptr(), dt, B, V, int(logits.stride(0)), _dev(cls_bits, torch.int32, "cls_bits"),
+        _dev(class_of_token, torch.int32, "class_of_token"), int(C),
+        _dev(tok_bits_out, torch.int32, "tok_bits_out") if tok_bits_out is not None else None,
+        _dev(tok, torch.int32, "tok"), _dev(rep_of_class, torch.int32, "rep_of_class"),
+        _dev(rep_out, torch.int32, "rep_out"), _stream(stream))
+    _check("cfgzip_decode_step", rc)
+    return rep_out
 
 
 def cfgzip_state_masks(sig_rep: torch.Tensor, live: torch.Tensor, *,

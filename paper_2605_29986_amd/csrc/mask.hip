@@ -57,6 +57,12 @@ struct MaskArgs {
     const int32_t *states_in;   // [B]
     int32_t *states_out;        // [B]
     int32_t S, C;
+    // decode step (null otherwise): the first workgroup also maps the sampled tokens to their
+    // representatives once its own rows are streamed
+    const int32_t *map_tok;       // [B]
+    const int32_t *rep_of_class;  // [map_C]
+    int32_t *map_out;             // [B]
+    int32_t map_C;
 };
 
 __device__ __forceinline__ uint32_t select_bf16_pair(uint32_t x, uint32_t two_bits) {
@@ -70,8 +76,7 @@ __device__ __forceinline__ uint32_t select_bf16_pair(uint32_t x, uint32_t two_bi
 // WRITE_BITS: also store the token-level mask.
 // VEC: logits rows and class_of_token allow 16-byte accesses at column multiples of 8.
 template <int LOGITS, bool FROM_CLASS, bool WRITE_BITS, bool VEC>
-__global__ __launch_bounds__(kThreads) void mask_kernel(MaskArgs a) {
-    extern __shared__ uint32_t cls_lds[];  // [rows_per_block][Wc] when FROM_CLASS
+__device__ __forceinline__ void mask_tile(const MaskArgs &a, uint32_t *cls_lds) {
 
     const int ct = blockIdx.x % a.col_tiles;
     const int rc = blockIdx.x / a.col_tiles;
@@ -242,17 +247,31 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(MaskArgs a) {
     }
 }
 
+// out = rep_of_class[class_of_token[t]], or -1 when the token id or its class id is out of range
+__device__ __forceinline__ int32_t representative_of(int32_t t, const int32_t *class_of_token,
+                                                     int32_t V, const int32_t *rep_of_class,
+                                                     int32_t C) {
+    if (t < 0 || t >= V) return -1;
+    const int32_t k = class_of_token[t];
+    return (k >= 0 && k < C) ? rep_of_class[k] : -1;
+}
+
+template <int LOGITS, bool FROM_CLASS, bool WRITE_BITS, bool VEC>
+__global__ __launch_bounds__(kThreads) void mask_kernel(MaskArgs a) {
+    extern __shared__ uint32_t cls_lds[];  // [rows_per_block][Wc] when FROM_CLASS
+    mask_tile<LOGITS, FROM_CLASS, WRITE_BITS, VEC>(a, cls_lds);
+    // The first workgroup is the first to be scheduled and to finish its rows; the B dependent
+    // look-ups then overlap with the streaming of all the others.
+    if (a.map_tok && blockIdx.x == 0)
+        for (int b = threadIdx.x; b < a.B; b += kThreads)
+            a.map_out[b] = representative_of(a.map_tok[b], a.class_of_token, a.V, a.rep_of_class, a.map_C);
+}
+
 __global__ void map_to_rep_kernel(const int32_t *tok, int32_t B, const int32_t *class_of_token,
                                   int32_t V, const int32_t *rep_of_class, int32_t C, int32_t *out) {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    int32_t t = tok[b];
-    int32_t res = -1;
-    if (t >= 0 && t < V) {
-        int32_t k = class_of_token[t];
-        if (k >= 0 && k < C) res = rep_of_class[k];
-    }
-    out[b] = res;
+    out[b] = representative_of(tok[b], class_of_token, V, rep_of_class, C);
 }
 
 constexpr size_t kMaxLds = 160 * 1024;
@@ -290,11 +309,23 @@ struct EngineStep {
     int32_t *states_out;
     int32_t S;
 };
+struct MapStep {
+    const int32_t *tok;
+    const int32_t *rep_of_class;
+    int32_t *out;
+};
 
 int run_mask(void *logits, int logits_kind, int32_t B, int32_t V, int64_t row_stride,
              const int32_t *bits, bool from_class, const int32_t *class_of_token, int32_t C,
-             int32_t *tok_bits_out, hipStream_t stream, const EngineStep *engine = nullptr) {
+             int32_t *tok_bits_out, hipStream_t stream, const EngineStep *engine = nullptr,
+             const MapStep *map = nullptr) {
     MaskArgs a{};
+    if (map) {
+        a.map_tok = map->tok;
+        a.rep_of_class = map->rep_of_class;
+        a.map_out = map->out;
+        a.map_C = C;
+    }
     if (engine) {
         a.state_mask = engine->state_mask;
         a.sig_rep = engine->sig_rep;
@@ -408,6 +439,26 @@ extern "C" int cfgzip_engine_step(void *logits, int32_t dtype, int32_t B, int32_
     return run_mask(logits, dtype == CFGZIP_DTYPE_BF16 ? LOGITS_BF16 : LOGITS_F32, B, V, row_stride,
                     state_mask, true, class_of_token, C, tok_bits_out,
                     static_cast<hipStream_t>(stream), &e);
+}
+
+extern "C" int cfgzip_decode_step(void *logits, int32_t dtype, int32_t B, int32_t V,
+                                  int64_t row_stride, const int32_t *cls_bits,
+                                  const int32_t *class_of_token, int32_t C, int32_t *tok_bits_out,
+                                  const int32_t *tok, const int32_t *rep_of_class, int32_t *rep_out,
+                                  void *stream) {
+    if (!logits || !cls_bits || !class_of_token || !tok || !rep_of_class || !rep_out)
+        return CFGZIP_E_INVALID;
+    if (B <= 0 || V <= 0 || C <= 0 || row_stride < V) return CFGZIP_E_INVALID;
+    if (dtype != CFGZIP_DTYPE_F32 && dtype != CFGZIP_DTYPE_BF16) return CFGZIP_E_INVALID;
+    const size_t esz = dtype == CFGZIP_DTYPE_BF16 ? 2 : 4;
+    if (!aligned_to(logits, esz) || !aligned_to(cls_bits, 4) || !aligned_to(class_of_token, 4) ||
+        !aligned_to(tok_bits_out, 4) || !aligned_to(tok, 4) || !aligned_to(rep_of_class, 4) ||
+        !aligned_to(rep_out, 4))
+        return CFGZIP_E_INVALID;
+    MapStep m{tok, rep_of_class, rep_out};
+    return run_mask(logits, dtype == CFGZIP_DTYPE_BF16 ? LOGITS_BF16 : LOGITS_F32, B, V, row_stride,
+                    cls_bits, true, class_of_token, C, tok_bits_out, static_cast<hipStream_t>(stream),
+                    nullptr, &m);
 }
 
 extern "C" int cfgzip_map_to_rep(const int32_t *tok, int32_t B, const int32_t *class_of_token,

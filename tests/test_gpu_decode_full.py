@@ -1,7 +1,7 @@
 """GPU parity at the benchmark's full decode-step size (batch 256, V = 128,256,
 C = 8,000, bf16 logits), in the launch configuration bench.py times: the fused
-expand + apply with the token mask as by-product, then the map to
-representatives.  The class map comes from the config-3 class build (HIP and
+expand + apply with the token mask as by-product and the map to
+representatives, as two calls and as the single-launch decode step.  The class map comes from the config-3 class build (HIP and
 oracle builds are compared first), resized to exactly 8,000 classes."""
 
 import numpy as np
@@ -45,6 +45,14 @@ def test_config5_full_size():
     assert (tbits.cpu().numpy() == want_bits).all()
     assert (logits_bits(lg) == want_logits).all()
     assert (rep.cpu().numpy() == want_rep).all()
+    # the whole step in one launch (what bench.py times): mask and map together
+    lg1 = logits_dev(d["logits"], "bf16")
+    tbits1 = torch.full((B, words_for(V)), -1, dtype=torch.int32, device="cuda")
+    rep1 = lib.cfgzip_decode_step(lg1, cls_d, c_d, C, dev(d["tok"]), r_d, tok_bits_out=tbits1)
+    torch.cuda.synchronize()
+    assert (tbits1.cpu().numpy() == want_bits).all()
+    assert (logits_bits(lg1) == want_logits).all()
+    assert (rep1.cpu().numpy() == want_rep).all()
     # the unfused pair gives the same result
     lg2 = logits_dev(d["logits"], "bf16")
     tb2 = lib.cfgzip_expand_mask(cls_d, C, c_d)

@@ -165,3 +165,34 @@ def test_invalid_arguments_are_rejected(lib):
     assert raw.cfgzip_expand_mask(None, 1, 1, c.data_ptr(), 64, bits.data_ptr(), None) == -1
     assert raw.cfgzip_map_to_rep(c.data_ptr(), 0, c.data_ptr(), 64, c.data_ptr(), 1,
                                  c.data_ptr(), None) == -1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decode_step_in_one_launch(lib, dtype):
+    """cfgzip_decode_step = cfgzip_apply_mask (class bits) + cfgzip_map_to_rep, with and without
+    the token mask, odd sizes, token ids out of range, more sequences than a workgroup has
+    threads."""
+    from gpu_util import dev, logits_dev, logits_bits
+    for case, (B, V, C) in enumerate([(1, 1, 1), (3, 77, 5), (300, 2049, 300), (17, 70001, 4099)]):
+        print(f"case decode step B={B} V={V} C={C} {dtype}", flush=True)
+        rng = np.random.default_rng(900 + case)
+        c = _class_map(rng, V, C)
+        r = rng.integers(0, V, size=C).astype(np.int32)
+        d = si.make_decode_inputs(77 + case, B, V, C, dtype, sigma=2.0)
+        tok = d["tok"].copy()
+        tok[::5] = [-1, V, V + 7, -2 ** 31, 2 ** 31 - 1][case % 5]
+        want_bits = oracle.expand_mask(d["cls_bits"], c, C)
+        logits = d["logits"].view(np.uint32) if dtype == "f32" else d["logits"]
+        want_logits = oracle.apply_mask(logits, want_bits, dtype)
+        want_rep = oracle.map_to_rep(tok, c, r)
+        assert (want_rep[::5] == -1).all()
+        for with_bits in (True, False):
+            lg = logits_dev(logits, dtype)
+            tbits = torch.full((B, words_for(V)), -1, dtype=torch.int32, device="cuda") if with_bits else None
+            rep = lib.cfgzip_decode_step(lg, dev(d["cls_bits"]), dev(c), C, dev(tok), dev(r),
+                                         tok_bits_out=tbits)
+            torch.cuda.synchronize()
+            assert (logits_bits(lg) == want_logits).all()
+            if with_bits:
+                assert (tbits.cpu().numpy() == want_bits).all()
+            assert (rep.cpu().numpy() == want_rep).all()
