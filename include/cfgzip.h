@@ -62,6 +62,7 @@ extern "C" {
 #define CFGZIP_E_WORKSPACE (-2) /* ws == NULL or ws_bytes smaller than the query says */
 #define CFGZIP_E_HIP (-3)       /* a HIP call failed; see cfgzip_last_hip_error() */
 #define CFGZIP_E_COLLISION (-4) /* hash collisions could not be resolved within the round limit */
+#define CFGZIP_E_TOO_LARGE (-5) /* a size beyond what an entry point with built-in scratch memory takes */
 
 #define CFGZIP_DTYPE_F32 0
 #define CFGZIP_DTYPE_BF16 1
@@ -104,6 +105,25 @@ int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t 
                       const uint16_t *table, int32_t S,
                       uint16_t *sig_out, uint64_t *hash_out, uint64_t hash_seed,
                       void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * cfgzip_signatures for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and results as cfgzip_signatures without `ws`; the tables the
+ * kernels need live in a device array that is part of the loaded library
+ * (about 14.2 MiB per GPU, held until the process ends), so the call allocates nothing.
+ *   S   1 .. CFGZIP_STATIC_MAX_STATES; a larger automaton is refused with CFGZIP_E_TOO_LARGE
+ *       (nothing enqueued)
+ * The compressed signatures are not kept: cfgzip_build_classes after this call is given
+ * signatures_ws = NULL.  All calls on one GPU share that GPU's array: two calls that overlap
+ * in time on the same GPU (different streams or host threads) race; calls on one stream, or
+ * ordered by events, are fine.  Nothing in the array needs clearing between calls.
+ */
+#define CFGZIP_STATIC_MAX_STATES 4096
+int cfgzip_signatures_static(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                             const uint16_t *table, int32_t S,
+                             uint16_t *sig_out, uint64_t *hash_out, uint64_t hash_seed,
+                             void *stream);
 
 /*
  * Equivalence classes, class ids and representatives (paper Section 3.1

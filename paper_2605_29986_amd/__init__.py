@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     cfgzip_nfa_signatures,
     cfgzip_representative_vocabulary,
     cfgzip_signatures,
+    cfgzip_signatures_static,
     cfgzip_stack_adjacency,
     cfgzip_state_masks,
     cfgzip_version,

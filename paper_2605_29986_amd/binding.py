@@ -28,6 +28,7 @@ _ERRORS = {
     -2: "CFGZIP_E_WORKSPACE (workspace missing, misaligned or too small)",
     -3: "CFGZIP_E_HIP (a HIP call failed)",
     -4: "CFGZIP_E_COLLISION (hash collisions not resolved)",
+    -5: "CFGZIP_E_TOO_LARGE (beyond what an entry point with built-in scratch memory takes)",
 }
 
 
@@ -61,6 +62,8 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_signatures_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_signatures.restype = ctypes.c_int
     lib.cfgzip_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp, sz, vp]
+    lib.cfgzip_signatures_static.restype = ctypes.c_int
+    lib.cfgzip_signatures_static.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp]
     lib.cfgzip_build_classes_workspace_bytes.restype = sz
     lib.cfgzip_build_classes_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_build_classes.restype = ctypes.c_int
@@ -158,6 +161,27 @@ def cfgzip_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: tor
         workspace.data_ptr(), workspace.numel(), _stream(stream))
     _check("cfgzip_signatures", rc)
     return sig_out, hash_out
+
+
+STATIC_MAX_STATES = 4096
+
+
+def cfgzip_signatures_static(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: torch.Tensor,
+                             sig_out: Optional[torch.Tensor], hash_out: Optional[torch.Tensor], *,
+                             hash_seed: int = DEFAULT_HASH_SEED, stream=None) -> None:
+    """cfgzip_signatures into caller-provided outputs, with the tables in memory that belongs to
+    the library: nothing is allocated (at most STATIC_MAX_STATES states)."""
+    lib = load_library()
+    V = tok_off.numel() - 1
+    S = table.shape[0]
+    rc = lib.cfgzip_signatures_static(
+        _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
+        _dev(tok_off, torch.int64, "tok_off"), V,
+        _dev(table, torch.uint16, "table"), S,
+        _dev(sig_out, torch.uint16, "sig_out") if sig_out is not None else None,
+        _dev(hash_out, torch.int64, "hash_out") if hash_out is not None else None,
+        ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF), _stream(stream))
+    _check("cfgzip_signatures_static", rc)
 
 
 def cfgzip_build_classes(tok_bytes: torch.Tensor, tok_off: torch.Tensor,

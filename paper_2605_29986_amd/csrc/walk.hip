@@ -12,6 +12,7 @@
 // L2-resident copy in the workspace.
 
 #include <algorithm>
+#include <mutex>
 
 #include "common.hpp"
 #include "walk_device.hpp"
@@ -303,19 +304,13 @@ extern "C" size_t cfgzip_signatures_workspace_bytes(int32_t V, int32_t S) {
     return sig_workspace_bytes(V, S);
 }
 
-extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
-                                 const uint16_t *table, int32_t S, uint16_t *sig_out,
-                                 uint64_t *hash_out, uint64_t hash_seed, void *ws, size_t ws_bytes,
-                                 void *stream_) {
-    if (!tok_off || !table || V <= 0 || S <= 0 || S > 65536) return CFGZIP_E_INVALID;
-    if (!sig_out && !hash_out) return CFGZIP_E_INVALID;
-    if (!aligned_to(tok_off, 8) || !aligned_to(table, 2) || !aligned_to(sig_out, 2) ||
-        !aligned_to(hash_out, 8))
-        return CFGZIP_E_INVALID;
-    if (!ws || ws_bytes < sig_workspace_bytes(V, S) || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
-    // tok_bytes may be null only if every token is empty; the kernels never read it then.
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
+namespace {
 
+// Shared by both entry points: `ws` holds at least sig_workspace_bytes(store_V, S) bytes;
+// store_V = V keeps the walk vectors for the class builder, store_V = 0 keeps nothing.
+int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, const uint16_t *table,
+                   int32_t S, uint16_t *sig_out, uint64_t *hash_out, uint64_t hash_seed, void *ws,
+                   int32_t store_V, hipStream_t stream) {
     WalkArgs a{};
     a.tok_bytes = tok_bytes;
     a.tok_off = tok_off;
@@ -323,7 +318,7 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
     a.S = S;
     a.sig_out = sig_out;
     a.hash_out = hash_out;
-    CFGZIP_TRY(prepare_tables(table, S, hash_seed, hash_out != nullptr, V, ws, &a.T, &a.store, stream));
+    CFGZIP_TRY(prepare_tables(table, S, hash_seed, hash_out != nullptr, store_V, ws, &a.T, &a.store, stream));
 
     int n_cu = 256;
     CFGZIP_TRY(device_cu_count(&n_cu));
@@ -355,4 +350,72 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), dyn, stream, a);
     }
     return check_launch();
+}
+
+int check_signature_args(const int64_t *tok_off, int32_t V, const uint16_t *table, int32_t S,
+                         const uint16_t *sig_out, const uint64_t *hash_out) {
+    if (!tok_off || !table || V <= 0 || S <= 0 || S > 65536) return CFGZIP_E_INVALID;
+    if (!sig_out && !hash_out) return CFGZIP_E_INVALID;
+    if (!aligned_to(tok_off, 8) || !aligned_to(table, 2) || !aligned_to(sig_out, 2) ||
+        !aligned_to(hash_out, 8))
+        return CFGZIP_E_INVALID;
+    return CFGZIP_OK;
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------
+// Its tables live in device memory that belongs to the loaded library itself.  Each GPU has its
+// own copy of the array at its own address; host code never uses the array's name as an
+// address, only the pointer hipGetSymbolAddress returns for the current device.
+constexpr int32_t kStaticMaxStates = CFGZIP_STATIC_MAX_STATES;
+constexpr size_t static_scratch_bytes(size_t S) {
+    // mirrors carve_sig_ws(ws, 0, S): header, Tt, nimg, img, idx, wsum, each rounded up to 256 bytes
+    return 256 + ((256 * S + kTablePad) * 2 + 255) / 256 * 256 + (kImageRows * 4 + 255) / 256 * 256 +
+           2 * ((kImageRows * S * 2 + 255) / 256 * 256) + (kImageRows * S * 8 + 255) / 256 * 256;
+}
+constexpr size_t kStaticScratchBytes = static_scratch_bytes(kStaticMaxStates);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // per device, filled at the first call on that device
+
+int static_scratch_for_current_device(void **out) {
+    int dev = 0;
+    CFGZIP_TRY(check_hip(hipGetDevice(&dev)));
+    if (dev < 0 || dev >= kMaxDevices) return CFGZIP_E_INVALID;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        CFGZIP_TRY(check_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))));
+        if (!ptr) return CFGZIP_E_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CFGZIP_OK;
+}
+
+}  // namespace
+
+extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                                 const uint16_t *table, int32_t S, uint16_t *sig_out,
+                                 uint64_t *hash_out, uint64_t hash_seed, void *ws, size_t ws_bytes,
+                                 void *stream_) {
+    CFGZIP_TRY(check_signature_args(tok_off, V, table, S, sig_out, hash_out));
+    if (!ws || ws_bytes < sig_workspace_bytes(V, S) || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
+    // tok_bytes may be null only if every token is empty; the kernels never read it then.
+    return run_signatures(tok_bytes, tok_off, V, table, S, sig_out, hash_out, hash_seed, ws, V,
+                          static_cast<hipStream_t>(stream_));
+}
+
+extern "C" int cfgzip_signatures_static(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                                        const uint16_t *table, int32_t S, uint16_t *sig_out,
+                                        uint64_t *hash_out, uint64_t hash_seed, void *stream_) {
+    CFGZIP_TRY(check_signature_args(tok_off, V, table, S, sig_out, hash_out));
+    if (S > kStaticMaxStates || sig_workspace_bytes(0, S) > kStaticScratchBytes) return CFGZIP_E_TOO_LARGE;
+    void *ws = nullptr;
+    CFGZIP_TRY(static_scratch_for_current_device(&ws));
+    // every table entry the kernels read is written by this call's own table kernels first, so
+    // what the previous call left in the array does not matter
+    return run_signatures(tok_bytes, tok_off, V, table, S, sig_out, hash_out, hash_seed, ws, 0,
+                          static_cast<hipStream_t>(stream_));
 }

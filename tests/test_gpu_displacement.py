@@ -58,6 +58,8 @@ def _check_rows(lib, g: Grammar, vocab, expect_overflow=None, row_len=256):
     want_status = np.zeros(vocab.V, np.int32)
     known = {}   # distinct byte string -> (set by Algorithm 1 or None when a limit breaks, its encoding)
     for t, tok in enumerate(toks):
+        if t and t % 25000 == 0:
+            print(f"  {t} of {vocab.V} tokens compared", flush=True)
         if tok not in known:
             pairs = D.displacement_within_limits(tuple(tok), prods, adj, index)
             if pairs is not None:   # within the limits the library must find Algorithm 1's set
