@@ -1,26 +1,30 @@
 // cfgzip_build_classes: group tokens with equal signature, number the classes
 // and pick representatives (paper Section 3.1 "Pre-Computation").
 //
-// Pipeline (all on the device):
-//   1. stable LSD radix sort of the key (low 32 or 40 bits of the hash, first
-//      byte of the token) with the token id as value, 8 bits per pass, two
-//      kernels per pass: per-tile digit counts, then a scatter that ranks its
-//      tile and adds over the counts of the earlier tiles itself;
-//   2. equal-hash segments; inside a segment tokens with the same first byte are
-//      neighbours.  Every member is compared with its left neighbour (a chain:
-//      equality is transitive).  Three sources, in order of preference: the walk
-//      vectors a preceding cfgzip_signatures call left in its workspace (compared
-//      on the short vector w when both tokens share the first byte, through the
-//      index tables otherwise - walk_device.hpp); stored signature rows; or, with
-//      neither, both tokens are re-walked with the image walk;
-//   3. if no link differs (no hash collision - the overwhelmingly common case),
-//      the segments are the classes.  Otherwise every differing member starts a
-//      new chain and the chain starts of a segment are matched against each
-//      other in rounds (the first unmatched one becomes a class, the rest are
-//      compared with it) - exact for any hash that is a function of the signature;
-//   4. class id = rank of the class's smallest token id among all classes, by a
-//      prefix sum over token ids;
-//   5. representative = min over members of (byte length, token id).
+// Pipeline (all on the device, eight launches when no hash collides):
+//   1. keys: (low 32 or 40 bits of the hash, first byte of the token), and the digit counts of
+//      the first sort pass per tile;
+//   2. stable LSD radix sort of the keys with the token id as value, 10 bits per pass, one
+//      launch per pass: a workgroup sums the counts of the earlier tiles itself, ranks its
+//      tile by wave-level match-by-ballot, writes, and counts the next pass's digits per
+//      destination tile on the way;
+//   3. links: equal-hash segments; inside a segment tokens with the same first byte are
+//      neighbours.  Every member is compared with its left neighbour (a chain: equality is
+//      transitive).  Three sources, in order of preference: the walk vectors a preceding
+//      cfgzip_signatures call left in its workspace (compared on the short vector w when both
+//      tokens share the first byte, through the index tables otherwise - walk_device.hpp);
+//      stored signature rows; or, with neither, both tokens are re-walked with the image walk
+//      (a kernel of its own).  The same launch reduces, per segment, the smallest token id and
+//      the smallest (byte length, token id);
+//   4. if no link differs (no hash collision - the overwhelmingly common case), the segments
+//      are the classes.  Otherwise every differing member starts a new chain and the chain
+//      starts of a segment are matched against each other in rounds (the first unmatched one
+//      becomes a class, the rest are compared with it) - exact for any hash that is a function
+//      of the signature;
+//   5. class id = rank of the class's smallest token id among all classes: the smallest ids
+//      are marked in a bit vector over token ids, and every workgroup of the last kernel
+//      ranks by prefix popcounts of that vector held in LDS;
+//   6. representative = min over members of (byte length, token id).
 // The host waits once, for the class count and the number of differing links.
 
 #include <algorithm>
@@ -31,24 +35,37 @@
 namespace cfgzip {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 256;             // link, minima and marking kernels: one position per thread
 constexpr int kItems = 8;
-constexpr int kTile = kThreads * kItems;  // keys per workgroup in sort and scan kernels
-constexpr int kRadixBits = 8;
+constexpr int kTile = kThreads * kItems;  // items per workgroup in the scan kernels
+constexpr int kSortThreads = 1024;
+constexpr int kSortItems = 8;
+constexpr int kSortTile = kSortThreads * kSortItems;  // keys per workgroup in the sort
+constexpr int kRadixBits = 10;
 constexpr int kBins = 1 << kRadixBits;
+static_assert(kSortThreads == kBins, "one thread per bin in the sort kernels");
+constexpr int kAggBits = 11;
+constexpr int kAggSlots = 1 << kAggBits;
+constexpr uint32_t kAggEmpty = 0xFFFFFFFFu;
+constexpr int kAssignThreads = 512;
+constexpr int kAssignItems = 4;
+constexpr int kAssignTile = kAssignThreads * kAssignItems;
+// token-id bit vector and its word prefix sums fit in LDS up to this many words (V <= 262,144)
+constexpr int kRankLdsWords = 8192;
 // Hash bits that take part in the sort, above the 8 bits of the first byte.  Two classes that
 // agree in these bits only cost a pass through the collision rounds (C classes: about
-// C^2 / 2^(bits+1) such pairs), so small vocabularies sort 32 bits (5 passes) and large ones 40.
+// C^2 / 2^(bits+1) such pairs), so small vocabularies sort 32 bits (4 passes) and large ones 40.
 constexpr int32_t kLargeVocabulary = 1 << 18;
 inline int hash_bits_for(int32_t V) { return V > kLargeVocabulary ? 40 : 32; }
-static_assert(kThreads == kBins, "one thread per bin in the sort kernels");
 
 struct Counters {
     int32_t unresolved;
     int32_t num_classes;
-    int32_t store_unusable;  // the walk store did not match this call or had overflowed
-    int32_t pad[5];
+    int32_t store_state;  // of the walk store handed in: 0 usable, 1 not this call's, 2 overflowed
+    int32_t other_rows;   // links between tokens of different image rows, listed for the kernel after
+    int32_t pad[4];
 };
+constexpr int kStoreForeign = 1, kStoreOverflowed = 2;
 
 // ---------------------------------------------------------------- radix sort
 
@@ -63,59 +80,103 @@ __device__ __forceinline__ uint64_t sort_key(const uint64_t *__restrict__ hash,
     return ((hash[t] & hash_mask) << 8) | fb;
 }
 
-// Digit counts of one pass per tile: hist[tile][digit].  The first pass forms its keys from
-// the hash and the first bytes; later passes read the keys the previous pass wrote.
-template <bool FIRST>
-__global__ __launch_bounds__(kThreads) void radix_hist_kernel(
-    const uint64_t *__restrict__ hash, const int64_t *__restrict__ tok_off,
-    const uint8_t *__restrict__ tok_bytes, const uint64_t *__restrict__ keys, int n, int shift,
-    uint64_t hash_mask, uint32_t *hist) {
-    __shared__ uint32_t bins[kBins];
-    bins[threadIdx.x] = 0;
-    __syncthreads();
-    const int base = blockIdx.x * kTile;
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        const int idx = base + j * kThreads + threadIdx.x;
-        if (idx < n) {
-            const uint64_t key = FIRST ? sort_key(hash, tok_off, tok_bytes, idx, hash_mask) : keys[idx];
-            atomicAdd(&bins[(uint32_t)(key >> shift) & (kBins - 1)], 1u);
-        }
-    }
-    __syncthreads();
-    hist[(size_t)blockIdx.x * kBins + threadIdx.x] = bins[threadIdx.x];
-}
-
-struct ScatterArgs {
-    const uint64_t *hash;  // first pass: keys are formed from the hash and the first bytes
+struct KeysArgs {
+    const uint64_t *hash;
     const int64_t *tok_off;
     const uint8_t *tok_bytes;
-    const uint64_t *keys_in;  // later passes
-    const int32_t *vals_in;
+    uint64_t *keys_out;
+    uint32_t *hist;  // [passes][nb][kBins]
+    uint64_t hash_mask;
+    int n, nb, passes;
+    // what the later kernels accumulate into, reset here
+    int32_t *min_id;
+    uint64_t *rep_key;
+    uint32_t *head_bits;
+    int n_words;
+    Counters *ctr;
+};
+
+// Forms the keys, counts the first pass's digits per tile, clears the later passes' counts and
+// everything the numbering accumulates into.
+__global__ __launch_bounds__(kSortThreads) void keys_kernel(KeysArgs a) {
+    __shared__ uint32_t bins[kBins];
+    bins[threadIdx.x] = 0;
+    for (int p = 1; p < a.passes; ++p)
+        a.hist[((size_t)p * a.nb + blockIdx.x) * kBins + threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        a.ctr->unresolved = 0;
+        a.ctr->num_classes = 0;
+        a.ctr->store_state = 0;
+        a.ctr->other_rows = 0;
+    }
+    __syncthreads();
+    const int base = blockIdx.x * kSortTile;
+#pragma unroll
+    for (int j = 0; j < kSortItems; ++j) {
+        const int idx = base + j * kSortThreads + threadIdx.x;
+        if (idx < a.n) {
+            const uint64_t key = sort_key(a.hash, a.tok_off, a.tok_bytes, idx, a.hash_mask);
+            a.keys_out[idx] = key;
+            atomicAdd(&bins[(uint32_t)key & (kBins - 1)], 1u);
+            a.min_id[idx] = 0x7FFFFFFF;
+            a.rep_key[idx] = ~0ull;
+        }
+    }
+    if (threadIdx.x < kSortTile / 32) {
+        const int w = base / 32 + threadIdx.x;
+        if (w < a.n_words) a.head_bits[w] = 0;
+    }
+    __syncthreads();
+    a.hist[(size_t)blockIdx.x * kBins + threadIdx.x] = bins[threadIdx.x];
+}
+
+struct PassArgs {
+    const uint64_t *keys_in;
+    const int32_t *vals_in;  // first pass: the value of position i is i
     uint64_t *keys_out;
     int32_t *vals_out;
-    const uint32_t *hist;  // [nb][256] digit counts of this pass per input tile
-    uint64_t hash_mask;
+    const uint32_t *hist;  // [nb][kBins] digit counts of this pass per input tile
+    uint32_t *hist_next;   // the same for the next pass, counted here; null in the last pass
     int n, nb, shift;
 };
 
 // One stable pass.  A wave owns a contiguous chunk of the tile and visits it 64 keys at a
 // time, so (wave, visit, lane) order is index order.
 template <bool FIRST>
-__global__ __launch_bounds__(kThreads) void radix_scatter_kernel(ScatterArgs a) {
-    __shared__ uint32_t wave_count[kThreads / 64][kBins];
-    __shared__ uint32_t wave_tot[kThreads / 64];
+__global__ __launch_bounds__(kSortThreads) void radix_pass_kernel(PassArgs a) {
+    constexpr int kWaves = kSortThreads / 64;
+    __shared__ uint16_t wave_count[kWaves][kBins];  // a wave holds 512 keys: counts fit 16 bits
+    __shared__ uint32_t bin_base[kBins];
+    __shared__ uint32_t wave_tot[kWaves];
+    // counts of the next pass's (destination tile, digit) pairs, gathered per workgroup before
+    // they go to memory: a class with many members puts thousands of keys on one counter
+    __shared__ uint32_t agg_tag[kAggSlots];
+    __shared__ uint32_t agg_cnt[kAggSlots];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int i = threadIdx.x; i < (kThreads / 64) * kBins; i += kThreads)
-        (&wave_count[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < kWaves * kBins / 2; i += kSortThreads)
+        reinterpret_cast<uint32_t *>(&wave_count[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < kAggSlots; i += kSortThreads) {
+        agg_tag[i] = kAggEmpty;
+        agg_cnt[i] = 0;
+    }
+
+    // the keys first: their loads overlap the count sums below
+    const int chunk = blockIdx.x * kSortTile + wave * (64 * kSortItems);
+    uint64_t key[kSortItems];
+    int32_t val[kSortItems];
+#pragma unroll
+    for (int j = 0; j < kSortItems; ++j) {
+        const int idx = chunk + j * 64 + lane;
+        key[j] = idx < a.n ? a.keys_in[idx] : 0ull;
+        val[j] = FIRST ? idx : (idx < a.n ? a.vals_in[idx] : 0);
+    }
 
     // first output position of this tile's keys with digit d:
     //   keys with a smaller digit anywhere + keys with digit d in earlier tiles
-    uint32_t bin_base;
     {
         const int d = threadIdx.x;
         uint32_t tot = 0, before = 0;
-        constexpr int kAhead = 16;  // independent loads in flight: the loop is latency-bound
+        constexpr int kAhead = 8;  // independent loads in flight: the loop is latency-bound
         for (int t0 = 0; t0 < a.nb; t0 += kAhead) {
             uint32_t c[kAhead];
 #pragma unroll
@@ -132,59 +193,80 @@ __global__ __launch_bounds__(kThreads) void radix_scatter_kernel(ScatterArgs a) 
         __syncthreads();  // also orders the clearing of wave_count before its use
         uint32_t prefix = 0;
         for (int w = 0; w < wave; ++w) prefix += wave_tot[w];
-        bin_base = prefix + (uint32_t)incl - tot + before;
+        bin_base[d] = prefix + (uint32_t)incl - tot + before;
     }
 
-    volatile uint32_t *my_count = wave_count[wave];
-    const int chunk = blockIdx.x * kTile + wave * (64 * kItems);
-    uint64_t key[kItems];
-    uint32_t rank[kItems];
+    volatile uint16_t *my_count = wave_count[wave];
+    uint32_t rank[kSortItems];
+    uint64_t peers[kSortItems];  // lanes of this visit with the same digit
     const uint64_t lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        const int idx = chunk + j * 64 + lane;
-        const bool valid = idx < a.n;
-        key[j] = !valid ? 0ull
-                 : FIRST ? sort_key(a.hash, a.tok_off, a.tok_bytes, idx, a.hash_mask)
-                         : a.keys_in[idx];
+    for (int j = 0; j < kSortItems; ++j) {
+        const bool valid = chunk + j * 64 + lane < a.n;
         const uint32_t d = (uint32_t)(key[j] >> a.shift) & (kBins - 1);
-        uint64_t peers = __ballot(valid);
+        uint64_t p = __ballot(valid);
 #pragma unroll
         for (int bit = 0; bit < kRadixBits; ++bit) {
             const bool one = (d >> bit) & 1u;
             const uint64_t bm = __ballot(one);
-            peers &= one ? bm : ~bm;
+            p &= one ? bm : ~bm;
         }
+        peers[j] = p;
         rank[j] = 0;
         if (valid) {
             const uint32_t before = my_count[d];
-            const uint32_t r = (uint32_t)__popcll(peers & lt_mask);
+            const uint32_t r = (uint32_t)__popcll(p & lt_mask);
             rank[j] = before + r;
-            if (r == 0) my_count[d] = before + (uint32_t)__popcll(peers);
+            if (r == 0) my_count[d] = (uint16_t)(before + (uint32_t)__popcll(p));
         }
     }
     __syncthreads();
     {
         const int d = threadIdx.x;
-        uint32_t run = bin_base;
+        uint32_t run = 0;
 #pragma unroll
-        for (int w = 0; w < kThreads / 64; ++w) {
+        for (int w = 0; w < kWaves; ++w) {
             const uint32_t c = wave_count[w][d];
-            wave_count[w][d] = run;
+            wave_count[w][d] = (uint16_t)run;  // keys of this tile with digit d in earlier waves
             run += c;
         }
     }
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        const int idx = chunk + j * 64 + lane;
-        if (idx < a.n) {
-            const uint32_t d = (uint32_t)(key[j] >> a.shift) & (kBins - 1);
-            const uint32_t pos = wave_count[wave][d] + rank[j];
-            if (pos >= (uint32_t)a.n) continue;  // cannot happen with consistent counts; stay in bounds
+    for (int j = 0; j < kSortItems; ++j) {
+        const bool valid = chunk + j * 64 + lane < a.n;
+        const uint32_t d = (uint32_t)(key[j] >> a.shift) & (kBins - 1);
+        uint32_t pos = valid ? bin_base[d] + wave_count[wave][d] + rank[j] : 0u;
+        const bool ok = valid && pos < (uint32_t)a.n;  // always, with consistent counts; stay in bounds
+        if (ok) {
             a.keys_out[pos] = key[j];
-            a.vals_out[pos] = FIRST ? idx : a.vals_in[idx];
+            a.vals_out[pos] = val[j];
         }
+        if (a.hist_next) {  // the same for the whole grid
+            // which counter of the next pass this key adds to
+            const uint32_t v = (pos / kSortTile) * kBins +
+                               ((uint32_t)(key[j] >> (a.shift + kRadixBits)) & (kBins - 1));
+            // lanes with the same digit sit at consecutive positions; those that also share the
+            // first such lane's counter are counted by it
+            const uint64_t p = peers[j];
+            const int first = p ? __ffsll((unsigned long long)p) - 1 : lane;
+            const uint32_t v_first = __shfl(v, first, 64);
+            const bool with_first = ok && v == v_first;
+            const uint64_t group = __ballot(with_first) & p;
+            uint32_t add = 0;
+            if (ok) add = lane == first ? (uint32_t)__popcll(group) : (with_first ? 0u : 1u);
+            if (add) {
+                const uint32_t s = (v * 2654435761u) >> (32 - kAggBits);
+                const uint32_t old = atomicCAS(&agg_tag[s], kAggEmpty, v);
+                if (old == kAggEmpty || old == v) atomicAdd(&agg_cnt[s], add);
+                else atomicAdd(&a.hist_next[v], add);  // the slot belongs to another counter
+            }
+        }
+    }
+    if (a.hist_next) {
+        __syncthreads();
+        for (int s = threadIdx.x; s < kAggSlots; s += kSortThreads)
+            if (agg_cnt[s]) atomicAdd(&a.hist_next[agg_tag[s]], agg_cnt[s]);
     }
 }
 
@@ -275,26 +357,205 @@ int device_scan(const int32_t *in, int32_t *out, int n, int32_t *tile_tmp, int32
     return check_launch();
 }
 
-// ---------------------------------------------------------------- segments
+// ---------------------------------------------------------------- comparing two tokens' signatures
 
 __device__ __forceinline__ uint64_t hash_part(uint64_t key) { return key >> 8; }
 
-// seg_head[i] = first sorted position with the same hash bits as position i.  Chain set-up:
-// a segment start is its own head and settled; every other position is compared with its
-// left neighbour.  Also clears the per-position and per-token arrays used later.
-__global__ __launch_bounds__(kThreads) void segments_kernel(
-    const uint64_t *__restrict__ keys, int n, int32_t *seg_head, int32_t *head_pos,
-    int32_t *resolved, int32_t *mismatch, int32_t *min_id, uint64_t *rep_key,
-    int32_t *is_head_token, Counters *ctr) {
+// What the comparisons read when the walk vectors of cfgzip_signatures are at hand.
+struct StoreSource {
+    Tables T;
+    WalkStoreView store;
+    int32_t V, S;
+};
+
+// 0 if the store holds this call's vectors, else why not.
+__device__ __forceinline__ int walk_store_state(const StoreSource &s) {
+    const WalkStore hdr = *s.store.header;
+    if (hdr.magic != kWalkStoreMagic || hdr.V != s.V || hdr.S != s.S ||
+        hdr.stride != walk_store_stride(s.S))
+        return kStoreForeign;
+    return hdr.overflow ? kStoreOverflowed : 0;
+}
+
+// Image row of a token as the store has it (256: the empty token, whose signature is the
+// identity and whose vector is not kept).
+__device__ __forceinline__ uint32_t store_row(const StoreSource &s, int32_t tok) {
+    return min((uint32_t)s.store.wrow[tok], 256u);
+}
+
+// Two tokens with the same image row `row` < 256: idx[row] is onto, so their signatures are
+// equal iff their walk vectors are.  One thread, 16 bytes at a time (the padding behind a
+// vector is zero on both sides).
+__device__ __forceinline__ bool store_same_row_differ(const StoreSource &s, int32_t ta, int32_t tb,
+                                                      uint32_t row) {
+    const uint32_t stride = walk_store_stride(s.S);
+    const uint32_t cnt = min((uint32_t)s.T.nimg[row], stride);
+    const uint4 *wa = reinterpret_cast<const uint4 *>(s.store.wvec + (size_t)ta * stride);
+    const uint4 *wb = reinterpret_cast<const uint4 *>(s.store.wvec + (size_t)tb * stride);
+    const uint32_t n16 = (cnt + 7u) / 8u;
+    bool diff = false;
+    constexpr int kAhead = 4;  // independent 16-byte loads in flight per side
+    for (uint32_t k0 = 0; k0 < n16; k0 += kAhead) {
+        uint4 x[kAhead], y[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const uint32_t k = min(k0 + u, n16 - 1);  // repeats the last one past the end
+            x[u] = wa[k];
+            y[u] = wb[k];
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u)
+            diff |= (x[u].x != y[u].x) | (x[u].y != y[u].y) | (x[u].z != y[u].z) | (x[u].w != y[u].w);
+    }
+    return diff;
+}
+
+// Two tokens with different image rows (neighbours at the border between two first bytes inside
+// a segment, or an empty token): sig[q] = w[idx[row][q]] has to be compared for every q; the
+// empty token's signature is sig[q] = q.  One wave; both vectors are staged in the wave's LDS
+// buffers la, lb (kWalkStoreMaxStride entries each).  Returns whether any entry differs
+// (wave-uniform).
+__device__ __forceinline__ bool store_other_row_differ(const StoreSource &s, int32_t ta, int32_t tb,
+                                                       uint32_t ra, uint32_t rb, uint16_t *la,
+                                                       uint16_t *lb) {
+    const int lane = threadIdx.x & 63;
+    const int S = s.S;
+    const uint32_t stride = walk_store_stride(S);
+    const bool ida = ra == 256u, idb = rb == 256u;
+    if (ida && idb) return false;
+    const uint32_t na = min((uint32_t)s.T.nimg[ra], stride), nb = min((uint32_t)s.T.nimg[rb], stride);
+    {
+        // lanes 0..31 copy vector a, lanes 32..63 vector b, 16 bytes each (stride <= 256 entries)
+        const uint32_t half = lane & 31;
+        const bool second = lane >= 32;
+        const uint16_t *src = s.store.wvec + (size_t)(second ? tb : ta) * stride;
+        if (half * 8 < stride && !(second ? idb : ida))
+            reinterpret_cast<uint4 *>(second ? lb : la)[half] = reinterpret_cast<const uint4 *>(src)[half];
+    }
+    // the staged vectors are read below as 16-bit entries by other lanes of this wave
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint16_t *ia = s.T.idx + (size_t)ra * S, *ib = s.T.idx + (size_t)rb * S;
+    bool d = false;
+    auto entry_a = [&](uint32_t q, uint32_t j) -> uint32_t { return ida ? q : (j < na ? la[j] : 0xFFFFu); };
+    auto entry_b = [&](uint32_t q, uint32_t j) -> uint32_t { return idb ? q : (j < nb ? lb[j] : 0xFFFFu); };
+    if ((S % 8) == 0) {
+        // 16 bytes of each index row per lane and step (the identity row is not read)
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        constexpr int kAhead = 2;
+        for (int q0 = lane * 8; q0 < S; q0 += 512 * kAhead) {
+            uint4 xa[kAhead], xb[kAhead];
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int q = q0 + 512 * u;
+                xa[u] = (!ida && q < S) ? *reinterpret_cast<const uint4 *>(ia + q) : zero;
+                xb[u] = (!idb && q < S) ? *reinterpret_cast<const uint4 *>(ib + q) : zero;
+            }
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int q = q0 + 512 * u;
+                if (q >= S) continue;
+                const uint32_t ja[8] = {xa[u].x & 0xFFFFu, xa[u].x >> 16, xa[u].y & 0xFFFFu, xa[u].y >> 16,
+                                        xa[u].z & 0xFFFFu, xa[u].z >> 16, xa[u].w & 0xFFFFu, xa[u].w >> 16};
+                const uint32_t jb[8] = {xb[u].x & 0xFFFFu, xb[u].x >> 16, xb[u].y & 0xFFFFu, xb[u].y >> 16,
+                                        xb[u].z & 0xFFFFu, xb[u].z >> 16, xb[u].w & 0xFFFFu, xb[u].w >> 16};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d |= entry_a(q + e, ja[e]) != entry_b(q + e, jb[e]);
+            }
+        }
+    } else {
+        for (int q = lane; q < S; q += 64)
+            d |= entry_a(q, ida ? 0u : (uint32_t)ia[q]) != entry_b(q, idb ? 0u : (uint32_t)ib[q]);
+    }
+    const bool any = __ballot(d) != 0ull;
+    __builtin_amdgcn_wave_barrier();  // the next pair restages la, lb
+    return any;
+}
+
+// Stored signature rows of two tokens, one wave.
+__device__ __forceinline__ bool rows_differ(const uint16_t *__restrict__ sig, int S, bool vec,
+                                            int32_t ta, int32_t tb) {
+    const int lane = threadIdx.x & 63;
+    const uint16_t *a = sig + (size_t)ta * S;
+    const uint16_t *b = sig + (size_t)tb * S;
+    bool diff = false;
+    if (vec) {
+        const uint4 *a4 = reinterpret_cast<const uint4 *>(a);
+        const uint4 *b4 = reinterpret_cast<const uint4 *>(b);
+        for (int j = lane; j < S / 8; j += 64) {
+            const uint4 x = a4[j], y = b4[j];
+            diff |= (x.x != y.x) | (x.y != y.y) | (x.z != y.z) | (x.w != y.w);
+        }
+    } else {
+        for (int j = lane; j < S; j += 64) diff |= a[j] != b[j];
+    }
+    return __ballot(diff) != 0ull;
+}
+
+// ---------------------------------------------------------------- per-class minima
+
+// Per class (keyed by its anchor position): smallest token id and smallest (length, id).
+// Sorted neighbours mostly share a class, so a wave first reduces over its lanes of equal
+// anchor and issues one pair of atomics per distinct anchor.  Called by whole waves.
+__device__ __forceinline__ void wave_class_minima(bool valid, int32_t anchor, int32_t tok, int64_t len,
+                                                  int32_t *min_id, uint64_t *rep_key) {
+    if (len > 0x7FFFFFFF) len = 0x7FFFFFFF;
+    if (len < 0) len = 0;
+    const uint64_t packed = valid ? ((uint64_t)len << 32) | (uint32_t)tok : ~0ull;
+    const int32_t a = valid ? anchor : -1;
+    uint64_t todo = __ballot(valid);
+    const int lane = threadIdx.x & 63;
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const int32_t a0 = __shfl(a, leader, 64);
+        const bool mine = valid && a == a0;
+        uint64_t m = mine ? packed : ~0ull;
+        int32_t id = mine ? (int32_t)(packed & 0x7FFFFFFFull) : 0x7FFFFFFF;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint64_t o = __shfl_xor(m, off, 64);
+            m = o < m ? o : m;
+            id = min(id, __shfl_xor(id, off, 64));
+        }
+        if (lane == leader) {
+            atomicMin(reinterpret_cast<unsigned long long *>(rep_key + a0), (unsigned long long)m);
+            atomicMin(min_id + a0, id);
+        }
+        todo &= ~__ballot(mine);
+    }
+}
+
+// ---------------------------------------------------------------- links
+
+enum : int { SRC_STORE = 0, SRC_ROWS = 1, SRC_NONE = 2 };
+
+struct LinkArgs {
+    const uint64_t *keys;  // sorted
+    const int32_t *vals;
+    int n;
+    const int64_t *tok_off;
+    int32_t *seg_head, *head_pos, *resolved, *mismatch, *min_id;
+    uint64_t *rep_key;
+    Counters *ctr;
+    StoreSource store;    // SRC_STORE
+    int32_t *other_list;  // SRC_STORE: sorted positions whose link crosses two image rows
+    const uint16_t *sig;  // SRC_ROWS: [V][S]
+    int S;
+};
+
+// One sorted position per thread.  seg_head[i] = first sorted position with the same hash bits
+// as position i.  Chain set-up: a segment start is its own head and settled; every other
+// position is compared with its left neighbour (SRC_NONE: left unsettled for the re-walk kernel
+// that follows).  Also reduces the per-segment minima.
+template <int SRC>
+__global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     __shared__ int32_t wave_tot[kThreads / 64];
     __shared__ int32_t carry_s;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tile0 = blockIdx.x * kTile;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        ctr->unresolved = 0;
-        ctr->num_classes = 0;
-        ctr->store_unusable = 0;
-    }
+    const int tile0 = blockIdx.x * kThreads;
+    const int n = a.n;
+    const uint64_t *keys = a.keys;
     // where the segment that reaches into this tile starts (64-ary search by the first wave)
     if (wave == 0) {
         int lo = tile0;
@@ -319,47 +580,120 @@ __global__ __launch_bounds__(kThreads) void segments_kernel(
         }
         if (lane == 0) carry_s = lo;
     }
-    const int base = tile0 + threadIdx.x * kItems;
-    int32_t v[kItems];
-    int32_t acc = -1;
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        const int i = base + j;
-        v[j] = -1;
-        if (i < n && (i == 0 || hash_part(keys[i]) != hash_part(keys[i - 1]))) v[j] = i;
-        acc = max(acc, v[j]);
+    const int i = tile0 + threadIdx.x;
+    const bool in = i < n;
+    bool start = false;
+    int32_t ta = 0, tb = 0;
+    int64_t len = 0;
+    if (in) {
+        start = i == 0 || hash_part(keys[i]) != hash_part(keys[i - 1]);
+        ta = a.vals[i];
+        tb = i > 0 ? a.vals[i - 1] : ta;
+        len = a.tok_off[ta + 1] - a.tok_off[ta];
     }
-    int32_t inc = acc;
+    int32_t inc = start ? i : -1;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         const int32_t o = __shfl_up(inc, off, 64);
         if (lane >= off) inc = max(inc, o);
     }
     if (lane == 63) wave_tot[wave] = inc;
-    __syncthreads();
-    int32_t run = carry_s;
-    for (int w = 0; w < wave; ++w) run = max(run, wave_tot[w]);
-    int32_t before = __shfl_up(inc, 1, 64);
-    if (lane == 0) before = -1;
-    run = max(run, before);
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        const int i = base + j;
-        run = max(run, v[j]);
-        if (i < n) {
-            const bool start = v[j] == i;
-            seg_head[i] = run;
-            head_pos[i] = start ? i : i - 1;
-            resolved[i] = start ? 1 : 0;
-            mismatch[i] = 0;
-            min_id[i] = 0x7FFFFFFF;
-            rep_key[i] = ~0ull;
-            is_head_token[i] = 0;
-        }
+
+    // SRC_STORE: is the store this call's?  The same answer in every workgroup.
+    int store_state = 0;
+    if (SRC == SRC_STORE) {
+        store_state = walk_store_state(a.store);
+        if (store_state && blockIdx.x == 0 && threadIdx.x == 0) a.ctr->store_state = store_state;
     }
+    const bool verify = in && !start && SRC != SRC_NONE && store_state == 0;
+    bool differs = false;
+    uint32_t ra = 0, rb = 0;
+    if (SRC == SRC_STORE && verify) {
+        ra = store_row(a.store, ta);
+        rb = store_row(a.store, tb);
+        if (ra == rb && ra != 256u) differs = store_same_row_differ(a.store, ta, tb, ra);
+    }
+    __syncthreads();
+    int32_t seg = carry_s;
+    for (int w = 0; w < wave; ++w) seg = max(seg, wave_tot[w]);
+    seg = max(seg, inc);
+
+    bool listed = false;
+    if (SRC == SRC_STORE) {
+        // Links between different image rows cost a pass over all S states each and bunch up
+        // where small classes sit: they are listed, and the next launch spreads them over the
+        // chip, a wave per link.  One append per wave.
+        listed = verify && ra != rb;  // two empty tokens (both rows 256) are equal as they are
+        const uint64_t lm = __ballot(listed);
+        if (lm) {
+            int32_t at = 0;
+            if (lane == 0) at = atomicAdd(&a.ctr->other_rows, (int)__popcll(lm));
+            at = __shfl(at, 0, 64);
+            if (listed) a.other_list[at + __popcll(lm & ((1ull << lane) - 1ull))] = i;
+        }
+    } else if (SRC == SRC_ROWS) {
+        // a wave takes its own positions four at a time: more row reads in flight
+        const bool vec = (a.S % 8) == 0 && (reinterpret_cast<uintptr_t>(a.sig) % 16) == 0;
+        uint64_t todo = __ballot(verify);
+        bool mine = false;
+        while (todo) {
+            int ls[4];
+            int32_t xa[4], xb[4];
+            int cnt = 0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (todo) {
+                    ls[u] = __ffsll((unsigned long long)todo) - 1;
+                    todo &= todo - 1;
+                    ++cnt;
+                } else {
+                    ls[u] = ls[0];  // repeats the first pair
+                }
+                xa[u] = __shfl(ta, ls[u], 64);
+                xb[u] = __shfl(tb, ls[u], 64);
+            }
+            bool d[4] = {false, false, false, false};
+            if (vec) {
+                for (int j = lane; j < a.S / 8; j += 64) {
+                    uint4 x[4], y[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        x[u] = reinterpret_cast<const uint4 *>(a.sig + (size_t)xa[u] * a.S)[j];
+                        y[u] = reinterpret_cast<const uint4 *>(a.sig + (size_t)xb[u] * a.S)[j];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        d[u] |= (x[u].x != y[u].x) | (x[u].y != y[u].y) | (x[u].z != y[u].z) |
+                                (x[u].w != y[u].w);
+                }
+            } else {
+                for (int j = lane; j < a.S; j += 64)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        d[u] |= a.sig[(size_t)xa[u] * a.S + j] != a.sig[(size_t)xb[u] * a.S + j];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool any = __ballot(d[u]) != 0ull;
+                if (u < cnt && lane == ls[u]) mine = any;
+            }
+        }
+        differs = mine;
+    }
+
+    if (in) {
+        a.seg_head[i] = seg;
+        a.head_pos[i] = start ? i : i - 1;
+        a.resolved[i] = (start || (verify && !listed && !differs)) ? 1 : 0;
+        a.mismatch[i] = differs ? 1 : 0;
+    }
+    const uint64_t dm = __ballot(differs);
+    if (dm && lane == 0) atomicAdd(&a.ctr->unresolved, (int)__popcll(dm));
+    wave_class_minima(in, seg, ta, len, a.min_id, a.rep_key);
 }
 
-// ---------------------------------------------------------------- verification
+// ---------------------------------------------------------------- verification of arbitrary pairs
+// (the collision rounds: position i against position head_pos[i], for every unsettled i)
 
 __device__ __forceinline__ void settle(bool differs, int i, int32_t *resolved, int32_t *mismatch,
                                        Counters *ctr) {
@@ -378,38 +712,18 @@ __global__ __launch_bounds__(kThreads) void verify_stored_kernel(
     const uint16_t *__restrict__ sig, int S, const int32_t *__restrict__ vals,
     const int32_t *__restrict__ head_pos, int32_t *resolved, int n, int32_t *mismatch,
     Counters *ctr) {
-    const int lane = threadIdx.x & 63;
     const int64_t gw = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     const int64_t total = (int64_t)gridDim.x * (kThreads / 64);
     const bool vec = (S % 8) == 0 && (reinterpret_cast<uintptr_t>(sig) % 16) == 0;
     for (int64_t i = gw; i < n; i += total) {
         if (resolved[i]) continue;  // wave-uniform
-        const uint16_t *a = sig + (size_t)vals[i] * S;
-        const uint16_t *b = sig + (size_t)vals[head_pos[i]] * S;
-        bool diff = false;
-        if (vec) {
-            const uint4 *a4 = reinterpret_cast<const uint4 *>(a);
-            const uint4 *b4 = reinterpret_cast<const uint4 *>(b);
-            for (int j = lane; j < S / 8; j += 64) {
-                const uint4 x = a4[j], y = b4[j];
-                diff |= (x.x != y.x) | (x.y != y.y) | (x.z != y.z) | (x.w != y.w);
-            }
-        } else {
-            for (int j = lane; j < S; j += 64) diff |= a[j] != b[j];
-        }
-        settle(__ballot(diff) != 0ull, (int)i, resolved, mismatch, ctr);
+        settle(rows_differ(sig, S, vec, vals[i], vals[head_pos[i]]), (int)i, resolved, mismatch, ctr);
     }
 }
 
-// Compares the walk vectors that cfgzip_signatures kept for position i and for position
-// head_pos[i], for the pairs whose tokens have the same image row: idx[row] is onto, so sig
-// equal <=> w equal.  One thread per position, 16 bytes at a time (the padding behind a
-// vector is zero on both sides).  A store that does not belong to this (V, S) or has
-// overflowed is reported and nothing is compared.
 struct StoreVerifyArgs {
-    Tables T;
-    WalkStoreView store;
-    int32_t V, S, n;
+    StoreSource src;
+    int32_t n;
     const int32_t *vals;
     const int32_t *head_pos;
     int32_t *resolved;
@@ -417,118 +731,45 @@ struct StoreVerifyArgs {
     Counters *ctr;
 };
 
-__device__ __forceinline__ bool walk_store_usable(const StoreVerifyArgs &a, uint32_t stride) {
-    const WalkStore hdr = *a.store.header;
-    return hdr.magic == kWalkStoreMagic && hdr.V == a.V && hdr.S == a.S && hdr.stride == stride &&
-           !hdr.overflow;
-}
-
-__device__ __forceinline__ void verify_store_same_row(const StoreVerifyArgs &a, int block) {
-    const uint32_t stride = walk_store_stride(a.S);
-    if (!walk_store_usable(a, stride)) {
-        if (block == 0 && threadIdx.x == 0) a.ctr->store_unusable = 1;
+// A workgroup looks at 256 positions.  Pairs with the same image row are compared by their own
+// thread; for the others, wave w takes the positions of its own 64 lanes one after the other (so
+// which wave settles a position never depends on what another wave has settled meanwhile).
+__global__ __launch_bounds__(kThreads) void verify_store_kernel(StoreVerifyArgs a) {
+    __shared__ __align__(16) uint16_t staged[kThreads / 64][2][kWalkStoreMaxStride];
+    const int state = walk_store_state(a.src);
+    if (state) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->store_state = state;
         return;
     }
-    const int i = block * (int)blockDim.x + threadIdx.x;
-    if (i >= a.n || a.resolved[i]) return;
-    const int32_t ta = a.vals[i], tb = a.vals[a.head_pos[i]];
-    const uint32_t ra = min((uint32_t)a.store.wrow[ta], 256u), rb = min((uint32_t)a.store.wrow[tb], 256u);
-    if (ra != rb) return;  // left to verify_store_other_row
-    const uint32_t cnt = min((uint32_t)a.T.nimg[ra], stride);
-    const uint4 *wa = reinterpret_cast<const uint4 *>(a.store.wvec + (size_t)ta * stride);
-    const uint4 *wb = reinterpret_cast<const uint4 *>(a.store.wvec + (size_t)tb * stride);
-    const uint32_t n16 = (cnt + 7u) / 8u;
-    bool diff = false;
-    constexpr int kAhead = 4;  // independent 16-byte loads in flight per side
-    for (uint32_t k0 = 0; k0 < n16; k0 += kAhead) {
-        uint4 x[kAhead], y[kAhead];
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const uint32_t k = min(k0 + u, n16 - 1);  // repeats the last one past the end
-            x[u] = wa[k];
-            y[u] = wb[k];
-        }
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u)
-            diff |= (x[u].x != y[u].x) | (x[u].y != y[u].y) | (x[u].z != y[u].z) | (x[u].w != y[u].w);
-    }
-    if (diff) {
-        a.mismatch[i] = 1;
-        atomicAdd(&a.ctr->unresolved, 1);
-    } else {
-        a.resolved[i] = 1;
-    }
-}
-
-// The pairs whose tokens have different image rows (neighbours at the border between two
-// first bytes inside a segment): sig[q] = w[idx[row][q]] has to be compared for every q.  A
-// workgroup of 16 waves looks at 64 consecutive positions; every wave finds the same list of
-// such pairs and takes every 16th of it, staging the two vectors in LDS.
-constexpr int kStoreVerifyThreads = 1024;
-__device__ __forceinline__ void verify_store_other_row(
-    const StoreVerifyArgs &a, int block, uint16_t (*staged)[2][kWalkStoreMaxStride]) {
-    const uint32_t stride = walk_store_stride(a.S);
-    if (!walk_store_usable(a, stride)) return;  // reported by the same-row part
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int S = a.S;
-    const int i = block * 64 + lane;
+    const int wave = threadIdx.x >> 6;
+    const int i = blockIdx.x * kThreads + threadIdx.x;
     const bool todo = i < a.n && !a.resolved[i];
     int32_t ta = 0, tb = 0;
     uint32_t ra = 256, rb = 256;
     if (todo) {
         ta = a.vals[i];
         tb = a.vals[a.head_pos[i]];
-        ra = min((uint32_t)a.store.wrow[ta], 256u);
-        rb = min((uint32_t)a.store.wrow[tb], 256u);
+        ra = store_row(a.src, ta);
+        rb = store_row(a.src, tb);
     }
-    uint64_t list = __ballot(todo && ra != rb);  // same-row pairs settle in the other kernel
-    uint16_t *la = staged[wave][0], *lb = staged[wave][1];
-    for (int ordinal = 0; list; ++ordinal) {
+    const bool same = todo && ra == rb && ra != 256u;
+    if (same) {
+        if (store_same_row_differ(a.src, ta, tb, ra)) {
+            a.mismatch[i] = 1;
+            atomicAdd(&a.ctr->unresolved, 1);
+        } else {
+            a.resolved[i] = 1;
+        }
+    }
+    uint64_t list = __ballot(todo && !same);
+    while (list) {
         const int l = __ffsll((unsigned long long)list) - 1;
         list &= list - 1;
-        if (ordinal % (kStoreVerifyThreads / 64) != wave) continue;  // wave-uniform
-        const int32_t sa = __shfl(ta, l, 64), sb = __shfl(tb, l, 64);
-        const uint32_t qa = __shfl(ra, l, 64), qb = __shfl(rb, l, 64);
-        const uint32_t na = min((uint32_t)a.T.nimg[qa], stride), nb = min((uint32_t)a.T.nimg[qb], stride);
-        {
-            // lanes 0..31 copy vector a, lanes 32..63 vector b, 16 bytes each (stride <= 256 entries)
-            const uint32_t half = lane & 31;
-            const uint16_t *src = a.store.wvec + (size_t)(lane < 32 ? sa : sb) * stride;
-            if (half * 8 < stride)
-                reinterpret_cast<uint4 *>(lane < 32 ? la : lb)[half] =
-                    reinterpret_cast<const uint4 *>(src)[half];
-        }
-        const uint16_t *ia = a.T.idx + (size_t)qa * S, *ib = a.T.idx + (size_t)qb * S;
-        bool d = false;
-        if ((S % 8) == 0) {
-            for (int q0 = lane * 8; q0 < S; q0 += 512) {
-                const uint4 xa = *reinterpret_cast<const uint4 *>(ia + q0);
-                const uint4 xb = *reinterpret_cast<const uint4 *>(ib + q0);
-                const uint32_t ja[8] = {xa.x & 0xFFFFu, xa.x >> 16, xa.y & 0xFFFFu, xa.y >> 16,
-                                        xa.z & 0xFFFFu, xa.z >> 16, xa.w & 0xFFFFu, xa.w >> 16};
-                const uint32_t jb[8] = {xb.x & 0xFFFFu, xb.x >> 16, xb.y & 0xFFFFu, xb.y >> 16,
-                                        xb.z & 0xFFFFu, xb.z >> 16, xb.w & 0xFFFFu, xb.w >> 16};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    d |= (ja[e] < na ? la[ja[e]] : 0xFFFFu) != (jb[e] < nb ? lb[jb[e]] : 0xFFFFu);
-            }
-        } else {
-            for (int q = lane; q < S; q += 64) {
-                const uint32_t ja = ia[q], jb = ib[q];
-                d |= (ja < na ? la[ja] : 0xFFFFu) != (jb < nb ? lb[jb] : 0xFFFFu);
-            }
-        }
-        settle(__ballot(d) != 0ull, block * 64 + l, a.resolved, a.mismatch, a.ctr);
+        const bool d = store_other_row_differ(a.src, __shfl(ta, l, 64), __shfl(tb, l, 64),
+                                              __shfl(ra, l, 64), __shfl(rb, l, 64), staged[wave][0],
+                                              staged[wave][1]);
+        settle(d, blockIdx.x * kThreads + wave * 64 + l, a.resolved, a.mismatch, a.ctr);
     }
-}
-
-// Both parts in one launch (they settle disjoint positions): the first `same_row_blocks`
-// workgroups take one position per thread, the rest 64 positions per workgroup.
-__global__ __launch_bounds__(kStoreVerifyThreads) void verify_store_kernel(StoreVerifyArgs a,
-                                                                           int same_row_blocks) {
-    __shared__ uint16_t staged[kStoreVerifyThreads / 64][2][kWalkStoreMaxStride];
-    if ((int)blockIdx.x < same_row_blocks) verify_store_same_row(a, blockIdx.x);
-    else verify_store_other_row(a, blockIdx.x - same_row_blocks, staged);
 }
 
 // Signatures of two walked batch slots, compared without materialising either: directly on w
@@ -730,77 +971,163 @@ __global__ void round_assign_kernel(int n, int32_t *resolved, const int32_t *__r
 // chain start.  Also clears what the numbering kernels accumulate into.
 __global__ void anchors_kernel(int n, const int32_t *__restrict__ chain_start,
                                const int32_t *__restrict__ head_pos, int32_t *anchor,
-                               int32_t *min_id, uint64_t *rep_key, int32_t *is_head_token) {
+                               int32_t *min_id, uint64_t *rep_key, uint32_t *head_bits, int n_words) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_words) head_bits[i] = 0;
     if (i >= n) return;
     anchor[i] = head_pos[chain_start[i]];
     min_id[i] = 0x7FFFFFFF;
     rep_key[i] = ~0ull;
-    is_head_token[i] = 0;
+}
+
+// The same clearing alone, before the links are taken again from another source.
+__global__ void reset_numbering_kernel(int n, int32_t *min_id, uint64_t *rep_key, uint32_t *head_bits,
+                                       int n_words, Counters *ctr) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        ctr->unresolved = 0;
+        ctr->num_classes = 0;
+        ctr->store_state = 0;
+        ctr->other_rows = 0;
+    }
+    if (i < n_words) head_bits[i] = 0;
+    if (i >= n) return;
+    min_id[i] = 0x7FFFFFFF;
+    rep_key[i] = ~0ull;
 }
 
 // ---------------------------------------------------------------- numbering and representatives
 
-// Per class (keyed by its anchor position): smallest token id and smallest (length, id).
-// Sorted neighbours mostly share a class, so a wave first reduces over its lanes of equal
-// anchor and issues one pair of atomics per distinct anchor.
+// The per-class minima over arbitrary anchors (after collision rounds; without collisions the
+// link kernel has done it over the segments).
 __global__ __launch_bounds__(kThreads) void class_minima_kernel(
     int n, const int32_t *__restrict__ anchor, const int32_t *__restrict__ vals,
     const int64_t *__restrict__ tok_off, int32_t *min_id, uint64_t *rep_key) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     const bool valid = i < n;
-    int32_t a = -1;
-    uint64_t packed = ~0ull;
+    int32_t a = 0, tok = 0;
+    int64_t len = 0;
     if (valid) {
-        const int32_t tok = vals[i];
+        tok = vals[i];
         a = anchor[i];
-        int64_t len = tok_off[tok + 1] - tok_off[tok];
-        if (len > 0x7FFFFFFF) len = 0x7FFFFFFF;
-        if (len < 0) len = 0;
-        packed = ((uint64_t)len << 32) | (uint32_t)tok;
+        len = tok_off[tok + 1] - tok_off[tok];
     }
-    uint64_t todo = __ballot(valid);
-    const int lane = threadIdx.x & 63;
-    while (todo) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const int32_t a0 = __shfl(a, leader, 64);
-        const bool mine = valid && a == a0;
-        uint64_t m = mine ? packed : ~0ull;
-        int32_t id = mine ? (int32_t)(packed & 0x7FFFFFFFull) : 0x7FFFFFFF;
+    wave_class_minima(valid, a, tok, len, min_id, rep_key);
+}
+
+// head_bits bit t = token t is the smallest member of its class (the first `mark_blocks`
+// workgroups, a sorted position per thread).  The other workgroups settle the links that the
+// link kernel listed: a wave per link, striding over the list.
+struct MarkArgs {
+    int n, mark_blocks;
+    const int32_t *anchor;
+    const int32_t *min_id;
+    uint32_t *head_bits;
+    // listed links (null list: none)
+    const int32_t *other_list;
+    StoreSource store;
+    const int32_t *vals;
+    int32_t *resolved, *mismatch;
+    Counters *ctr;
+};
+
+__global__ __launch_bounds__(kThreads) void mark_heads_kernel(MarkArgs a) {
+    __shared__ __align__(16) uint16_t staged[kThreads / 64][2][kWalkStoreMaxStride];
+    if ((int)blockIdx.x < a.mark_blocks) {
+        const int i = blockIdx.x * kThreads + threadIdx.x;
+        if (i < a.n && a.anchor[i] == i) {
+            const uint32_t m = (uint32_t)a.min_id[i];
+            if (m < (uint32_t)a.n) atomicOr(&a.head_bits[m >> 5], 1u << (m & 31));  // always: a class has a member
+        }
+        return;
+    }
+    if (!a.other_list) return;
+    const int wave = threadIdx.x >> 6;
+    const int count = min(a.ctr->other_rows, a.n);
+    const int waves = ((int)gridDim.x - a.mark_blocks) * (kThreads / 64);
+    for (int e = ((int)blockIdx.x - a.mark_blocks) * (kThreads / 64) + wave; e < count; e += waves) {
+        const int i = a.other_list[e];
+        if (i <= 0 || i >= a.n) continue;  // never listed; stay in bounds
+        const int32_t ta = a.vals[i], tb = a.vals[i - 1];
+        const bool d = store_other_row_differ(a.store, ta, tb, store_row(a.store, ta),
+                                              store_row(a.store, tb), staged[wave][0], staged[wave][1]);
+        settle(d, i, a.resolved, a.mismatch, a.ctr);
+    }
+}
+
+__global__ void popcount_words_kernel(const uint32_t *__restrict__ bits, int n_words, int32_t *out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_words) out[i] = __popc(bits[i]);
+}
+
+struct AssignArgs {
+    int n, n_words;
+    const int32_t *anchor;
+    const int32_t *vals;
+    const int32_t *min_id;
+    const uint32_t *head_bits;
+    const int32_t *word_prefix;  // !LDS_RANK: set bits before each word of head_bits
+    const uint64_t *rep_key;
+    Counters *ctr;
+    int32_t *class_of_token, *rep_of_class, *num_classes_dev;
+};
+
+// Class id of a class = number of classes whose smallest token id is smaller = set bits of
+// head_bits below its own.  LDS_RANK: every workgroup copies the bit vector into LDS and sums
+// its words' popcounts there (a redundant scan per workgroup, no launch of its own).
+template <bool LDS_RANK>
+__global__ __launch_bounds__(kAssignThreads) void assign_classes_kernel(AssignArgs a) {
+    extern __shared__ uint32_t rank_lds[];  // LDS_RANK: [n_words] bits, [n_words] prefix
+    __shared__ uint32_t wave_tot[kAssignThreads / 64];
+    uint32_t *bits = rank_lds, *prefix = rank_lds + a.n_words;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (LDS_RANK) {
+        for (int w = threadIdx.x; w < a.n_words; w += kAssignThreads) bits[w] = a.head_bits[w];
+        __syncthreads();
+        // thread t owns the words [t * per, (t + 1) * per)
+        const int per = (a.n_words + kAssignThreads - 1) / kAssignThreads;
+        const int w0 = min(a.n_words, (int)threadIdx.x * per), w1 = min(a.n_words, w0 + per);
+        uint32_t sum = 0;
+        for (int w = w0; w < w1; ++w) sum += __popc(bits[w]);
+        const uint32_t incl = (uint32_t)wave_inclusive_sum((int)sum);
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t run = incl - sum;
+        for (int w = 0; w < wave; ++w) run += wave_tot[w];
+        for (int w = w0; w < w1; ++w) {
+            prefix[w] = run;
+            run += __popc(bits[w]);
+        }
+        if (blockIdx.x == 0 && threadIdx.x == kAssignThreads - 1) {
+            a.ctr->num_classes = (int32_t)run;  // the last thread's running sum is the total
+            if (a.num_classes_dev) *a.num_classes_dev = (int32_t)run;
+        }
+        __syncthreads();
+    } else if (blockIdx.x == 0 && threadIdx.x == 0 && a.num_classes_dev) {
+        *a.num_classes_dev = a.ctr->num_classes;  // written by the scan before this launch
+    }
+    const int base = blockIdx.x * kAssignTile;
+    int32_t anc[kAssignItems], tok[kAssignItems];
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint64_t o = __shfl_xor(m, off, 64);
-            m = o < m ? o : m;
-            id = min(id, __shfl_xor(id, off, 64));
-        }
-        if (lane == leader) {
-            atomicMin(reinterpret_cast<unsigned long long *>(rep_key + a0), (unsigned long long)m);
-            atomicMin(min_id + a0, id);
-        }
-        todo &= ~__ballot(mine);
+    for (int j = 0; j < kAssignItems; ++j) {
+        const int i = base + j * kAssignThreads + threadIdx.x;
+        anc[j] = i < a.n ? a.anchor[i] : 0;
+        tok[j] = i < a.n ? a.vals[i] : 0;
     }
-}
-
-__global__ void mark_heads_kernel(int n, const int32_t *__restrict__ anchor,
-                                  const int32_t *__restrict__ min_id, int32_t *is_head_token) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n && anchor[i] == i) is_head_token[min_id[i]] = 1;
-}
-
-__global__ void assign_classes_kernel(int n, const int32_t *__restrict__ anchor,
-                                      const int32_t *__restrict__ vals,
-                                      const int32_t *__restrict__ min_id,
-                                      const int32_t *__restrict__ id_of_head_token,
-                                      const uint64_t *__restrict__ rep_key, const Counters *ctr,
-                                      int32_t *class_of_token, int32_t *rep_of_class,
-                                      int32_t *num_classes_dev) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0 && num_classes_dev) *num_classes_dev = ctr->num_classes;
-    if (i >= n) return;
-    const int32_t a = anchor[i];
-    const int32_t k = id_of_head_token[min_id[a]];
-    class_of_token[vals[i]] = k;
-    if (a == i) rep_of_class[k] = (int32_t)(rep_key[i] & 0xFFFFFFFFull);
+    uint32_t m[kAssignItems];
+#pragma unroll
+    for (int j = 0; j < kAssignItems; ++j) m[j] = (uint32_t)a.min_id[anc[j]];
+#pragma unroll
+    for (int j = 0; j < kAssignItems; ++j) {
+        const int i = base + j * kAssignThreads + threadIdx.x;
+        if (i >= a.n) continue;
+        if (m[j] >= (uint32_t)a.n) continue;  // cannot happen: every anchor has a member; stay in bounds
+        const uint32_t w = m[j] >> 5, below = (1u << (m[j] & 31)) - 1u;
+        const int32_t k = LDS_RANK ? (int32_t)(prefix[w] + __popc(bits[w] & below))
+                                   : a.word_prefix[w] + __popc(a.head_bits[w] & below);
+        a.class_of_token[tok[j]] = k;
+        if (anc[j] == i) a.rep_of_class[k] = (int32_t)(a.rep_key[i] & 0xFFFFFFFFull);
+    }
 }
 
 struct BuildWorkspace {
@@ -809,24 +1136,29 @@ struct BuildWorkspace {
     int32_t *vals[2];
     uint32_t *hist;
     int32_t *seg_head, *head_pos, *resolved, *mismatch, *next_head, *cand, *chain_start, *anchor;
-    int32_t *min_id, *is_head_token, *id_of_head_token, *tile_tmp;
+    int32_t *min_id, *word_prefix, *tile_tmp;
+    uint32_t *head_bits;
     uint64_t *rep_key;
     uint16_t *verify_w;  // walk vectors of the re-walk verification when they do not fit in LDS
     Counters *ctr;
     size_t bytes;
 };
 
+inline int sort_passes_for(int32_t V) { return (hash_bits_for(V) + 8 + kRadixBits - 1) / kRadixBits; }
+
 BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
     Carver c(ws);
     BuildWorkspace w;
     const size_t n = (size_t)V;
+    const size_t nb = (size_t)ceil_div(V, kSortTile);
     const size_t nt = (size_t)ceil_div(V, kTile);
+    const size_t n_words = (size_t)words_for(V);
     w.sig_ws = c.take<char>(sig_workspace_bytes(0, S));
     w.keys[0] = c.take<uint64_t>(n);
     w.keys[1] = c.take<uint64_t>(n);
     w.vals[0] = c.take<int32_t>(n);
     w.vals[1] = c.take<int32_t>(n);
-    w.hist = c.take<uint32_t>(nt * kBins);
+    w.hist = c.take<uint32_t>((size_t)sort_passes_for(V) * nb * kBins);
     w.seg_head = c.take<int32_t>(n);
     w.head_pos = c.take<int32_t>(n);
     w.resolved = c.take<int32_t>(n);
@@ -836,8 +1168,8 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
     w.chain_start = c.take<int32_t>(n);
     w.anchor = c.take<int32_t>(n);
     w.min_id = c.take<int32_t>(n);
-    w.is_head_token = c.take<int32_t>(n);
-    w.id_of_head_token = c.take<int32_t>(n);
+    w.word_prefix = c.take<int32_t>(n_words);
+    w.head_bits = c.take<uint32_t>(n_words);
     w.tile_tmp = c.take<int32_t>(nt);
     w.rep_key = c.take<uint64_t>(n);
     w.verify_w = walk_cap_for(S) > kMaxLdsWalkEntries
@@ -896,25 +1228,21 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const int n = V;
-    const int nb = (int)ceil_div(n, kTile);
-    int n_cu = 256;
-    {
-        int dev = 0;
-        CFGZIP_TRY(check_hip(hipGetDevice(&dev)));
-        CFGZIP_TRY(check_hip(
-            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)));
-        if (n_cu <= 0) n_cu = 256;
-    }
+    const int nb = (int)ceil_div(n, kSortTile);
+    const int n_words = (int)words_for(n);
 
     // where the comparisons read signatures from
     enum { FROM_STORE, FROM_ROWS, FROM_REWALK } source =
         signatures_ws ? FROM_STORE : (sig ? FROM_ROWS : FROM_REWALK);
-    Tables store_tables{};
-    WalkStoreView store{};
-    if (source == FROM_STORE) view_signature_workspace(signatures_ws, V, S, &store_tables, &store);
+    StoreSource store_src{};
+    store_src.V = V;
+    store_src.S = S;
+    if (source == FROM_STORE) view_signature_workspace(signatures_ws, V, S, &store_src.T, &store_src.store);
     RewalkArgs ra{};
-    auto prepare_rewalk = [&]() -> int {
-        CFGZIP_TRY(prepare_tables(table, S, 0, false, 0, w.sig_ws, &ra.T, nullptr, stream));
+    // tables_from_store: the signature call's tables are good although its walk vectors are not
+    auto prepare_rewalk = [&](bool tables_from_store) -> int {
+        if (tables_from_store) ra.T = store_src.T;
+        else CFGZIP_TRY(prepare_tables(table, S, 0, false, 0, w.sig_ws, &ra.T, nullptr, stream));
         ra.S = S;
         ra.wcap = walk_cap_for(S);
         ra.n = n;
@@ -927,77 +1255,100 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         return CFGZIP_OK;
     };
     // re-walking needs its own tables: enqueue them first (independent of the sort)
-    if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk());
+    if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk(false));
 
-    // 1. sort (hash bits, first byte) with the token id as value
+    // 1. keys and the first pass's digit counts
     const int hash_bits = hash_bits_for(V);
-    const uint64_t hash_mask = (1ull << hash_bits) - 1ull;
-    const int passes = (hash_bits + 8) / kRadixBits;
-    int cur = 0;
-    for (int pass = 0; pass < passes; ++pass) {
-        ScatterArgs sa{};
-        sa.hash = hash;
-        sa.tok_off = tok_off;
-        sa.tok_bytes = tok_bytes;
-        sa.keys_in = pass ? w.keys[cur ^ 1] : nullptr;
-        sa.vals_in = pass ? w.vals[cur ^ 1] : nullptr;
-        sa.keys_out = w.keys[cur];
-        sa.vals_out = w.vals[cur];
-        sa.hist = w.hist;
-        sa.hash_mask = hash_mask;
-        sa.n = n;
-        sa.nb = nb;
-        sa.shift = pass * kRadixBits;
-        if (pass == 0) {
-            hipLaunchKernelGGL(radix_hist_kernel<true>, dim3(nb), dim3(kThreads), 0, stream, hash,
-                               tok_off, tok_bytes, nullptr, n, sa.shift, hash_mask, w.hist);
-            CFGZIP_TRY(check_launch());
-            hipLaunchKernelGGL(radix_scatter_kernel<true>, dim3(nb), dim3(kThreads), 0, stream, sa);
-        } else {
-            hipLaunchKernelGGL(radix_hist_kernel<false>, dim3(nb), dim3(kThreads), 0, stream, hash,
-                               tok_off, tok_bytes, sa.keys_in, n, sa.shift, hash_mask, w.hist);
-            CFGZIP_TRY(check_launch());
-            hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(nb), dim3(kThreads), 0, stream, sa);
-        }
+    const int passes = sort_passes_for(V);
+    {
+        KeysArgs ka{};
+        ka.hash = hash;
+        ka.tok_off = tok_off;
+        ka.tok_bytes = tok_bytes;
+        ka.keys_out = w.keys[0];
+        ka.hist = w.hist;
+        ka.hash_mask = (1ull << hash_bits) - 1ull;
+        ka.n = n;
+        ka.nb = nb;
+        ka.passes = passes;
+        ka.min_id = w.min_id;
+        ka.rep_key = w.rep_key;
+        ka.head_bits = w.head_bits;
+        ka.n_words = n_words;
+        ka.ctr = w.ctr;
+        hipLaunchKernelGGL(keys_kernel, dim3(nb), dim3(kSortThreads), 0, stream, ka);
         CFGZIP_TRY(check_launch());
-        cur ^= 1;
     }
-    const uint64_t *keys = w.keys[cur ^ 1];
-    const int32_t *vals = w.vals[cur ^ 1];
+    // 2. sort (hash bits, first byte) with the token id as value
+    int cur = 0;
+    for (int pass = 0; pass < passes; ++pass, cur ^= 1) {
+        PassArgs pa{};
+        pa.keys_in = w.keys[cur];
+        pa.vals_in = w.vals[cur];
+        pa.keys_out = w.keys[cur ^ 1];
+        pa.vals_out = w.vals[cur ^ 1];
+        pa.hist = w.hist + (size_t)pass * nb * kBins;
+        pa.hist_next = pass + 1 < passes ? w.hist + (size_t)(pass + 1) * nb * kBins : nullptr;
+        pa.n = n;
+        pa.nb = nb;
+        pa.shift = pass * kRadixBits;
+        if (pass == 0) hipLaunchKernelGGL(radix_pass_kernel<true>, dim3(nb), dim3(kSortThreads), 0, stream, pa);
+        else hipLaunchKernelGGL(radix_pass_kernel<false>, dim3(nb), dim3(kSortThreads), 0, stream, pa);
+        CFGZIP_TRY(check_launch());
+    }
+    const uint64_t *keys = w.keys[cur];
+    const int32_t *vals = w.vals[cur];
     ra.vals = vals;
     ra.head_pos = w.head_pos;
 
-    // 2. equal-hash segments, chain set-up
-    auto set_up_chains = [&]() -> int {
-        hipLaunchKernelGGL(segments_kernel, dim3(nb), dim3(kThreads), 0, stream, keys, n, w.seg_head,
-                           w.head_pos, w.resolved, w.mismatch, w.min_id, w.rep_key, w.is_head_token,
-                           w.ctr);
-        return check_launch();
+    // 3. equal-hash segments, chain links, per-segment minima
+    auto link = [&]() -> int {
+        LinkArgs la{};
+        la.keys = keys;
+        la.vals = vals;
+        la.n = n;
+        la.tok_off = tok_off;
+        la.seg_head = w.seg_head;
+        la.head_pos = w.head_pos;
+        la.resolved = w.resolved;
+        la.mismatch = w.mismatch;
+        la.min_id = w.min_id;
+        la.rep_key = w.rep_key;
+        la.ctr = w.ctr;
+        la.store = store_src;
+        la.other_list = w.cand;  // free until the collision rounds, which start after a host wait
+        la.sig = sig;
+        la.S = S;
+        if (source == FROM_STORE) hipLaunchKernelGGL(link_kernel<SRC_STORE>, grid_for(n), dim3(kThreads), 0, stream, la);
+        else if (source == FROM_ROWS) hipLaunchKernelGGL(link_kernel<SRC_ROWS>, grid_for(n), dim3(kThreads), 0, stream, la);
+        else hipLaunchKernelGGL(link_kernel<SRC_NONE>, grid_for(n), dim3(kThreads), 0, stream, la);
+        CFGZIP_TRY(check_launch());
+        if (source == FROM_REWALK)  // the chain links: head_pos[i] == i - 1 for every unsettled i
+            return launch_rewalk(verify_chain_rewalk_kernel<false>, verify_chain_rewalk_kernel<true>, ra,
+                                 (int)ceil_div(n, kBatchTokens - 1), stream);
+        return CFGZIP_OK;
     };
-    CFGZIP_TRY(set_up_chains());
-
-    const int64_t wave_grid = ceil_div(std::min<int64_t>(n, (int64_t)n_cu * 32), kThreads / 64);
-    StoreVerifyArgs sva{};
-    sva.T = store_tables;
-    sva.store = store;
-    sva.V = V;
-    sva.S = S;
-    sva.n = n;
-    sva.vals = vals;
-    sva.head_pos = w.head_pos;
-    sva.resolved = w.resolved;
-    sva.mismatch = w.mismatch;
-    sva.ctr = w.ctr;
-    // compares every unsettled position i with position head_pos[i]
+    // compares every unsettled position i with position head_pos[i] (collision rounds)
     auto verify_pairs = [&]() -> int {
         if (source == FROM_STORE) {
-            const int same_row_blocks = (int)ceil_div(n, kStoreVerifyThreads);
-            hipLaunchKernelGGL(verify_store_kernel,
-                               dim3((unsigned)(same_row_blocks + ceil_div(n, 64))),
-                               dim3(kStoreVerifyThreads), 0, stream, sva, same_row_blocks);
+            StoreVerifyArgs sva{};
+            sva.src = store_src;
+            sva.n = n;
+            sva.vals = vals;
+            sva.head_pos = w.head_pos;
+            sva.resolved = w.resolved;
+            sva.mismatch = w.mismatch;
+            sva.ctr = w.ctr;
+            hipLaunchKernelGGL(verify_store_kernel, grid_for(n), dim3(kThreads), 0, stream, sva);
             return check_launch();
         }
         if (source == FROM_ROWS) {
+            int n_cu = 256;
+            int dev = 0;
+            CFGZIP_TRY(check_hip(hipGetDevice(&dev)));
+            CFGZIP_TRY(check_hip(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)));
+            if (n_cu <= 0) n_cu = 256;
+            const int64_t wave_grid = ceil_div(std::min<int64_t>(n, (int64_t)n_cu * 32), kThreads / 64);
             hipLaunchKernelGGL(verify_stored_kernel, dim3((unsigned)wave_grid), dim3(kThreads), 0,
                                stream, sig, S, vals, w.head_pos, w.resolved, n, w.mismatch, w.ctr);
             return check_launch();
@@ -1005,25 +1356,59 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         return launch_rewalk(verify_pairs_rewalk_kernel<false>, verify_pairs_rewalk_kernel<true>, ra,
                              (int)ceil_div(n, kBatchTokens / 2), stream);
     };
-    // the chain links: head_pos[i] == i - 1 for every unsettled i
-    auto verify_links = [&]() -> int {
-        if (source != FROM_REWALK) return verify_pairs();
-        return launch_rewalk(verify_chain_rewalk_kernel<false>, verify_chain_rewalk_kernel<true>, ra,
-                             (int)ceil_div(n, kBatchTokens - 1), stream);
-    };
-    // 4./5. class ids by ascending smallest member id, representatives
-    auto number_classes = [&](const int32_t *anchor) -> int {
-        hipLaunchKernelGGL(class_minima_kernel, grid_for(n), dim3(kThreads), 0, stream, n, anchor,
-                           vals, tok_off, w.min_id, w.rep_key);
+    // 5./6. class ids by ascending smallest member id, representatives
+    // `settle_listed`: right after the link kernel, the same launch also compares the links it listed
+    auto number_classes = [&](const int32_t *anchor, bool settle_listed) -> int {
+        MarkArgs ma{};
+        ma.n = n;
+        ma.mark_blocks = (int)ceil_div(n, kThreads);
+        ma.anchor = anchor;
+        ma.min_id = w.min_id;
+        ma.head_bits = w.head_bits;
+        int verify_blocks = 0;
+        if (settle_listed && source == FROM_STORE) {
+            ma.other_list = w.cand;
+            ma.store = store_src;
+            ma.vals = vals;
+            ma.resolved = w.resolved;
+            ma.mismatch = w.mismatch;
+            ma.ctr = w.ctr;
+            verify_blocks = (int)std::min<int64_t>(ceil_div(n, kThreads / 64), 2048);
+        }
+        hipLaunchKernelGGL(mark_heads_kernel, dim3((unsigned)(ma.mark_blocks + verify_blocks)),
+                           dim3(kThreads), 0, stream, ma);
         CFGZIP_TRY(check_launch());
-        hipLaunchKernelGGL(mark_heads_kernel, grid_for(n), dim3(kThreads), 0, stream, n, anchor,
-                           w.min_id, w.is_head_token);
-        CFGZIP_TRY(check_launch());
-        CFGZIP_TRY((device_scan<false, false>(w.is_head_token, w.id_of_head_token, n, w.tile_tmp,
-                                              &w.ctr->num_classes, stream)));
-        hipLaunchKernelGGL(assign_classes_kernel, grid_for(n), dim3(kThreads), 0, stream, n, anchor,
-                           vals, w.min_id, w.id_of_head_token, w.rep_key, w.ctr, class_of_token,
-                           rep_of_class, num_classes_dev);
+        AssignArgs aa{};
+        aa.n = n;
+        aa.n_words = n_words;
+        aa.anchor = anchor;
+        aa.vals = vals;
+        aa.min_id = w.min_id;
+        aa.head_bits = w.head_bits;
+        aa.word_prefix = w.word_prefix;
+        aa.rep_key = w.rep_key;
+        aa.ctr = w.ctr;
+        aa.class_of_token = class_of_token;
+        aa.rep_of_class = rep_of_class;
+        aa.num_classes_dev = num_classes_dev;
+        const unsigned grid = (unsigned)ceil_div(n, kAssignTile);
+        if (n_words <= kRankLdsWords) {
+            const size_t dyn = (size_t)n_words * 8;
+            auto kern = assign_classes_kernel<true>;
+            if (dyn > 48 * 1024)
+                CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                         (int)dyn)));
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(kAssignThreads), dyn, stream, aa);
+        } else {
+            // large vocabularies: the word prefix sums by a scan of their own (w.cand is free here)
+            hipLaunchKernelGGL(popcount_words_kernel, grid_for(n_words), dim3(kThreads), 0, stream,
+                               w.head_bits, n_words, w.cand);
+            CFGZIP_TRY(check_launch());
+            CFGZIP_TRY((device_scan<false, false>(w.cand, w.word_prefix, n_words, w.tile_tmp,
+                                                  &w.ctr->num_classes, stream)));
+            hipLaunchKernelGGL(assign_classes_kernel<false>, dim3(grid), dim3(kAssignThreads), 0, stream, aa);
+        }
         return check_launch();
     };
     Counters host_ctr{};
@@ -1033,19 +1418,22 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         return check_hip(hipStreamSynchronize(stream));
     };
 
-    // 3. chain links; the numbering is enqueued right behind them on the assumption that no
-    //    link differs (then the segments are the classes), and redone in the rare other case
-    CFGZIP_TRY(verify_links());
-    CFGZIP_TRY(number_classes(w.seg_head));
+    // 4. the numbering is enqueued right behind the links on the assumption that none differs
+    //    (then the segments are the classes), and redone in the rare other case
+    CFGZIP_TRY(link());
+    CFGZIP_TRY(number_classes(w.seg_head, true));
     CFGZIP_TRY(read_counters());
-    if (source == FROM_STORE && host_ctr.store_unusable) {
-        // the workspace did not hold this call's walk vectors (or they had overflowed): start
-        // over from the chain set-up with the next source
+    if (source == FROM_STORE && host_ctr.store_state) {
+        // the workspace did not hold this call's walk vectors (or they had overflowed): take the
+        // links again from the next source; an overflowed store still has this call's tables
+        const bool tables_ok = host_ctr.store_state == kStoreOverflowed;
         source = sig ? FROM_ROWS : FROM_REWALK;
-        if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk());
-        CFGZIP_TRY(set_up_chains());
-        CFGZIP_TRY(verify_links());
-        CFGZIP_TRY(number_classes(w.seg_head));
+        if (source == FROM_REWALK) CFGZIP_TRY(prepare_rewalk(tables_ok));
+        hipLaunchKernelGGL(reset_numbering_kernel, grid_for(std::max(n, n_words)), dim3(kThreads), 0, stream,
+                           n, w.min_id, w.rep_key, w.head_bits, n_words, w.ctr);
+        CFGZIP_TRY(check_launch());
+        CFGZIP_TRY(link());
+        CFGZIP_TRY(number_classes(w.seg_head, true));
         CFGZIP_TRY(read_counters());
     }
     const int32_t collisions = host_ctr.unresolved;
@@ -1075,10 +1463,13 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
             CFGZIP_TRY(verify_pairs());
             CFGZIP_TRY(read_counters());
         }
-        hipLaunchKernelGGL(anchors_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.chain_start,
-                           w.head_pos, w.anchor, w.min_id, w.rep_key, w.is_head_token);
+        hipLaunchKernelGGL(anchors_kernel, grid_for(std::max(n, n_words)), dim3(kThreads), 0, stream, n,
+                           w.chain_start, w.head_pos, w.anchor, w.min_id, w.rep_key, w.head_bits, n_words);
         CFGZIP_TRY(check_launch());
-        CFGZIP_TRY(number_classes(w.anchor));
+        hipLaunchKernelGGL(class_minima_kernel, grid_for(n), dim3(kThreads), 0, stream, n, w.anchor, vals,
+                           tok_off, w.min_id, w.rep_key);
+        CFGZIP_TRY(check_launch());
+        CFGZIP_TRY(number_classes(w.anchor, false));
         CFGZIP_TRY(read_counters());
     }
     if (num_classes_host) *num_classes_host = host_ctr.num_classes;

@@ -184,7 +184,8 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
                 // image row of the kept vector (the walk wrote the vector and its zero padding)
                 const uint32_t m = threadIdx.x;
                 a.store.wrow[tcur + m] = (uint16_t)B.row[m];
-                if ((uint32_t)B.cnt[m] > stride) a.store.header->overflow = 1;
+                // (the empty token's identity vector is never looked at: its row says it all)
+                if ((uint32_t)B.cnt[m] > stride && B.row[m] != 256) a.store.header->overflow = 1;
             }
             if (a.sig_out) {
                 // sig[t][q] = w[idx[row][q]]

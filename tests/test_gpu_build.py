@@ -288,6 +288,25 @@ def test_signature_workspace_that_does_not_match_is_ignored(lib, cfg1, cfg2_smal
         c, r, C, _ = lib.cfgzip_build_classes(tb, to, tt, None, h, signatures_workspace=ws)
         assert C == len(want_r)
         assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+    print("case a workspace no larger than the smaller call needs", flush=True)
+    small = torch.zeros(raw.cfgzip_signatures_workspace_bytes(v1.V, 24), dtype=torch.uint8, device="cuda")
+    assert small.numel() < raw.cfgzip_signatures_workspace_bytes(v2.V, 256) // 4
+    lib.cfgzip_signatures(*vocab_dev(v1, t1), want_sig=False, workspace=small)
+    c, r, C, _ = lib.cfgzip_build_classes(tb, to, tt, None, h, signatures_workspace=small)
+    assert C == len(want_r)
+    assert (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+    print("case empty tokens next to an automaton of more states than a kept vector holds", flush=True)
+    rng = np.random.default_rng(78)
+    S = 700
+    table = _structured_table(rng, S, n_narrow=256)       # every column narrow: the vectors fit
+    toks = [b"", b"ab", b"", b"ba", b"ab", b"a", b"", b"b"] * 40
+    raw_ws = torch.zeros(raw.cfgzip_signatures_workspace_bytes(len(toks), S), dtype=torch.uint8, device="cuda")
+    ev = vocab_from_tokens(toks)
+    etb, eto, ett = vocab_dev(ev, table)
+    _, eh = lib.cfgzip_signatures(etb, eto, ett, want_sig=False, workspace=raw_ws)
+    hdr = raw_ws[:32].cpu().numpy().view(np.uint32)
+    assert hdr[1] == len(toks) and hdr[2] == S and hdr[4] == 0, "the empty tokens must not mark the store overflowed"
+    _check_build(lib, ev, table, stored=False, use_store=True)
     print("case overflow", flush=True)
     rng = np.random.default_rng(77)
     S = 1000
