@@ -30,9 +30,11 @@
  *
  * Conventions for every call
  *   - Every pointer is a DEVICE pointer owned by the caller unless the comment
- *     says "host".  The library allocates nothing, frees nothing and keeps no
+ *     says "host".  The library allocates no device memory, frees nothing and keeps no
  *     pointer after a call returns.  Scratch memory comes in as `ws`, sized by
- *     the matching *_workspace_bytes query (a host-only computation).
+ *     the matching *_workspace_bytes query (a host-only computation).  (cfgzip_build_classes
+ *     keeps 32 bytes of pinned host memory per calling thread, through which its counts reach
+ *     the host.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
  *     is enqueued on it; calls do not synchronise, except cfgzip_build_classes
  *     (it must hand the class count back to the host).

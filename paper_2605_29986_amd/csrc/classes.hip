@@ -44,7 +44,7 @@ constexpr int kSortTile = kSortThreads * kSortItems;  // keys per workgroup in t
 constexpr int kRadixBits = 10;
 constexpr int kBins = 1 << kRadixBits;
 static_assert(kSortThreads == kBins, "one thread per bin in the sort kernels");
-constexpr int kAggBits = 11;
+constexpr int kAggBits = 12;
 constexpr int kAggSlots = 1 << kAggBits;
 constexpr uint32_t kAggEmpty = 0xFFFFFFFFu;
 constexpr int kAssignThreads = 512;
@@ -498,14 +498,31 @@ __device__ __forceinline__ bool rows_differ(const uint16_t *__restrict__ sig, in
 // Per class (keyed by its anchor position): smallest token id and smallest (length, id).
 // Sorted neighbours mostly share a class, so a wave first reduces over its lanes of equal
 // anchor and issues one pair of atomics per distinct anchor.  Called by whole waves.
+// `ends` (or null): instead of issuing the atomics for the anchors of its first and of its last
+// lane, the wave leaves them there (entries 2 * wave and 2 * wave + 1) for flush_wave_ends, which
+// merges them over the workgroup: a class with many members spans whole workgroups, and thousands
+// of atomics on one address are served one after the other.
+struct WaveEnd {
+    int32_t anchor;  // -1: nothing
+    int32_t id;
+    uint64_t packed;
+};
+
 __device__ __forceinline__ void wave_class_minima(bool valid, int32_t anchor, int32_t tok, int64_t len,
-                                                  int32_t *min_id, uint64_t *rep_key) {
+                                                  int32_t *min_id, uint64_t *rep_key,
+                                                  WaveEnd *ends = nullptr) {
     if (len > 0x7FFFFFFF) len = 0x7FFFFFFF;
     if (len < 0) len = 0;
     const uint64_t packed = valid ? ((uint64_t)len << 32) | (uint32_t)tok : ~0ull;
     const int32_t a = valid ? anchor : -1;
     uint64_t todo = __ballot(valid);
-    const int lane = threadIdx.x & 63;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // anchors do not decrease along the sorted positions: the first and the last valid lane hold
+    // the two anchors that may continue in the neighbouring waves
+    const int first_lane = todo ? __ffsll((unsigned long long)todo) - 1 : 0;
+    const int last_lane = todo ? 63 - __clzll((unsigned long long)todo) : 0;
+    const int32_t a_first = __shfl(a, first_lane, 64), a_last = __shfl(a, last_lane, 64);
+    if (ends && lane < 2) ends[2 * wave + lane].anchor = -1;
     while (todo) {
         const int leader = __ffsll((unsigned long long)todo) - 1;
         const int32_t a0 = __shfl(a, leader, 64);
@@ -519,10 +536,43 @@ __device__ __forceinline__ void wave_class_minima(bool valid, int32_t anchor, in
             id = min(id, __shfl_xor(id, off, 64));
         }
         if (lane == leader) {
-            atomicMin(reinterpret_cast<unsigned long long *>(rep_key + a0), (unsigned long long)m);
-            atomicMin(min_id + a0, id);
+            if (ends && (a0 == a_first || a0 == a_last)) {
+                WaveEnd &e = ends[2 * wave + (a0 == a_first ? 0 : 1)];
+                e.anchor = a0;
+                e.id = id;
+                e.packed = m;
+            } else {
+                atomicMin(reinterpret_cast<unsigned long long *>(rep_key + a0), (unsigned long long)m);
+                atomicMin(min_id + a0, id);
+            }
         }
         todo &= ~__ballot(mine);
+    }
+}
+
+// After a __syncthreads(): one thread goes through the waves' end entries in order, merges
+// neighbours with the same anchor and issues the atomics.
+__device__ __forceinline__ void flush_wave_ends(const WaveEnd *ends, int n_entries, int32_t *min_id,
+                                                uint64_t *rep_key) {
+    if (threadIdx.x != 0) return;
+    int32_t cur = -1, id = 0x7FFFFFFF;
+    uint64_t m = ~0ull;
+    for (int e = 0; e <= n_entries; ++e) {
+        const int32_t an = e < n_entries ? ends[e].anchor : -2;
+        if (e < n_entries && an == -1) continue;
+        if (an != cur) {
+            if (cur >= 0) {
+                atomicMin(reinterpret_cast<unsigned long long *>(rep_key + cur), (unsigned long long)m);
+                atomicMin(min_id + cur, id);
+            }
+            cur = an;
+            id = 0x7FFFFFFF;
+            m = ~0ull;
+        }
+        if (e < n_entries) {
+            id = min(id, ends[e].id);
+            m = ends[e].packed < m ? ends[e].packed : m;
+        }
     }
 }
 
@@ -552,6 +602,7 @@ template <int SRC>
 __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     __shared__ int32_t wave_tot[kThreads / 64];
     __shared__ int32_t carry_s;
+    __shared__ WaveEnd ends[2 * (kThreads / 64)];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tile0 = blockIdx.x * kThreads;
     const int n = a.n;
@@ -608,10 +659,44 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     const bool verify = in && !start && SRC != SRC_NONE && store_state == 0;
     bool differs = false;
     uint32_t ra = 0, rb = 0;
-    if (SRC == SRC_STORE && verify) {
-        ra = store_row(a.store, ta);
-        rb = store_row(a.store, tb);
-        if (ra == rb && ra != 256u) differs = store_same_row_differ(a.store, ta, tb, ra);
+    if (SRC == SRC_STORE) {
+        if (verify) {
+            ra = store_row(a.store, ta);
+            rb = store_row(a.store, tb);
+        }
+        // Links inside one image row: the two walk vectors are compared by eight lanes together,
+        // 16 bytes each per round, so that a wave's reads fall into whole cache lines; the wave
+        // takes its 64 positions eight at a time and keeps all eight pairs' reads in flight.
+        const uint32_t stride = walk_store_stride(a.S);
+        const bool same = verify && ra == rb && ra != 256u;
+        const uint32_t n16 = same ? (min((uint32_t)a.store.T.nimg[ra], stride) + 7u) / 8u : 0u;
+        const uint32_t sub = lane & 7, group = lane >> 3;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        uint32_t dmask = 0;  // bit k: this lane saw a difference in the pair of position 8 k + group
+        for (uint32_t r = 0; r < kWalkStoreMaxStride / 64; ++r) {
+            if (__ballot(n16 > 8u * r) == 0ull) break;  // nobody's vector is that long
+            uint4 x[8], y[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int owner = k * 8 + (int)group;
+                const uint32_t pn = __shfl(n16, owner, 64);
+                const int32_t pa = __shfl(ta, owner, 64), pb = __shfl(tb, owner, 64);
+                const uint32_t u = sub + 8u * r;
+                const bool ok = u < pn;
+                x[k] = ok ? reinterpret_cast<const uint4 *>(a.store.store.wvec + (size_t)pa * stride)[u] : zero;
+                y[k] = ok ? reinterpret_cast<const uint4 *>(a.store.store.wvec + (size_t)pb * stride)[u] : zero;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if ((x[k].x != y[k].x) | (x[k].y != y[k].y) | (x[k].z != y[k].z) | (x[k].w != y[k].w))
+                    dmask |= 1u << k;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint64_t dm = __ballot((dmask >> k) & 1u);
+            // position 8 k + j was looked at by the eight lanes of group j
+            if ((lane >> 3) == k) differs = differs || ((dm >> (8 * (lane & 7))) & 0xFFull) != 0ull;
+        }
     }
     __syncthreads();
     int32_t seg = carry_s;
@@ -689,7 +774,9 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     }
     const uint64_t dm = __ballot(differs);
     if (dm && lane == 0) atomicAdd(&a.ctr->unresolved, (int)__popcll(dm));
-    wave_class_minima(in, seg, ta, len, a.min_id, a.rep_key);
+    wave_class_minima(in, seg, ta, len, a.min_id, a.rep_key, ends);
+    __syncthreads();
+    flush_wave_ends(ends, 2 * (kThreads / 64), a.min_id, a.rep_key);
 }
 
 // ---------------------------------------------------------------- verification of arbitrary pairs
@@ -1069,8 +1156,19 @@ struct AssignArgs {
     const int32_t *word_prefix;  // !LDS_RANK: set bits before each word of head_bits
     const uint64_t *rep_key;
     Counters *ctr;
+    Counters *host_ctr;  // pinned host memory: the counters as they stand when this kernel ends
     int32_t *class_of_token, *rep_of_class, *num_classes_dev;
 };
+
+// The host reads the counters from pinned memory after waiting for the stream: every kernel that
+// counts has finished before this one starts, so one thread copies them over.
+__device__ __forceinline__ void publish_counters(const AssignArgs &a, int32_t num_classes) {
+    if (!a.host_ctr) return;
+    a.host_ctr->unresolved = a.ctr->unresolved;
+    a.host_ctr->store_state = a.ctr->store_state;
+    a.host_ctr->other_rows = a.ctr->other_rows;
+    a.host_ctr->num_classes = num_classes;
+}
 
 // Class id of a class = number of classes whose smallest token id is smaller = set bits of
 // head_bits below its own.  LDS_RANK: every workgroup copies the bit vector into LDS and sums
@@ -1101,10 +1199,13 @@ __global__ __launch_bounds__(kAssignThreads) void assign_classes_kernel(AssignAr
         if (blockIdx.x == 0 && threadIdx.x == kAssignThreads - 1) {
             a.ctr->num_classes = (int32_t)run;  // the last thread's running sum is the total
             if (a.num_classes_dev) *a.num_classes_dev = (int32_t)run;
+            publish_counters(a, (int32_t)run);
         }
         __syncthreads();
-    } else if (blockIdx.x == 0 && threadIdx.x == 0 && a.num_classes_dev) {
-        *a.num_classes_dev = a.ctr->num_classes;  // written by the scan before this launch
+    } else if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const int32_t total = a.ctr->num_classes;  // written by the scan before this launch
+        if (a.num_classes_dev) *a.num_classes_dev = total;
+        publish_counters(a, total);
     }
     const int base = blockIdx.x * kAssignTile;
     int32_t anc[kAssignItems], tok[kAssignItems];
@@ -1199,6 +1300,25 @@ int launch_rewalk(Kern kern_lds, Kern kern_global, const RewalkArgs &a, int n_ch
     return check_launch();
 }
 
+// One small pinned host buffer per host thread (a thread runs one build at a time: the call
+// waits for its stream), allocated at the thread's first build and kept until the thread ends.
+struct PinnedCounters {
+    Counters *ptr = nullptr;
+    ~PinnedCounters() {
+        if (ptr) (void)hipHostFree(ptr);
+    }
+};
+int pinned_counters(Counters **out) {
+    static thread_local PinnedCounters slot;
+    if (!slot.ptr) {
+        void *p = nullptr;
+        CFGZIP_TRY(check_hip(hipHostMalloc(&p, sizeof(Counters), hipHostMallocDefault)));
+        slot.ptr = static_cast<Counters *>(p);
+    }
+    *out = slot.ptr;
+    return CFGZIP_OK;
+}
+
 }  // namespace
 }  // namespace cfgzip
 
@@ -1227,6 +1347,8 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
     BuildWorkspace w = carve_build_ws(ws, V, S);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    Counters *pinned = nullptr;
+    CFGZIP_TRY(pinned_counters(&pinned));
     const int n = V;
     const int nb = (int)ceil_div(n, kSortTile);
     const int n_words = (int)words_for(n);
@@ -1388,6 +1510,7 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         aa.word_prefix = w.word_prefix;
         aa.rep_key = w.rep_key;
         aa.ctr = w.ctr;
+        aa.host_ctr = pinned;
         aa.class_of_token = class_of_token;
         aa.rep_of_class = rep_of_class;
         aa.num_classes_dev = num_classes_dev;
@@ -1412,7 +1535,14 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         return check_launch();
     };
     Counters host_ctr{};
+    // after a numbering: its last kernel has left the counters in pinned memory
     auto read_counters = [&]() -> int {
+        CFGZIP_TRY(check_hip(hipStreamSynchronize(stream)));
+        host_ctr = *pinned;
+        return CFGZIP_OK;
+    };
+    // in the collision rounds, between numberings: a copy
+    auto copy_counters = [&]() -> int {
         CFGZIP_TRY(check_hip(hipMemcpyAsync(&host_ctr, w.ctr, sizeof(Counters),
                                             hipMemcpyDeviceToHost, stream)));
         return check_hip(hipStreamSynchronize(stream));
@@ -1447,7 +1577,7 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
                            w.mismatch, w.head_pos, w.resolved, w.ctr);
         CFGZIP_TRY(check_launch());
         CFGZIP_TRY(verify_pairs());
-        CFGZIP_TRY(read_counters());
+        CFGZIP_TRY(copy_counters());
         int64_t rounds = 0;
         while (host_ctr.unresolved > 0) {
             if (++rounds > (int64_t)V) return CFGZIP_E_COLLISION;  // cannot happen: a round settles >= 1
@@ -1461,7 +1591,7 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
                                w.resolved, w.seg_head, w.next_head, w.head_pos);
             CFGZIP_TRY(check_launch());
             CFGZIP_TRY(verify_pairs());
-            CFGZIP_TRY(read_counters());
+            CFGZIP_TRY(copy_counters());
         }
         hipLaunchKernelGGL(anchors_kernel, grid_for(std::max(n, n_words)), dim3(kThreads), 0, stream, n,
                            w.chain_start, w.head_pos, w.anchor, w.min_id, w.rep_key, w.head_bits, n_words);
