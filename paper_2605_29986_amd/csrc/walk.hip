@@ -23,74 +23,71 @@ namespace {
 // native 16-byte vector (the nontemporal builtins do not take HIP's uint4 struct)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// table read from L2 (S > 256): threads per workgroup and tokens per chunk
+constexpr int kWalkThreads = 256;
+constexpr int kWalkChunkTokens = 64;
+
 struct WalkArgs {
     const uint8_t *tok_bytes;
     const int64_t *tok_off;
     int32_t V;
     int32_t S;
     int32_t wcap;  // entries of w in LDS
+    int32_t chunk_tokens;  // consecutive tokens a workgroup takes at a time, <= kBatchTokens
     Tables T;
     WalkStoreView store;
     uint16_t *sig_out;   // [V][S] or null
     uint64_t *hash_out;  // [V] or null
 };
 
-// Tt[b][q] = table[q][b]; the workgroups of the last grid row clear the padding behind Tt.
-__global__ __launch_bounds__(256) void transpose_table_kernel(const uint16_t *__restrict__ table,
-                                                              uint16_t *__restrict__ Tt, int S,
-                                                              WalkStore *store, int V) {
-    __shared__ uint16_t tile[64][65];
-    if (blockIdx.y == 4) {
-        uint16_t *pad = Tt + (size_t)256 * S;
-        for (int i = blockIdx.x * 256 + threadIdx.x; i < kTablePad; i += gridDim.x * 256) pad[i] = 0;
-        if (store && blockIdx.x == 0 && threadIdx.x == 0) {
-            store->magic = kWalkStoreMagic;
-            store->V = V;
-            store->S = S;
-            store->stride = walk_store_stride(S);
-            store->overflow = 0;
-        }
-        return;
-    }
-    const int q0 = blockIdx.x * 64, b0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 x 4
-    for (int r = ty; r < 64; r += 4) {
-        const int q = q0 + r;
-        tile[r][tx] = q < S ? table[(size_t)q * 256 + b0 + tx] : (uint16_t)0;
-    }
-    __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int q = q0 + tx;
-        if (q < S) Tt[(size_t)(b0 + r) * S + q] = tile[tx][r];
-    }
-}
-
 constexpr int kStateWords = 65536 / 32;  // presence bitmap over every uint16 value
 constexpr int kAccCap = 4096;            // ranks whose multiplier sums are reduced in LDS
 
-// One workgroup per image row b: distinct states of column b (row 256: the identity map),
-// their ranks, and the multiplier sum of every rank.
-__global__ __launch_bounds__(1024) void image_tables_kernel(const uint16_t *__restrict__ Tt, int S,
-                                                            uint64_t seed, int32_t *nimg,
-                                                            uint16_t *img, uint16_t *idx,
-                                                            uint64_t *wsum) {
+// All tables of a call in one launch, one workgroup per image row b.  Rows 0..255: column b of
+// the caller's table becomes row b of Tt (each thread keeps to its own states q = tid, tid + 1024,
+// .., so what it reads back later is what it wrote), then the distinct states of the column, their
+// ranks, and the multiplier sum of every rank.  Row 256 (the identity map of the empty token)
+// also clears the padding behind Tt and writes the walk store's header.
+__global__ __launch_bounds__(1024) void tables_kernel(const uint16_t *__restrict__ table,
+                                                      uint16_t *Tt, int S, uint64_t seed,
+                                                      int32_t *nimg, uint16_t *img, uint16_t *idx,
+                                                      uint64_t *wsum, WalkStore *store, int V) {
     __shared__ uint32_t present[kStateWords];
     __shared__ uint32_t wprefix[kStateWords];
     __shared__ uint32_t wave_tot[16];
     __shared__ unsigned long long acc[kAccCap];
     const int b = blockIdx.x, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const uint16_t *col = Tt + (size_t)b * S;
-    auto state_of = [&](int q) -> uint32_t { return b < 256 ? (uint32_t)col[q] : (uint32_t)q; };
+    uint16_t *col = Tt + (size_t)b * S;  // rows 0..255 only
 
-    for (int i = tid; i < kStateWords; i += 1024) present[i] = 0;
-    for (int i = tid; i < kAccCap; i += 1024) acc[i] = 0ull;
+    for (int i = tid; i < kStateWords; i += 1024) present[i] = 0;  // a table entry may be any uint16
+    if (wsum)
+        for (int i = tid; i < kAccCap && i < S; i += 1024) acc[i] = 0ull;
     __syncthreads();
-    for (int q = tid; q < S; q += 1024) {
-        const uint32_t s = state_of(q);
-        atomicOr(&present[s >> 5], 1u << (s & 31));
+    if (b < 256) {
+        for (int q = tid; q < S; q += 1024) {
+            const uint32_t s = table[(size_t)q * 256 + b];
+            col[q] = (uint16_t)s;
+            // most states of a lexer's column are the same few: look before the atomic
+            if (!((present[s >> 5] >> (s & 31)) & 1u)) atomicOr(&present[s >> 5], 1u << (s & 31));
+        }
+    } else {
+        for (int w = tid; w < kStateWords; w += 1024) {
+            const int lo = w * 32;
+            present[w] = lo + 32 <= S ? 0xFFFFFFFFu : (lo < S ? (1u << (S - lo)) - 1u : 0u);
+        }
+        uint16_t *pad = Tt + (size_t)256 * S;
+        for (int i = tid; i < kTablePad; i += 1024) pad[i] = 0;
+        if (store && tid == 0) {
+            store->magic = kWalkStoreMagic;
+            store->V = V;
+            store->S = S;
+            store->stride = walk_store_stride(S);
+            store->overflow = 0;
+        }
     }
     __syncthreads();
+    auto state_of = [&](int q) -> uint32_t { return b < 256 ? (uint32_t)col[q] : (uint32_t)q; };
     // exclusive prefix of the per-word population counts; thread i owns words 2i, 2i+1
     const uint32_t c0 = __popc(present[2 * tid]), c1 = __popc(present[2 * tid + 1]);
     int incl = wave_inclusive_sum((int)(c0 + c1));
@@ -120,14 +117,39 @@ __global__ __launch_bounds__(1024) void image_tables_kernel(const uint16_t *__re
     if (wsum)
         for (uint32_t r = kAccCap + tid; r < n; r += 1024) wsum[(size_t)b * S + r] = 0ull;
     __syncthreads();
-    for (int q = tid; q < S; q += 1024) {
-        const uint32_t s = state_of(q);
+    for (int q0 = 0; q0 < S; q0 += 1024) {  // whole waves go round together: they vote below
+        const int q = q0 + tid;
+        const bool in = q < S;
+        const uint32_t s = in ? state_of(q) : 0u;
         const uint32_t r = wprefix[s >> 5] + __popc(present[s >> 5] & ((1u << (s & 31)) - 1u));
-        idx[(size_t)b * S + q] = (uint16_t)r;
+        if (in) idx[(size_t)b * S + q] = (uint16_t)r;
         if (wsum) {
-            const unsigned long long a = splitmix64_at(seed, (uint32_t)q) | 1ull;
-            if (r < kAccCap) atomicAdd(&acc[r], a);
-            else atomicAdd(reinterpret_cast<unsigned long long *>(wsum + (size_t)b * S + r), a);
+            const unsigned long long a = in ? (splitmix64_at(seed, (uint32_t)q) | 1ull) : 0ull;
+            // A lexer's column sends most states to one or two ranks; thousands of atomics on one
+            // LDS address are served one after the other.  The lanes that share the rank of the
+            // wave's first active lane add up in registers first, twice over.
+            bool pending = in;
+#pragma unroll 1
+            for (int round = 0; round < 2; ++round) {
+                const uint64_t todo = __ballot(pending);
+                if (!todo) break;
+                const int leader = __ffsll((unsigned long long)todo) - 1;
+                const uint32_t r0 = __shfl(r, leader, 64);
+                const bool mine = pending && r == r0;
+                if (__popcll(__ballot(mine)) < 4) break;  // not worth the reduction
+                unsigned long long sum = mine ? a : 0ull;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) sum += __shfl_xor(sum, off, 64);
+                if (mine) pending = false;
+                if (lane == leader) {
+                    if (r0 < kAccCap) atomicAdd(&acc[r0], sum);
+                    else atomicAdd(reinterpret_cast<unsigned long long *>(wsum + (size_t)b * S + r0), sum);
+                }
+            }
+            if (pending) {
+                if (r < kAccCap) atomicAdd(&acc[r], a);
+                else atomicAdd(reinterpret_cast<unsigned long long *>(wsum + (size_t)b * S + r), a);
+            }
         }
     }
     __syncthreads();
@@ -136,7 +158,7 @@ __global__ __launch_bounds__(1024) void image_tables_kernel(const uint16_t *__re
 }
 
 template <bool LDS_TABLE>
-__global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(WalkArgs a) {
+__global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_kernel(WalkArgs a) {
     extern __shared__ __align__(16) uint16_t dyn_lds[];  // [table S*256 if LDS_TABLE][w wcap]
     __shared__ Batch B;
     __shared__ uint8_t ldsb[kByteCap];
@@ -148,15 +170,16 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
         for (int i = threadIdx.x; i < n16; i += blockDim.x) dst[i] = src[i];
     }
     const uint16_t *tab = LDS_TABLE ? dyn_lds : a.T.Tt;
-    uint16_t *w = dyn_lds + (LDS_TABLE ? (size_t)S * 256 : 0);
+    // the walk vectors go through LDS only when rows are expanded from them
+    uint16_t *w = (LDS_TABLE || a.sig_out) ? dyn_lds + (LDS_TABLE ? (size_t)S * 256 : 0) : nullptr;
     const int lane = threadIdx.x & 63;
     const bool first_wave = threadIdx.x < 64;
     const bool vec = (S % 8) == 0 && (reinterpret_cast<uintptr_t>(a.sig_out) % 16) == 0;
 
-    const int64_t n_chunks = ((int64_t)a.V + kBatchTokens - 1) / kBatchTokens;
+    const int64_t n_chunks = ((int64_t)a.V + a.chunk_tokens - 1) / a.chunk_tokens;
     for (int64_t chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
-        const int64_t t_end = min((int64_t)a.V, (chunk + 1) * kBatchTokens);
-        int64_t tcur = chunk * kBatchTokens;
+        const int64_t t_end = min((int64_t)a.V, (chunk + 1) * a.chunk_tokens);
+        int64_t tcur = chunk * a.chunk_tokens;
         while (tcur < t_end) {  // workgroup-uniform
             __syncthreads();    // previous batch fully consumed (and the table loaded)
             if (first_wave) {
@@ -190,23 +213,36 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : 256) void signatures_kernel(Walk
             if (a.sig_out) {
                 // sig[t][q] = w[idx[row][q]]
                 if (vec) {
+                    // four 16-byte pieces per thread at a time: their index reads are in flight together
                     const uint32_t s8 = (uint32_t)S / 8;
                     const uint32_t items = (uint32_t)k * s8;
-                    for (uint32_t x = threadIdx.x; x < items; x += blockDim.x) {
-                        const uint32_t m = x / s8, q0 = (x - m * s8) * 8;
-                        const uint4 id = *reinterpret_cast<const uint4 *>(
-                            a.T.idx + (size_t)B.row[m] * S + q0);
-                        const uint16_t *wm = w + B.wstart[m];
-                        uint4 o;
-                        o.x = (uint32_t)wm[id.x & 0xFFFFu] | ((uint32_t)wm[id.x >> 16] << 16);
-                        o.y = (uint32_t)wm[id.y & 0xFFFFu] | ((uint32_t)wm[id.y >> 16] << 16);
-                        o.z = (uint32_t)wm[id.z & 0xFFFFu] | ((uint32_t)wm[id.z >> 16] << 16);
-                        o.w = (uint32_t)wm[id.w & 0xFFFFu] | ((uint32_t)wm[id.w >> 16] << 16);
-                        // written once, not read again by this call: keep it out of the caches
-                        // that hold the table
-                        const u32x4 ov = {o.x, o.y, o.z, o.w};
-                        __builtin_nontemporal_store(
-                            ov, reinterpret_cast<u32x4 *>(a.sig_out + (size_t)(tcur + m) * S + q0));
+                    constexpr int kAhead = 4;
+                    for (uint32_t x0 = threadIdx.x; x0 < items; x0 += kAhead * blockDim.x) {
+                        uint4 id[kAhead];
+#pragma unroll
+                        for (int u = 0; u < kAhead; ++u) {
+                            const uint32_t x = min(x0 + u * blockDim.x, items - 1);  // repeats the last past the end
+                            const uint32_t m = x / s8, q0 = (x - m * s8) * 8;
+                            id[u] = *reinterpret_cast<const uint4 *>(a.T.idx + (size_t)B.row[m] * S + q0);
+                        }
+#pragma unroll
+                        for (int u = 0; u < kAhead; ++u) {
+                            const uint32_t x = x0 + u * blockDim.x;
+                            if (x < items) {
+                                const uint32_t m = x / s8, q0 = (x - m * s8) * 8;
+                                const uint16_t *wm = w + B.wstart[m];
+                                uint4 o;
+                                o.x = (uint32_t)wm[id[u].x & 0xFFFFu] | ((uint32_t)wm[id[u].x >> 16] << 16);
+                                o.y = (uint32_t)wm[id[u].y & 0xFFFFu] | ((uint32_t)wm[id[u].y >> 16] << 16);
+                                o.z = (uint32_t)wm[id[u].z & 0xFFFFu] | ((uint32_t)wm[id[u].z >> 16] << 16);
+                                o.w = (uint32_t)wm[id[u].w & 0xFFFFu] | ((uint32_t)wm[id[u].w >> 16] << 16);
+                                // written once, not read again by this call: keep it out of the
+                                // caches that hold the table
+                                const u32x4 ov = {o.x, o.y, o.z, o.w};
+                                __builtin_nontemporal_store(
+                                    ov, reinterpret_cast<u32x4 *>(a.sig_out + (size_t)(tcur + m) * S + q0));
+                            }
+                        }
                     }
                 } else {
                     const uint32_t items = (uint32_t)k * (uint32_t)S;
@@ -269,11 +305,8 @@ SigWorkspace carve_sig_ws(void *ws, int32_t V, int32_t S) {
 int prepare_tables(const uint16_t *table, int32_t S, uint64_t hash_seed, bool want_wsum, int32_t V,
                    void *ws, Tables *out, WalkStoreView *store, hipStream_t stream) {
     SigWorkspace w = carve_sig_ws(ws, V, S);
-    hipLaunchKernelGGL(transpose_table_kernel, dim3((S + 63) / 64, 5), dim3(256), 0, stream, table,
-                       w.Tt, S, w.store.header, V);
-    CFGZIP_TRY(check_launch());
-    hipLaunchKernelGGL(image_tables_kernel, dim3(kImageRows), dim3(1024), 0, stream, w.Tt, S,
-                       hash_seed, w.nimg, w.img, w.idx, want_wsum ? w.wsum : nullptr);
+    hipLaunchKernelGGL(tables_kernel, dim3(kImageRows), dim3(1024), 0, stream, table, w.Tt, S, hash_seed,
+                       w.nimg, w.img, w.idx, want_wsum ? w.wsum : nullptr, w.store.header, V);
     CFGZIP_TRY(check_launch());
     out->Tt = w.Tt;
     out->nimg = w.nimg;
@@ -323,8 +356,9 @@ int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, 
 
     int n_cu = 256;
     CFGZIP_TRY(device_cu_count(&n_cu));
-    const int64_t n_chunks = ceil_div(V, kBatchTokens);
     const bool lds_table = (size_t)S * 512 <= kLdsTableLimit;
+    a.chunk_tokens = lds_table ? kBatchTokens : kWalkChunkTokens;
+    const int64_t n_chunks = ceil_div(V, a.chunk_tokens);
     // the signatures kernel walks one token at a time in the worst case: S entries suffice
     a.wcap = std::max(kMinWalkCap, (S + kWalkGroup - 1) / kWalkGroup * kWalkGroup);
     if (lds_table) {
@@ -339,7 +373,8 @@ int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, 
         const int64_t grid = std::min<int64_t>(ceil_div(n_chunks, 2), (int64_t)n_cu * per_cu);
         hipLaunchKernelGGL(kern, dim3((unsigned)std::max<int64_t>(1, grid)), dim3(1024), dyn, stream, a);
     } else {
-        const size_t dyn = (size_t)a.wcap * 2;
+        const size_t dyn = sig_out ? (size_t)a.wcap * 2 : 0;
+        if (!sig_out) a.wcap = 0x3FFFFFFF;  // no LDS buffer bounds a batch's walks
         auto kern = signatures_kernel<false>;
         if (dyn > 48 * 1024)
             CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -348,7 +383,7 @@ int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, 
         // one workgroup per chunk: the hardware hands out chunks as workgroups retire, which
         // balances chunks of very different cost
         const int64_t grid = std::min<int64_t>(n_chunks, 0x7FFFFFFF);
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), dyn, stream, a);
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kWalkThreads), dyn, stream, a);
     }
     return check_launch();
 }

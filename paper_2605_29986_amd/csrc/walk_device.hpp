@@ -218,6 +218,12 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
         uint32_t cur[kWalkGroup];
 #pragma unroll
         for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)T.img[e0 + u] : 0u;
+        // the hash multipliers are asked for now and used after the walk: off the critical path
+        uint64_t mult[kWalkGroup];
+        if (HASH) {
+#pragma unroll
+            for (int u = 0; u < kWalkGroup; ++u) mult[u] = j0 + u < n ? T.wsum[e0 + u] : 0ull;
+        }
         const uint32_t rem = B.len[m] > 0 ? (uint32_t)B.len[m] - 1u : 0u;
         const uint32_t lsrc = (uint32_t)B.boff[m] + 1u;                               // byte 1 in ldsb
         const uint8_t *gsrc = LDS_BYTES ? tok_bytes : tok_bytes + B.beg[m] + 1;       // or in memory
@@ -234,11 +240,13 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
 #pragma unroll
         for (int u = 0; u < kWalkGroup; ++u) {
             if (j0 + u >= n) cur[u] = 0;  // padding
-            else if (HASH) term += T.wsum[e0 + u] * (uint64_t)cur[u];
+            else if (HASH) term += mult[u] * (uint64_t)cur[u];
         }
-        uint16_t *dst = w + (uint32_t)B.wstart[m] + j0;
+        if (w) {  // null: the caller needs the end states only in the hash and in `keep`
+            uint16_t *dst = w + (uint32_t)B.wstart[m] + j0;
 #pragma unroll
-        for (int u = 0; u < kWalkGroup; ++u) dst[u] = (uint16_t)cur[u];
+            for (int u = 0; u < kWalkGroup; ++u) dst[u] = (uint16_t)cur[u];
+        }
         if (keep && j0 < keep_stride) {
             uint16_t *kd = keep + (size_t)m * keep_stride + j0;
 #pragma unroll
