@@ -107,8 +107,19 @@ def gather_ceiling(sizes):
             for (S, col), rec in best.items()}
 
 
-def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
-    """Times cfgzip_signatures + cfgzip_build_classes on the class-build workloads."""
+def random_automaton(seed: int, S: int) -> np.ndarray:
+    """Every transition drawn uniformly: no lexer structure at all (an input, seeded)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+    table[0, :] = 0
+    return table
+
+
+def bench_class_build(lib_mod, raw, torch, configs, repeats: int, random_tables: bool = False):
+    """Times cfgzip_signatures + cfgzip_build_classes on the class-build workloads.  With
+    random_tables the vocabulary of each workload meets an automaton of the same size whose
+    transitions are uniformly random: a byte then leaves about 0.63 S distinct states, the image
+    walk saves nothing, the kept walk vectors overflow and the builder walks again to compare."""
     import synthetic_inputs as si
     out = {}
     stream = torch.cuda.current_stream()
@@ -116,10 +127,12 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
         cfg = si.make_config(idx)
         vocab, table = cfg["vocab"], cfg["table"]
         V, S = vocab.V, cfg["S"]
+        if random_tables:
+            table = random_automaton(cfg["seed"] + 4242, S)
         tb = torch.from_numpy(vocab.tok_bytes).cuda()
         to = torch.from_numpy(vocab.tok_off).cuda()
         tt = torch.from_numpy(table).cuda()
-        stored = idx != 4  # the largest workload hashes on the fly and verifies by re-walking
+        stored = idx != 4 and not random_tables  # the largest workload hashes on the fly and verifies by re-walking
         sig = torch.empty((V, S), dtype=torch.uint16, device="cuda") if stored else None
         h = torch.empty((V,), dtype=torch.int64, device="cuda")
         c = torch.empty((V,), dtype=torch.int32, device="cuda")
@@ -142,7 +155,7 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
         for _ in range(repeats):
             t_sig.append(event_ms(run_sig, stream))
             t_all.append(event_ms(lambda: (run_sig(), run_build()), stream))
-        C = res["out"][2]
+        C, collisions = res["out"][2], res["out"][3]
         sum_len = int(vocab.tok_off[-1])
         ms_sig, ms_all = min(t_sig), min(t_all)
         # table reads: a plain walk from every state does S reads per token byte; the image walk
@@ -152,19 +165,33 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int):
         lens = np.diff(vocab.tok_off)
         first = np.where(lens > 0, vocab.tok_bytes[np.minimum(vocab.tok_off[:-1], max(sum_len - 1, 0))], 256)
         reads_done = int((nimg[first] * np.maximum(lens - 1, 0)).sum())
-        out[f"config{idx}"] = {
+        kept = bool((nimg[first] <= min(S, 256)).all())
+        entry = {
             "V": V, "S": S, "C": C, "V_over_C": round(V / C, 2), "sig_stored": stored,
+            "automaton": "uniformly random transitions" if random_tables else "lexer-like (synthetic_inputs)",
             "ms_signatures": round(ms_sig, 4), "ms_build_total": round(ms_all, 4),
+            "ms_grouping": round(ms_all - ms_sig, 4),
+            # EFFECTIVE rates: V * S token-state pairs get their end state per call, but the image
+            # walk does not perform V * S walks: it reads table_reads_image_walk table entries
+            # where a plain walk reads table_reads_plain_walk
             "walks_per_s": V * S / (ms_all * 1e-3),
             "walks_per_s_signatures_only": V * S / (ms_sig * 1e-3),
+            "walks_per_s_kind": "effective (token-state pairs resolved per second)",
             "table_reads_plain_walk": S * sum_len,
             "table_reads_image_walk": reads_done,
+            "table_reads_ratio": round(reads_done / max(S * sum_len, 1), 4),
+            "mean_image_states_per_token": round(float(nimg[first].mean()), 1),
+            "walk_vectors_kept_for_the_builder": kept,
+            "comparison_source": "kept walk vectors" if kept else "second walk (the kept vectors overflowed)",
+            "collisions": collisions,
             "sig_store_GBps": round(2 * V * S / (ms_sig * 1e-3) / 1e9, 1) if stored else None,
             # table reads of the image walk per second over the whole call (tables included)
             "table_reads_per_s": reads_done / (ms_sig * 1e-3),
         }
-        log(f"class build config {idx}: V={V} S={S} C={C} signatures {ms_sig:.3f} ms, "
-            f"total {ms_all:.3f} ms, {V * S / (ms_all * 1e-3):.3e} walks/s")
+        out[f"config{idx}"] = entry
+        log(f"class build config {idx}{' (random automaton)' if random_tables else ''}: V={V} S={S} C={C} "
+            f"signatures {ms_sig:.3f} ms, total {ms_all:.3f} ms, {V * S / (ms_all * 1e-3):.3e} effective walks/s "
+            f"({reads_done:.3e} of {S * sum_len:.3e} table reads done)")
         del sig, h, c, r, ws_sig, ws_bld
     return out
 
@@ -334,11 +361,13 @@ def cpu_baseline_decode(c5, r5, d, budget_s: float = 10.0, max_steps: int = 2000
                       f"OpenMP over batch rows"}
 
 
-def cpu_baseline_build(idx: int):
+def cpu_baseline_build(idx: int, random_table: bool = False):
     import oracle
     import synthetic_inputs as si
     cfg = si.make_config(idx)
     vocab, table = cfg["vocab"], cfg["table"]
+    if random_table:
+        table = random_automaton(cfg["seed"] + 4242, cfg["S"])
     t0 = time.perf_counter()
     sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
     t1 = time.perf_counter()
@@ -358,6 +387,8 @@ def main() -> int:
     ap.add_argument("--build-configs", type=str, default="2,3,4")
     ap.add_argument("--build-repeats", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-random-automata", action="store_true",
+                    help="skip the class build against uniformly random automata")
     ap.add_argument("--no-displacement", action="store_true",
                     help="skip the grammar and non-deterministic automaton pre-computation workloads")
     ap.add_argument("--mask-variants", action="store_true",
@@ -586,6 +617,18 @@ def main() -> int:
             v["frac_of_table_read_ceiling"] = round(v["table_reads_per_s"] / c["reads_per_s"], 4)
             log(f"S={v['S']}: {v['table_reads_per_s']:.3e} table reads/s in the signature call, "
                 f"pure-gather ceiling {c['reads_per_s']:.3e} ({v['frac_of_table_read_ceiling']:.1%})")
+    # the same vocabularies against automata without any structure (the image walk's worst case)
+    class_build_random = {}
+    if build_cfgs and not args.no_random_automata:
+        class_build_random = bench_class_build(lib_mod, raw, torch, [i for i in build_cfgs if i in (3, 4)],
+                                               args.build_repeats, random_tables=True)
+        for v in class_build_random.values():
+            c = ceilings.get(f"S{v['S']}_wave-uniform")
+            if c:
+                v["table_read_ceiling_per_s"] = c["reads_per_s"]
+                v["frac_of_table_read_ceiling"] = round(v["table_reads_per_s"] / c["reads_per_s"], 4)
+                log(f"random automaton S={v['S']}: {v['table_reads_per_s']:.3e} table reads/s in the signature "
+                    f"call, pure-gather ceiling {c['reads_per_s']:.3e} ({v['frac_of_table_read_ceiling']:.1%})")
     if ceilings:
         class_build["gather_ceiling"] = ceilings
 
@@ -615,6 +658,7 @@ def main() -> int:
                      "us_per_launch_cache_resident": round(mask_cached_ms * 1e3, 3)},
         "ms_per_step_two_calls": round(ms_per_step_two_calls, 6),
         "class_build": class_build,
+        "class_build_random_automaton": class_build_random,
         "engine": engine,
     }
     if not args.no_displacement:
@@ -629,6 +673,9 @@ def main() -> int:
         result["cpu_baseline"] = cpu_baseline_decode(c5_np, r5_np, d)
         for idx in build_cfgs:  # the oracle's class build on the same workloads, host cores
             result["class_build"][f"config{idx}"]["cpu_baseline"] = cpu_baseline_build(idx)
+        for key in class_build_random:
+            idx = int(key[len("config"):])
+            class_build_random[key]["cpu_baseline"] = cpu_baseline_build(idx, random_table=True)
     print(json.dumps(result), flush=True)
     return 0
 

@@ -215,6 +215,26 @@ def test_build_random_automaton_every_token_its_own_class(lib):
     _check_build(lib, vocab, table, stored=False)
 
 
+def test_random_automaton_at_scale(lib):
+    """An automaton without structure at the size of the measured ones: every byte leaves about
+    0.63 S distinct states, the image walk saves nothing, the walk vectors the signature call
+    keeps overflow, and the builder falls back to walking again (or to stored rows).  Config 2's
+    32,000 tokens against 1,024 uniformly random states; nearly every token is its own class."""
+    print("case random automaton S=1024 V=32000", flush=True)
+    rng = np.random.default_rng(4242)
+    S = 1024
+    table = rng.integers(0, S, size=(S, 256)).astype(np.uint16)
+    table[0, :] = 0
+    vocab = si.make_config(2)["vocab"]
+    assert vocab.V >= 32000
+    want_sig, _sig, _h = _check_signatures(lib, vocab, table)
+    assert np.unique(want_sig[:2000], axis=0).shape[0] > 1000
+    C, _coll = _check_build(lib, vocab, table, stored=False, use_store=True)   # store overflows -> second walk
+    assert C > vocab.V // 2
+    _check_build(lib, vocab, table, stored=False, use_store=False)
+    _check_build(lib, vocab, table, stored=True)
+
+
 def _structured_table(rng, S, n_narrow):
     """A random automaton in which `n_narrow` byte columns have few distinct states (like a
     lexer's) and the rest reject or scatter: mixes short and long walk vectors in one batch."""
