@@ -210,9 +210,12 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, gramm
     stream = torch.cuda.current_stream()
     tb = torch.from_numpy(vocab.tok_bytes).cuda()
     to = torch.from_numpy(vocab.tok_off).cuda()
-    gd = [torch.from_numpy(x).cuda() for x in (g.head, g.byte, g.length, g.body)]
+    gd = [torch.from_numpy(x).cuda() for x in g.arrays()]
     ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(V, g.N), dtype=torch.uint8, device="cuda")
-    ws_bld = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, lib_mod.DISP_ROW), dtype=torch.uint8,
+    # rows long enough for every set of these workloads (no token left in a class of its own for
+    # want of room); the shortest row length is timed beside it
+    ROW = 1024
+    ws_bld = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, ROW), dtype=torch.uint8,
                          device="cuda")
     c = torch.empty((V,), dtype=torch.int32, device="cuda")
     r = torch.empty((V,), dtype=torch.int32, device="cuda")
@@ -222,7 +225,7 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, gramm
         lib_mod.cfgzip_stack_adjacency(*gd, g.N, workspace=ws)
 
     def run_disp():
-        res["rows"] = lib_mod.cfgzip_displacements(tb, to, *gd, g.N, workspace=ws)
+        res["rows"] = lib_mod.cfgzip_displacements(tb, to, *gd, g.N, row_len=ROW, workspace=ws)
 
     def run_build():
         rows, hashes, _st = res["rows"]
@@ -241,7 +244,7 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, gramm
     out = {
         "workload": "%s in Greibach normal form (%d non-terminals, %d productions) x "
                     "config 3 vocabulary" % (name, g.N, g.P),
-        "V": V, "N": g.N, "P": g.P, "C": C, "V_over_C": round(V / C, 2),
+        "V": V, "N": g.N, "P": g.P, "C": C, "V_over_C": round(V / C, 2), "row_len": ROW,
         "overflow_tokens": int((status == lib_mod.DISP_OVERFLOW).sum()),
         "ms_stack_adjacency": round(min(t_adj), 4),
         "ms_displacements": round(min(t_disp), 4),     # adjacency included
@@ -251,20 +254,20 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, gramm
     }
     log(f"displacement ({name}): V={V} N={g.N} P={g.P} C={C} overflow={out['overflow_tokens']} adjacency "
         f"{min(t_adj):.3f} ms, displacements {min(t_disp):.3f} ms, with classes {ms_all:.3f} ms")
-    # the same with rows long enough for every set of this workload (no token left on its own)
-    ws_bld4 = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, 1024), dtype=torch.uint8, device="cuda")
+    # the same with the shortest rows the library takes: sets that need more become singletons
+    ws_bld4 = torch.empty(raw.cfgzip_build_classes_workspace_bytes(V, 256), dtype=torch.uint8, device="cuda")
 
-    def run_long():
-        rows, hashes, st = lib_mod.cfgzip_displacements(tb, to, *gd, g.N, row_len=1024, workspace=ws)
-        res["long"] = (lib_mod.cfgzip_build_classes(tb, to, None, rows, hashes, class_of_token=c,
-                                                    rep_of_class=r, workspace=ws_bld4), st)
+    def run_short():
+        rows, hashes, st = lib_mod.cfgzip_displacements(tb, to, *gd, g.N, row_len=256, workspace=ws)
+        res["short"] = (lib_mod.cfgzip_build_classes(tb, to, None, rows, hashes, class_of_token=c,
+                                                     rep_of_class=r, workspace=ws_bld4), st)
 
-    run_long(); torch.cuda.synchronize()
-    ms_long = min(event_ms(run_long, stream) for _ in range(repeats))
-    out["row_len_1024"] = {"C": res["long"][0][2], "ms_total_with_classes": round(ms_long, 4),
-                           "overflow_tokens": int((res["long"][1].cpu().numpy() == lib_mod.DISP_OVERFLOW).sum())}
-    log(f"displacement, 1024-entry rows: C={out['row_len_1024']['C']} overflow="
-        f"{out['row_len_1024']['overflow_tokens']} with classes {ms_long:.3f} ms")
+    run_short(); torch.cuda.synchronize()
+    ms_short = min(event_ms(run_short, stream) for _ in range(repeats))
+    out["row_len_256"] = {"C": res["short"][0][2], "ms_total_with_classes": round(ms_short, 4),
+                          "overflow_tokens": int((res["short"][1].cpu().numpy() == lib_mod.DISP_OVERFLOW).sum())}
+    log(f"displacement, 256-entry rows: C={out['row_len_256']['C']} overflow="
+        f"{out['row_len_256']['overflow_tokens']} with classes {ms_short:.3f} ms")
     if cpu_sample > 0:
         from oracle import displacement as D
         import oracle
@@ -272,7 +275,7 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, gramm
         toks = vocab.tokens()[:n]
         prods = g.productions()
         t0 = time.perf_counter()
-        rows, _h, _st = D.displacement_rows(toks, prods, seed=1)
+        rows, _h, _st = D.displacement_rows(toks, prods, seed=1, row_len=ROW)
         oracle.build_classes(rows, vocab.tok_off[:n + 1])
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",

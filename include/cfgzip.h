@@ -299,13 +299,15 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
 
 /*
  * General case: grammars in Greibach normal form (paper Section 2.1), every production
- *     A -> a B_1 .. B_n,   one terminal byte a, 0 <= n <= 4 non-terminals,
+ *     A -> a B_1 .. B_n,   one terminal byte a, n >= 0 non-terminals (any number),
  * non-terminals numbered 0 .. N-1, N <= 4096, given as flat arrays
- *     prod_head uint16 [P], prod_byte uint8 [P], prod_len uint8 [P] (n), prod_body uint16 [P][4]
- *     (prod_body 8-byte aligned)
+ *     prod_head uint16 [P], prod_byte uint8 [P],
+ *     prod_body_off int32 [P + 1], prod_body uint16 [body_total]
+ *     (the body of production i is prod_body[prod_body_off[i] .. prod_body_off[i+1]);
+ *      prod_body_off[0] = 0, prod_body_off[P] = body_total; prod_body may be NULL if body_total = 0)
  * in strictly ascending order of (byte, head, body), bodies compared symbol by symbol with a
- * proper prefix first (so no production occurs twice).  The order and the value ranges are
- * checked on the device; a grammar that breaks them is reported, not computed (below).
+ * proper prefix first (so no production occurs twice).  The order, the offsets and the value
+ * ranges are checked on the device; a grammar that breaks them is reported, not computed (below).
  *
  * cfgzip_stack_adjacency (paper Section 3.2.2, Appendix C): the relation "Y can be consumed
  * right before Z":  for every production A -> a B_1 .. B_n Z beta with n >= 1, every Y that is
@@ -325,10 +327,13 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
  *     in ascending order of (ni, no), then of the queue, then of the stack; the rest is 0.
  * hash_out[t] is the sum over the pairs of a 64-bit mix of the record and hash_seed (a
  * function of the set, for cfgzip_build_classes; never part of a result).
- * Bounds.  Every token is first taken with queue <= 12, stack <= 12 and at most 128 successors
- * of all live configurations per byte (counted before duplicates are dropped); a token that
- * crosses one of these is taken again with queue <= 32, stack <= 32, successors <= 256.  A
- * token that crosses those too, or whose set needs more than row_len entries, gets status
+ * Bounds.  With C_p the set of configurations (queue, stack, symbol consumed last) that
+ * Algorithm 1 reaches after p bytes of the token: no successor of a configuration of C_p may
+ * hold more than 32 queue symbols or more than 32 stack symbols, and the successors of C_p, one
+ * per configuration and applicable production (counted before equal ones fall together), may
+ * number at most 256.  (Tokens are first tried in smaller buffers and taken again when those do
+ * not suffice; which attempt finishes a token shows in no output.)  A token that breaks one of
+ * the bounds, or whose set needs more than row_len entries, gets status
  * CFGZIP_DISP_OVERFLOW and a row no other token has (0xFFFF, id & 0xFFFF, id >> 16, 0 ..):
  * it forms a class of its own.  With status CFGZIP_DISP_OK the row holds exactly the set
  * Algorithm 1 returns.
@@ -347,13 +352,15 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
 #define CFGZIP_DISP_BAD_GRAMMAR 2
 size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N);
 int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
-                           const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
-                           int32_t N, int32_t *adj_out, int32_t *invalid_out,
+                           const int32_t *prod_body_off, const uint16_t *prod_body,
+                           int32_t body_total, int32_t P, int32_t N,
+                           int32_t *adj_out, int32_t *invalid_out,
                            void *ws, size_t ws_bytes, void *stream);
 int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                          const uint16_t *prod_head, const uint8_t *prod_byte,
-                         const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
-                         int32_t N, uint16_t *rows_out, int32_t row_len, uint64_t *hash_out,
+                         const int32_t *prod_body_off, const uint16_t *prod_body,
+                         int32_t body_total, int32_t P, int32_t N,
+                         uint16_t *rows_out, int32_t row_len, uint64_t *hash_out,
                          int32_t *status_out, uint64_t hash_seed,
                          void *ws, size_t ws_bytes, void *stream);
 

@@ -91,9 +91,9 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_displacements_workspace_bytes.restype = sz
     lib.cfgzip_displacements_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_stack_adjacency.restype = ctypes.c_int
-    lib.cfgzip_stack_adjacency.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.cfgzip_stack_adjacency.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.cfgzip_displacements.restype = ctypes.c_int
-    lib.cfgzip_displacements.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, i32, vp, i32, vp, vp, u64,
+    lib.cfgzip_displacements.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, vp, i32, vp, vp, u64,
                                          vp, sz, vp]
     _lib = lib
     return lib
@@ -378,16 +378,21 @@ DISP_ROW = 256
 DISP_OK, DISP_OVERFLOW, DISP_BAD_GRAMMAR = 0, 1, 2
 
 
-def _grammar_args(prod_head, prod_byte, prod_len, prod_body):
+def _grammar_args(prod_head, prod_byte, prod_body_off, prod_body):
+    """Device pointers of a grammar given as flat arrays: heads uint16 [P], terminals uint8 [P],
+    body offsets int32 [P + 1], body symbols uint16 [>= body_off[P]] (the count of body symbols
+    is the caller's `prod_body.numel()` unless `prod_body` carries padding: see body_total)."""
     P = prod_head.numel()
-    if prod_body.shape != (P, 4):
-        raise ValueError("prod_body must have shape [P, 4]")
+    if prod_body_off.numel() != P + 1:
+        raise ValueError("prod_body_off must have P + 1 entries")
     return (_dev(prod_head, torch.uint16, "prod_head"), _dev(prod_byte, torch.uint8, "prod_byte"),
-            _dev(prod_len, torch.uint8, "prod_len"), _dev(prod_body, torch.uint16, "prod_body"), P)
+            _dev(prod_body_off, torch.int32, "prod_body_off"),
+            _dev(prod_body, torch.uint16, "prod_body") if prod_body.numel() else None, P)
 
 
 def cfgzip_stack_adjacency(prod_head: torch.Tensor, prod_byte: torch.Tensor,
-                           prod_len: torch.Tensor, prod_body: torch.Tensor, N: int, *,
+                           prod_body_off: torch.Tensor, prod_body: torch.Tensor, N: int, *,
+                           body_total: Optional[int] = None,
                            workspace: Optional[torch.Tensor] = None, stream=None):
     """(adj int32 [N, W(N)], invalid int32 [1]): bit Y of row Z <=> (Y, Z) stack-adjacent."""
     lib = load_library()
@@ -396,16 +401,18 @@ def cfgzip_stack_adjacency(prod_head: torch.Tensor, prod_byte: torch.Tensor,
     invalid = torch.empty((1,), dtype=torch.int32, device=dev)
     if workspace is None:
         workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(0, N), dev)
-    h, b, ln, bd, P = _grammar_args(prod_head, prod_byte, prod_len, prod_body)
-    rc = lib.cfgzip_stack_adjacency(h, b, ln, bd, P, N, adj.data_ptr(), invalid.data_ptr(),
+    h, b, off, bd, P = _grammar_args(prod_head, prod_byte, prod_body_off, prod_body)
+    total = prod_body.numel() if body_total is None else int(body_total)
+    rc = lib.cfgzip_stack_adjacency(h, b, off, bd, total, P, N, adj.data_ptr(), invalid.data_ptr(),
                                     workspace.data_ptr(), workspace.numel(), _stream(stream))
     _check("cfgzip_stack_adjacency", rc)
     return adj, invalid
 
 
 def cfgzip_displacements(tok_bytes: torch.Tensor, tok_off: torch.Tensor, prod_head: torch.Tensor,
-                         prod_byte: torch.Tensor, prod_len: torch.Tensor, prod_body: torch.Tensor,
-                         N: int, *, row_len: int = DISP_ROW, hash_seed: int = DEFAULT_HASH_SEED,
+                         prod_byte: torch.Tensor, prod_body_off: torch.Tensor, prod_body: torch.Tensor,
+                         N: int, *, body_total: Optional[int] = None, row_len: int = DISP_ROW,
+                         hash_seed: int = DEFAULT_HASH_SEED,
                          workspace: Optional[torch.Tensor] = None, stream=None):
     """(rows uint16 [V, row_len], hash int64 [V] holding uint64 bit patterns, status int32 [V])."""
     lib = load_library()
@@ -416,10 +423,11 @@ def cfgzip_displacements(tok_bytes: torch.Tensor, tok_off: torch.Tensor, prod_he
     status = torch.empty((V,), dtype=torch.int32, device=dev)
     if workspace is None:
         workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(V, N), dev)
-    h, b, ln, bd, P = _grammar_args(prod_head, prod_byte, prod_len, prod_body)
+    h, b, off, bd, P = _grammar_args(prod_head, prod_byte, prod_body_off, prod_body)
+    total = prod_body.numel() if body_total is None else int(body_total)
     rc = lib.cfgzip_displacements(
         _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
-        _dev(tok_off, torch.int64, "tok_off"), V, h, b, ln, bd, P, N,
+        _dev(tok_off, torch.int64, "tok_off"), V, h, b, off, bd, total, P, N,
         rows.data_ptr(), row_len, hashes.data_ptr(), status.data_ptr(),
         ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF),
         workspace.data_ptr(), workspace.numel(), _stream(stream))

@@ -30,7 +30,6 @@
 namespace cfgzip {
 namespace {
 
-constexpr int kMaxBody = 4;
 constexpr int kRowChunk = 256;                 // row entries staged in LDS at a time
 constexpr int kMaxRowLen = 4096;
 constexpr int kMaxSymbols = 4096;
@@ -46,6 +45,7 @@ constexpr int kIn2 = 32, kOut2 = 32, kFrontier2 = 256;
 constexpr int kFrontier2Narrow = 128;
 // the second pass keeps the current byte's productions and the relation in LDS when they fit
 constexpr int kStageCap = 128;      // productions of one terminal
+constexpr int kStageBodyCap = 512;  // body symbols of those productions together
 constexpr int kAdjLdsWords = 512;   // N * W(N) words: N <= 128
 
 // A record in LDS: ni, no, MAX_IN queue entries, MAX_OUT stack entries (top first), the symbol
@@ -79,10 +79,13 @@ struct GrammarHeader {
 struct Grammar {
     const uint16_t *head;
     const uint8_t *byte;
-    const uint8_t *len;
-    const uint16_t *body;  // [P][kMaxBody]
-    int P, N, W;           // W = words per bit row over the symbols
+    const int32_t *body_off;  // [P + 1]: the body of production i is body[body_off[i] .. body_off[i+1])
+    const uint16_t *body;
+    int P, N, W;              // W = words per bit row over the symbols
+    int body_total;           // body symbols the caller says there are (the offsets are checked against it)
 };
+
+__device__ __forceinline__ int body_len(const Grammar &g, int i) { return g.body_off[i + 1] - g.body_off[i]; }
 
 struct GrammarWorkspace {
     GrammarHeader *hdr;
@@ -126,30 +129,37 @@ __global__ void clear_words_kernel(uint32_t *p, size_t n) {
 }
 
 // (byte, head, body) of production i strictly below that of production j, bodies compared
-// symbol by symbol, a proper prefix first
+// symbol by symbol, a proper prefix first.  Both bodies lie inside the body array.
 __device__ bool production_less(const Grammar &g, int i, int j) {
     if (g.byte[i] != g.byte[j]) return g.byte[i] < g.byte[j];
     if (g.head[i] != g.head[j]) return g.head[i] < g.head[j];
-    const int li = min((int)g.len[i], kMaxBody), lj = min((int)g.len[j], kMaxBody);
-    for (int k = 0; k < min(li, lj); ++k) {
-        const uint16_t x = g.body[i * kMaxBody + k], y = g.body[j * kMaxBody + k];
-        if (x != y) return x < y;
-    }
+    const int li = body_len(g, i), lj = body_len(g, j);
+    const uint16_t *bi = g.body + g.body_off[i], *bj = g.body + g.body_off[j];
+    for (int k = 0; k < min(li, lj); ++k)
+        if (bi[k] != bj[k]) return bi[k] < bj[k];
     return li < lj;
 }
 
 // One thread per production and per symbol: checks the rules the other kernels rely on
-// (symbols < N, body length <= kMaxBody, strictly ascending order), finds where each
-// terminal's productions start, marks unary symbols and seeds the reachability matrix with
-// the identity and the edges head -> right-most body symbol (Appendix C's graph).
+// (body offsets ascending from 0 to the stated total, symbols < N, strictly ascending order of
+// the productions), finds where each terminal's productions start, marks unary symbols and
+// seeds the reachability matrix with the identity and the edges head -> right-most body symbol
+// (Appendix C's graph).
 __global__ void grammar_index_kernel(Grammar g, GrammarWorkspace w) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < g.N) atomicOr(&w.reach[0][(size_t)i * g.W + (i >> 5)], 1u << (i & 31));
     if (i >= g.P) return;
-    const int len = g.len[i];
-    bool ok = g.head[i] < g.N && len <= kMaxBody;
+    const int off = g.body_off[i], end = g.body_off[i + 1];
+    bool ok = g.head[i] < g.N && off >= 0 && end >= off && end <= g.body_total;
+    if (ok && i == 0) ok = off == 0;
+    if (ok && i == g.P - 1) ok = end == g.body_total;
+    if (ok && i > 0) {  // the body before this one must be in bounds before it is compared
+        const int poff = g.body_off[i - 1];
+        ok = poff >= 0 && poff <= off;
+    }
+    const int len = end - off;
     if (ok)
-        for (int k = 0; k < len; ++k) ok = ok && g.body[i * kMaxBody + k] < g.N;
+        for (int k = 0; k < len; ++k) ok = ok && g.body[off + k] < g.N;
     if (ok && i > 0) ok = production_less(g, i - 1, i);
     if (!ok) {
         w.hdr->invalid = 1;
@@ -165,7 +175,7 @@ __global__ void grammar_index_kernel(Grammar g, GrammarWorkspace w) {
     if (len == 0) {
         atomicOr(&w.unary[A >> 5], 1u << (A & 31));
     } else {
-        const int last = g.body[i * kMaxBody + len - 1];
+        const int last = g.body[end - 1];
         atomicOr(&w.reach[0][(size_t)A * g.W + (last >> 5)], 1u << (last & 31));
     }
 }
@@ -193,19 +203,19 @@ __global__ __launch_bounds__(64) void closure_round_kernel(const uint32_t *__res
 }
 
 // Appendix C: for a production A -> a B_1 .. B_n Z beta (n >= 1), every unary symbol reachable
-// from B_n is consumed right before Z.  One thread per (production, n, word).
+// from B_n is consumed right before Z.  One thread per (production, word); it goes through the
+// neighbouring pairs of the body.
 __global__ void adjacency_kernel(Grammar g, GrammarWorkspace w, const uint32_t *__restrict__ reach) {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int word = (int)(idx % g.W);
-    const int64_t pair = idx / g.W;
-    const int n = (int)(pair % (kMaxBody - 1)) + 1;
-    const int64_t i = pair / (kMaxBody - 1);
+    const int64_t i = idx / g.W;
     if (i >= g.P || w.hdr->invalid) return;
-    if (n >= (int)g.len[i]) return;
-    const int Bn = g.body[i * kMaxBody + n - 1], Z = g.body[i * kMaxBody + n];
-    if (Bn >= g.N || Z >= g.N) return;
-    const uint32_t bits = reach[(size_t)Bn * g.W + word] & w.unary[word];
-    if (bits) atomicOr(&w.adj[(size_t)Z * g.W + word], bits);
+    const int off = g.body_off[i], end = g.body_off[i + 1];
+    for (int p = off; p + 1 < end; ++p) {
+        const int Bn = g.body[p], Z = g.body[p + 1];
+        const uint32_t bits = reach[(size_t)Bn * g.W + word] & w.unary[word];
+        if (bits) atomicOr(&w.adj[(size_t)Z * g.W + word], bits);
+    }
 }
 
 __global__ void copy_words_kernel(const uint32_t *__restrict__ src, int32_t *__restrict__ dst,
@@ -230,7 +240,7 @@ int enqueue_grammar_tables(const Grammar &g, const GrammarWorkspace &w, hipStrea
                            w.reach[cur ^ 1], g.N, g.W);
         CFGZIP_TRY(check_launch());
     }
-    const int64_t items = (int64_t)g.P * (kMaxBody - 1) * g.W;
+    const int64_t items = (int64_t)g.P * g.W;
     hipLaunchKernelGGL(adjacency_kernel, dim3((unsigned)ceil_div(items, 256)), dim3(256), 0, stream,
                        g, w, w.reach[cur]);
     return check_launch();
@@ -351,10 +361,6 @@ __device__ int drop_duplicates(const Sym (*src)[R::kStride], Sym (*dst)[R::kStri
     return kept;
 }
 
-__device__ __forceinline__ uint32_t body_at(uint2 body, int k) {
-    return ((k < 2 ? body.x : body.y) >> (16 * (k & 1))) & 0xFFFFu;
-}
-
 // LDS of one workgroup (one wave)
 template <typename Sym, typename R, int FRONTIER, bool STAGE>
 struct TokenLds {
@@ -364,10 +370,11 @@ struct TokenLds {
     unsigned long long hash_sum;
     uint16_t fingerprint[FRONTIER];
     uint8_t empty_list[FRONTIER];  // positions of the live configurations with an empty stack
-    // STAGE only: the productions lo .. hi-1 of the byte being read, and the relation
-    __align__(8) uint2 sp_body[STAGE ? kStageCap : 1];
+    // STAGE only: the productions lo .. hi-1 of the byte being read (heads, body offsets
+    // relative to the first, body symbols), and the relation
+    uint16_t sp_body[STAGE ? kStageBodyCap : 1];
+    uint16_t sp_off[STAGE ? kStageCap + 1 : 1];
     uint16_t sp_head[STAGE ? kStageCap : 1];
-    uint8_t sp_len[STAGE ? kStageCap : 1];
     uint32_t adj[STAGE ? kAdjLdsWords : 1];
 };
 
@@ -403,19 +410,23 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
         const int ch = a.tok_bytes[p];
         const int lo = a.byte_off[ch], hi = a.byte_off[ch + 1];
         if (lane == 0) L.n_emit = 0;
-        const bool staged = STAGE && hi - lo <= kStageCap;  // the same for every lane
-        if (staged)
-            for (int i = lo + lane; i < hi; i += 64) {
-                L.sp_head[i - lo] = g.head[i];
-                L.sp_len[i - lo] = g.len[i];
-                L.sp_body[i - lo] = reinterpret_cast<const uint2 *>(g.body)[i];
-            }
+        const int body_lo = hi > lo ? g.body_off[lo] : 0;
+        const bool staged = STAGE && hi - lo <= kStageCap &&
+                            (hi > lo ? g.body_off[hi] - body_lo : 0) <= kStageBodyCap;  // the same for every lane
+        if (staged) {
+            for (int i = lo + lane; i < hi; i += 64) L.sp_head[i - lo] = g.head[i];
+            for (int i = lo + lane; i <= hi; i += 64) L.sp_off[i - lo] = (uint16_t)(g.body_off[i] - body_lo);
+            const int symbols = hi > lo ? g.body_off[hi] - body_lo : 0;
+            for (int x = lane; x < symbols; x += 64) L.sp_body[x] = g.body[body_lo + x];
+        }
         __syncthreads();
         auto head_of = [&](int i) -> int { return staged ? L.sp_head[i - lo] : g.head[i]; };
-        auto len_of = [&](int i) -> int { return staged ? L.sp_len[i - lo] : g.len[i]; };
-        auto body_of = [&](int i) -> uint2 {
-            return staged ? L.sp_body[i - lo] : reinterpret_cast<const uint2 *>(g.body)[i];
+        auto len_of = [&](int i) -> int {
+            return staged ? L.sp_off[i - lo + 1] - L.sp_off[i - lo] : g.body_off[i + 1] - g.body_off[i];
         };
+        // where the body of production i starts: an index into the staged symbols or into g.body
+        auto body_start = [&](int i) -> int { return staged ? L.sp_off[i - lo] : g.body_off[i]; };
+        auto body_sym = [&](int start, int k) -> int { return staged ? L.sp_body[start + k] : g.body[start + k]; };
 
         // pops: a lane per configuration (few productions per (terminal, head))
         for (int c = lane; c < n; c += 64) {
@@ -427,7 +438,7 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
             if (first < 0) continue;
             for (int i = first; i < hi && head_of(i) == top; ++i) {
                 const int len = len_of(i);
-                const uint2 body = body_of(i);
+                const int body = body_start(i);
                 const int slot = atomicAdd(&L.n_emit, 1);
                 if (no - 1 + len > MAX_OUT) {
                     L.crossed = 1;
@@ -439,7 +450,7 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
                     for (int k = 0; k < R::kWords; ++k) ow[k] = rw[k];
                     const int new_no = no - 1 + len;
                     for (int k = 0; k < new_no; ++k)
-                        o[R::kStackAt + k] = k < len ? (Sym)body_at(body, k) : rec[R::kStackAt + k - len + 1];
+                        o[R::kStackAt + k] = k < len ? (Sym)body_sym(body, k) : rec[R::kStackAt + k - len + 1];
                     if (len == 0) o[R::kStackAt + new_no] = 0;  // the stack got shorter by one
                     o[1] = (Sym)new_no;
                     o[R::kPrevAt] = (Sym)top;
@@ -460,9 +471,9 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
                     if (!((bits >> (prev & 31)) & 1u)) continue;
                 }
                 const int len = len_of(i);
-                const uint2 body = body_of(i);
+                const int body = body_start(i);
                 const int slot = atomicAdd(&L.n_emit, 1);
-                if (ni + 1 > MAX_IN) {
+                if (ni + 1 > MAX_IN || len > MAX_OUT) {
                     L.crossed = 1;
                 } else if (slot < FRONTIER) {
                     // the old record (its stack is empty) with A appended to the queue, the body
@@ -474,7 +485,7 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
                     o[0] = (Sym)(ni + 1);
                     o[1] = (Sym)len;
                     o[2 + ni] = (Sym)A;
-                    for (int k = 0; k < len; ++k) o[R::kStackAt + k] = (Sym)body_at(body, k);
+                    for (int k = 0; k < len; ++k) o[R::kStackAt + k] = (Sym)body_sym(body, k);
                     o[R::kPrevAt] = (Sym)A;
                 }
             }
@@ -651,11 +662,13 @@ int launch_displacements(const DisplacementArgs &a, int n_cu, hipStream_t stream
     return check_launch();
 }
 
-int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, const uint8_t *prod_len,
-                       const uint16_t *prod_body, int32_t P, int32_t N) {
-    if (!prod_head || !prod_byte || !prod_len || !prod_body) return CFGZIP_E_INVALID;
-    if (P <= 0 || N <= 0 || N > kMaxSymbols) return CFGZIP_E_INVALID;
-    if (!aligned_to(prod_head, 2) || !aligned_to(prod_body, 8)) return CFGZIP_E_INVALID;
+int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, const int32_t *prod_body_off,
+                       const uint16_t *prod_body, int32_t body_total, int32_t P, int32_t N) {
+    if (!prod_head || !prod_byte || !prod_body_off) return CFGZIP_E_INVALID;
+    if (P <= 0 || N <= 0 || N > kMaxSymbols || body_total < 0) return CFGZIP_E_INVALID;
+    if (body_total > 0 && !prod_body) return CFGZIP_E_INVALID;
+    if (!aligned_to(prod_head, 2) || !aligned_to(prod_body_off, 4) || !aligned_to(prod_body, 2))
+        return CFGZIP_E_INVALID;
     return CFGZIP_OK;
 }
 
@@ -670,16 +683,16 @@ extern "C" size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N) {
 }
 
 extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
-                                      const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
-                                      int32_t N, int32_t *adj_out, int32_t *invalid_out, void *ws,
-                                      size_t ws_bytes, void *stream_) {
-    CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_len, prod_body, P, N));
+                                      const int32_t *prod_body_off, const uint16_t *prod_body,
+                                      int32_t body_total, int32_t P, int32_t N, int32_t *adj_out,
+                                      int32_t *invalid_out, void *ws, size_t ws_bytes, void *stream_) {
+    CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_body_off, prod_body, body_total, P, N));
     if (!adj_out || !aligned_to(adj_out, 4) || !aligned_to(invalid_out, 4)) return CFGZIP_E_INVALID;
     if (!ws || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
     GrammarWorkspace w = carve_grammar_ws(ws, N, 0);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    Grammar g{prod_head, prod_byte, prod_len, prod_body, P, N, (int)ceil_div(N, 32)};
+    Grammar g{prod_head, prod_byte, prod_body_off, prod_body, P, N, (int)ceil_div(N, 32), body_total};
     CFGZIP_TRY(enqueue_grammar_tables(g, w, stream));
     const size_t words = (size_t)N * g.W;
     hipLaunchKernelGGL(copy_words_kernel, dim3((unsigned)std::min<int64_t>(1024, ceil_div((int64_t)words, 256))),
@@ -696,11 +709,11 @@ extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *
 
 extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                                     const uint16_t *prod_head, const uint8_t *prod_byte,
-                                    const uint8_t *prod_len, const uint16_t *prod_body, int32_t P,
-                                    int32_t N, uint16_t *rows_out, int32_t row_len,
-                                    uint64_t *hash_out, int32_t *status_out, uint64_t hash_seed,
-                                    void *ws, size_t ws_bytes, void *stream_) {
-    CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_len, prod_body, P, N));
+                                    const int32_t *prod_body_off, const uint16_t *prod_body,
+                                    int32_t body_total, int32_t P, int32_t N, uint16_t *rows_out,
+                                    int32_t row_len, uint64_t *hash_out, int32_t *status_out,
+                                    uint64_t hash_seed, void *ws, size_t ws_bytes, void *stream_) {
+    CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_body_off, prod_body, body_total, P, N));
     if (!tok_off || !rows_out || !hash_out || V <= 0) return CFGZIP_E_INVALID;
     if (row_len < kRowChunk || row_len > kMaxRowLen || row_len % kRowChunk) return CFGZIP_E_INVALID;
     if (!aligned_to(tok_off, 8) || !aligned_to(rows_out, 8) || !aligned_to(hash_out, 8) ||
@@ -710,7 +723,7 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
     GrammarWorkspace w = carve_grammar_ws(ws, N, V);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    Grammar g{prod_head, prod_byte, prod_len, prod_body, P, N, (int)ceil_div(N, 32)};
+    Grammar g{prod_head, prod_byte, prod_body_off, prod_body, P, N, (int)ceil_div(N, 32), body_total};
     CFGZIP_TRY(enqueue_grammar_tables(g, w, stream));
     DisplacementArgs a{};
     a.g = g;

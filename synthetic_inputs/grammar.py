@@ -1,8 +1,9 @@
 """Seeded context-free grammars in Greibach normal form over bytes, as flat arrays.
 
-Every production is  A -> a B_1 .. B_n  with one terminal byte `a` and at most
-MAX_BODY non-terminals.  Non-terminals are numbered 0 .. N-1.  Productions are unique and
-sorted by (byte, head, body): the order in which the GPU library expects them.
+Every production is  A -> a B_1 .. B_n  with one terminal byte `a` and any number of
+non-terminals.  Non-terminals are numbered 0 .. N-1.  Productions are unique and sorted by
+(byte, head, body): the order in which the GPU library expects them; bodies are stored one
+after the other with an offset array (CSR).
 
 Nothing here parses anything or computes displacements: these are inputs only.
 """
@@ -16,7 +17,6 @@ import numpy as np
 
 from .vocab import Vocab, vocab_from_tokens
 
-MAX_BODY = 4
 
 
 @dataclass
@@ -24,29 +24,40 @@ class Grammar:
     N: int                  # number of non-terminals
     head: np.ndarray        # uint16 [P]
     byte: np.ndarray        # uint8  [P]
-    length: np.ndarray      # uint8  [P]   body length 0..MAX_BODY
-    body: np.ndarray        # uint16 [P, MAX_BODY] (unused entries 0)
+    body_off: np.ndarray    # int32  [P + 1]: body of production i = body[body_off[i]:body_off[i+1]]
+    body: np.ndarray        # uint16 [body_off[P]]
 
     @property
     def P(self) -> int:
         return int(self.head.shape[0])
 
+    @property
+    def length(self) -> np.ndarray:
+        return np.diff(self.body_off)
+
+    def arrays(self):
+        """(head, byte, body_off, body): the argument order of the library."""
+        return self.head, self.byte, self.body_off, self.body
+
     def productions(self) -> List[Tuple[int, int, Tuple[int, ...]]]:
         """[(A, a, (B_1, .., B_n))] in the array order."""
         return [(int(self.head[i]), int(self.byte[i]),
-                 tuple(int(x) for x in self.body[i, :int(self.length[i])])) for i in range(self.P)]
+                 tuple(int(x) for x in self.body[int(self.body_off[i]):int(self.body_off[i + 1])]))
+                for i in range(self.P)]
 
 
 def grammar_from_productions(N: int, prods: Sequence[Tuple[int, int, Sequence[int]]]) -> Grammar:
     uniq = sorted({(int(a), int(A), tuple(int(x) for x in beta)) for (A, a, beta) in prods})
     P = len(uniq)
-    g = Grammar(N=N, head=np.zeros(P, np.uint16), byte=np.zeros(P, np.uint8),
-                length=np.zeros(P, np.uint8), body=np.zeros((P, MAX_BODY), np.uint16))
+    body_off = np.zeros(P + 1, np.int32)
+    body: List[int] = []
+    head, byte = np.zeros(P, np.uint16), np.zeros(P, np.uint8)
     for i, (a, A, beta) in enumerate(uniq):
-        assert 0 <= A < N and 0 <= a < 256 and len(beta) <= MAX_BODY and all(0 <= b < N for b in beta)
-        g.head[i], g.byte[i], g.length[i] = A, a, len(beta)
-        g.body[i, :len(beta)] = beta
-    return g
+        assert 0 <= A < N and 0 <= a < 256 and all(0 <= b < N for b in beta)
+        head[i], byte[i] = A, a
+        body += beta
+        body_off[i + 1] = len(body)
+    return Grammar(N=N, head=head, byte=byte, body_off=body_off, body=np.array(body, np.uint16))
 
 
 def make_random_gnf(seed: int, n_nt: int, alphabet: bytes, n_prod: int, max_body: int = 3,
@@ -193,7 +204,6 @@ def make_clike_gnf() -> Grammar:
 
     def add(head: str, byte, *body: str):
         b = byte if isinstance(byte, int) else ord(byte)
-        assert len(body) <= MAX_BODY, (head, byte, body)
         P.append((nt[head], b, tuple(nt[x] for x in body)))
 
     id_start = b"abcdefghijklmnopqrstuvwxyzABCDEFGHIJKLMNOPQRSTUVWXYZ_"

@@ -34,7 +34,7 @@ def lib():
 
 def _grammar_dev(g: Grammar):
     from gpu_util import dev
-    return dev(g.head), dev(g.byte), dev(g.length), dev(g.body)
+    return tuple(dev(x) for x in g.arrays())
 
 
 def _check_adjacency(lib, g: Grammar):
@@ -290,19 +290,58 @@ def test_unsorted_or_out_of_range_grammar_is_reported(lib):
 
     rows, status, invalid = run(g, g.N)
     assert invalid == 0 and (status != 2).all()
-    swapped = Grammar(g.N, g.head.copy(), g.byte.copy(), g.length.copy(), g.body.copy())
-    for arr in (swapped.head, swapped.byte, swapped.length, swapped.body):
-        arr[[3, 4]] = arr[[4, 3]]
-    rows, status, invalid = run(swapped, g.N)
+    prods = g.productions()
+    swapped = list(prods)
+    swapped[3], swapped[4] = swapped[4], swapped[3]
+
+    def flat(N, plist):     # the arrays in the order given, not sorted
+        off = np.zeros(len(plist) + 1, np.int32)
+        off[1:] = np.cumsum([len(p[2]) for p in plist])
+        body = np.array([x for p in plist for x in p[2]], np.uint16)
+        return Grammar(N, np.array([p[0] for p in plist], np.uint16), np.array([p[1] for p in plist], np.uint8),
+                       off, body)
+
+    rows, status, invalid = run(flat(g.N, swapped), g.N)
     assert invalid == 1 and (status == 2).all() and (rows == 0).all()
-    twice = Grammar(g.N, np.repeat(g.head, 2), np.repeat(g.byte, 2), np.repeat(g.length, 2),
-                    np.repeat(g.body, 2, axis=0))
-    assert run(twice, g.N)[2] == 1
+    assert run(flat(g.N, [p for p in prods for _ in range(2)]), g.N)[2] == 1      # every production twice
     rows, status, invalid = run(g, int(g.head.max()))        # a head >= N
     assert invalid == 1 and (status == 2).all()
-    long_body = Grammar(g.N, g.head.copy(), g.byte.copy(), g.length.copy(), g.body.copy())
-    long_body.length[0] = 5
-    assert run(long_body, g.N)[2] == 1
+    # body offsets that decrease, start above 0, or end short of the stated total
+    for damage in ("decrease", "start", "end"):
+        bad = Grammar(g.N, g.head, g.byte, g.body_off.copy(), g.body)
+        if damage == "decrease":
+            k = int(np.nonzero(g.length >= 2)[0][0])
+            bad.body_off[k + 1] = bad.body_off[k] - 1 if bad.body_off[k] > 0 else bad.body_off[k + 2] + 1
+        elif damage == "start":
+            bad.body_off[0] = 1
+        else:
+            bad.body_off[-1] -= 1
+        assert run(bad, g.N)[2] == 1, damage
+
+
+def test_long_bodies(lib):
+    """Productions with more body symbols than a fixed-width record would hold: six and nine
+    symbols, a body as long as the stack limit, and one beyond it (its tokens overflow)."""
+    print("case long bodies", flush=True)
+    a = ord("a")
+    prods = [(0, ord("s"), (1, 2, 3, 1, 2, 3)), (0, ord("t"), (1,) * 9), (0, ord("u"), (2,) * D.LIMIT_STACK),
+             (0, ord("v"), (2,) * (D.LIMIT_STACK + 1)), (1, a, ()), (2, ord("b"), ()), (3, ord("c"), ()),
+             (1, ord("x"), (3, 3, 3, 3, 3)), (3, ord("c"), (1,))]
+    g = grammar_from_productions(4, prods)
+    _check_adjacency(lib, g)
+    toks = [b"s", b"sa", b"sab", b"sabc", b"sabcab", b"sabcabc", b"t", b"t" + b"a" * 9, b"taaaa", b"u", b"ub",
+            b"u" + b"b" * D.LIMIT_STACK, b"v", b"vb", b"sx", b"sxccccc", b"sxcacccc", b"abc", b""]
+    rows, status, _ = _check_rows(lib, g, vocab_from_tokens(toks), row_len=512)
+    assert status[toks.index(b"v")] == 1 and status[toks.index(b"vb")] == 1
+    assert status[toks.index(b"u")] == 0 and status[toks.index(b"sabcabc")] == 0
+    assert D.decode_displacement(rows[0]) == frozenset({((0,), (1, 2, 3, 1, 2, 3))})
+    # random grammars with bodies of up to eight symbols
+    for seed in range(4):
+        g = make_random_gnf(900 + seed, n_nt=6 + seed, alphabet=b"abcd", n_prod=30 + 6 * seed, max_body=8,
+                            unary_fraction=0.5)
+        assert g.length.max() >= 6
+        _check_adjacency(lib, g)
+        _check_rows(lib, g, _all_tokens(b"abcd", 4))
 
 
 def test_argument_errors(lib):
@@ -387,7 +426,7 @@ def test_status_pointer_is_optional(lib):
     hashes2 = torch.zeros_like(hashes)
     ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(vocab.V, g.N), dtype=torch.uint8, device="cuda")
     rc = raw.cfgzip_displacements(tb.data_ptr(), to.data_ptr(), vocab.V, gd[0].data_ptr(), gd[1].data_ptr(),
-                                  gd[2].data_ptr(), gd[3].data_ptr(), g.P, g.N, rows2.data_ptr(), 256,
+                                  gd[2].data_ptr(), gd[3].data_ptr(), g.body.size, g.P, g.N, rows2.data_ptr(), 256,
                                   hashes2.data_ptr(), None, ctypes.c_uint64(SEED), ws.data_ptr(), ws.numel(),
                                   None)
     assert rc == 0

@@ -33,7 +33,7 @@ def test_whole_path_on_a_side_stream(cfg1):
     g, atoms = make_bracket_gnf(5)
     gv = make_token_strings(6, 400, atoms + b"()[]{},+-*", 5)
     gtb, gto = dev(gv.tok_bytes), dev(gv.tok_off)
-    gd = [dev(x) for x in (g.head, g.byte, g.length, g.body)]
+    gd = [dev(x) for x in g.arrays()]
     torch.cuda.synchronize()
 
     side = torch.cuda.Stream()

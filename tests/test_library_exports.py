@@ -64,19 +64,21 @@ def test_widening_rows_queries_and_argument_checks(raw):
     assert large >= small + 128256 * 4              # plus the list of tokens for the second pass
     assert q(0, 4096) >= 3 * 4096 * 128 * 4 + 256 * 4096 * 4   # three bit matrices and the index
     u64, sz = ctypes.c_uint64(0), ctypes.c_size_t(0)
-    assert raw.cfgzip_displacements(None, None, 1, None, None, None, None, 1, 1, None, 256, None, None, u64,
+    assert raw.cfgzip_displacements(None, None, 1, None, None, None, None, 0, 1, 1, None, 256, None, None, u64,
                                     None, sz, None) == -1
-    assert raw.cfgzip_stack_adjacency(None, None, None, None, 1, 1, None, None, None, sz, None) == -1
+    assert raw.cfgzip_stack_adjacency(None, None, None, None, 0, 1, 1, None, None, None, sz, None) == -1
     assert raw.cfgzip_nfa_signatures(None, None, 1, None, 1, None, None, u64, None) == -1
     # sizes are checked before any pointer is used
     buf = ctypes.create_string_buffer(4096)
     p = ctypes.cast(buf, ctypes.c_void_p)
     assert raw.cfgzip_nfa_signatures(p, p, 1, p, 257, p, None, u64, None) == -1
-    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 1, 5000, p, 256, p, None, u64, p, sz, None) == -1
+    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 2, 1, 5000, p, 256, p, None, u64, p, sz, None) == -1
+    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, -1, 1, 5, p, 256, p, None, u64, p, sz, None) == -1
+    assert raw.cfgzip_displacements(p, p, 1, p, p, p, None, 2, 1, 5, p, 256, p, None, u64, p, sz, None) == -1
     for bad_row_len in (0, 255, 300, 8192):
-        assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 1, 5, p, bad_row_len, p, None, u64, p, sz,
+        assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 2, 1, 5, p, bad_row_len, p, None, u64, p, sz,
                                         None) == -1
-    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 1, 5, p, 256, p, None, u64, None, sz, None) == -2
+    assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 2, 1, 5, p, 256, p, None, u64, None, sz, None) == -2
 
 
 def test_null_and_range_arguments_are_rejected_without_a_gpu(raw):

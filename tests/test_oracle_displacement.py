@@ -135,3 +135,15 @@ def test_right_linear_grammar_partition_equals_walk_partition(seed):
         assert disp[i] == frozenset(want)
     for a, b in itertools.combinations(range(len(toks)), 2):
         assert (disp[a] == disp[b]) == (c[a] == c[b])
+
+
+def test_bodies_of_any_length_are_pushed_whole():
+    """Section 2.1: beta in delta_G(a, A) iff A -> a beta, whatever the length of beta.  A
+    six-symbol body shows up whole on the output stack and is consumed symbol by symbol."""
+    prods = [("S", "s", ("A", "B", "C", "A", "B", "C")), ("A", "a", ()), ("B", "b", ()), ("C", "c", ())]
+    assert D.displacement("s", prods) == frozenset({(("S",), ("A", "B", "C", "A", "B", "C"))})
+    assert D.displacement("sab", prods) == frozenset({(("S",), ("C", "A", "B", "C"))})
+    assert D.displacement("sabcabc", prods) == frozenset({(("S",), ())})
+    assert D.displacement("sb", prods) == frozenset()
+    d = D.delta(prods)
+    assert D.pi("sabcabc", ("S",), d) == {()}

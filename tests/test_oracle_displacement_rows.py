@@ -267,7 +267,7 @@ def test_json_and_clike_grammars_accept_what_they_should():
         g = make()
         prods = g.productions()
         assert prods == sorted(set(prods), key=lambda p: (p[1], p[0], p[2])) and len(prods) == g.P
-        assert all(0 <= A < g.N and len(beta) <= 4 and all(0 <= b < g.N for b in beta) for A, _a, beta in prods)
+        assert all(0 <= A < g.N and all(0 <= b < g.N for b in beta) for A, _a, beta in prods)
         d = D.delta(prods)
         for text in good:
             assert () in D.pi(tuple(text), (0,), d), text
