@@ -150,9 +150,17 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int, random_tables:
                                                       rep_of_class=r, workspace=ws_bld,
                                                       signatures_workspace=ws_sig)
 
-        run_sig(); run_build(); torch.cuda.synchronize()  # warm-up
-        t_sig, t_all = [], []
+        # the same signatures by composition over token prefixes (Appendix A, Lemma 1)
+        ws_cmp = torch.empty(raw.cfgzip_signatures_composed_workspace_bytes(V, S), dtype=torch.uint8, device="cuda")
+
+        def run_sig_composed():
+            lib_mod.cfgzip_signatures(tb, to, tt, want_sig=stored, sig_out=sig, hash_out=h,
+                                      workspace=ws_cmp, composed=True)
+
+        run_sig_composed(); run_sig(); run_build(); torch.cuda.synchronize()  # warm-up
+        t_sig, t_all, t_cmp = [], [], []
         for _ in range(repeats):
+            t_cmp.append(event_ms(run_sig_composed, stream))
             t_sig.append(event_ms(run_sig, stream))
             t_all.append(event_ms(lambda: (run_sig(), run_build()), stream))
         C, collisions = res["out"][2], res["out"][3]
@@ -166,10 +174,25 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int, random_tables:
         first = np.where(lens > 0, vocab.tok_bytes[np.minimum(vocab.tok_off[:-1], max(sum_len - 1, 0))], 256)
         reads_done = int((nimg[first] * np.maximum(lens - 1, 0)).sum())
         kept = bool((nimg[first] <= min(S, 256)).all())
+        # table reads left when every token of four bytes or more starts from its longest prefix
+        # of two or three bytes that is itself a token (input statistics, for the report)
+        short = {bytes(vocab.token(t)) for t in np.nonzero((lens >= 2) & (lens <= 3))[0]}
+        reads_composed = 0
+        for t in range(V):
+            L = int(lens[t])
+            if L == 0:
+                continue
+            skip = 1
+            if L > 3:
+                tok = bytes(vocab.token(t))
+                skip = 3 if tok[:3] in short else (2 if tok[:2] in short else 1)
+            reads_composed += int(nimg[first[t]]) * (L - skip)
         entry = {
             "V": V, "S": S, "C": C, "V_over_C": round(V / C, 2), "sig_stored": stored,
             "automaton": "uniformly random transitions" if random_tables else "lexer-like (synthetic_inputs)",
             "ms_signatures": round(ms_sig, 4), "ms_build_total": round(ms_all, 4),
+            "ms_signatures_by_composition": round(min(t_cmp), 4),
+            "table_reads_by_composition": reads_composed,
             "ms_grouping": round(ms_all - ms_sig, 4),
             # EFFECTIVE rates: V * S token-state pairs get their end state per call, but the image
             # walk does not perform V * S walks: it reads table_reads_image_walk table entries
@@ -192,7 +215,9 @@ def bench_class_build(lib_mod, raw, torch, configs, repeats: int, random_tables:
         log(f"class build config {idx}{' (random automaton)' if random_tables else ''}: V={V} S={S} C={C} "
             f"signatures {ms_sig:.3f} ms, total {ms_all:.3f} ms, {V * S / (ms_all * 1e-3):.3e} effective walks/s "
             f"({reads_done:.3e} of {S * sum_len:.3e} table reads done)")
-        del sig, h, c, r, ws_sig, ws_bld
+        log(f"  signatures by composition over token prefixes: {min(t_cmp):.3f} ms "
+            f"({reads_composed:.3e} table reads)")
+        del sig, h, c, r, ws_sig, ws_bld, ws_cmp
     return out
 
 

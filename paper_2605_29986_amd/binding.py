@@ -62,6 +62,10 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_signatures_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_signatures.restype = ctypes.c_int
     lib.cfgzip_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp, sz, vp]
+    lib.cfgzip_signatures_composed_workspace_bytes.restype = sz
+    lib.cfgzip_signatures_composed_workspace_bytes.argtypes = [i32, i32]
+    lib.cfgzip_signatures_composed.restype = ctypes.c_int
+    lib.cfgzip_signatures_composed.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp, sz, vp]
     lib.cfgzip_signatures_static.restype = ctypes.c_int
     lib.cfgzip_signatures_static.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp]
     lib.cfgzip_build_classes_workspace_bytes.restype = sz
@@ -137,10 +141,14 @@ def cfgzip_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: tor
                       want_sig: bool = True, want_hash: bool = True,
                       hash_seed: int = DEFAULT_HASH_SEED, sig_out: Optional[torch.Tensor] = None,
                       hash_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                      stream=None) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+                      stream=None, composed: bool = False) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
     """sig[t][q] = state reached from q on bytes(t) (uint16 [V, S]) and/or its 64-bit hash
-    (int64 tensor holding the uint64 bit patterns, [V])."""
+    (int64 tensor holding the uint64 bit patterns, [V]).  composed=True calls
+    cfgzip_signatures_composed (same results; longer tokens continue the walk of a short token
+    that is a prefix of theirs); its workspace is larger."""
     lib = load_library()
+    entry = lib.cfgzip_signatures_composed if composed else lib.cfgzip_signatures
+    query = lib.cfgzip_signatures_composed_workspace_bytes if composed else lib.cfgzip_signatures_workspace_bytes
     V = tok_off.numel() - 1
     S = table.shape[0]
     dev = tok_off.device
@@ -148,10 +156,10 @@ def cfgzip_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: tor
         sig_out = torch.empty((V, S), dtype=torch.uint16, device=dev)
     if want_hash and hash_out is None:
         hash_out = torch.empty((V,), dtype=torch.int64, device=dev)
-    need = lib.cfgzip_signatures_workspace_bytes(V, S)
+    need = query(V, S)
     if workspace is None:
         workspace = _workspace(need, dev)
-    rc = lib.cfgzip_signatures(
+    rc = entry(
         _dev(tok_bytes, torch.uint8, "tok_bytes") if tok_bytes.numel() else None,
         _dev(tok_off, torch.int64, "tok_off"), V,
         _dev(table, torch.uint16, "table"), S,
@@ -159,7 +167,7 @@ def cfgzip_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, table: tor
         _dev(hash_out, torch.int64, "hash_out") if hash_out is not None else None,
         ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF),
         workspace.data_ptr(), workspace.numel(), _stream(stream))
-    _check("cfgzip_signatures", rc)
+    _check("cfgzip_signatures_composed" if composed else "cfgzip_signatures", rc)
     return sig_out, hash_out
 
 

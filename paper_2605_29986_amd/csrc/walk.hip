@@ -38,7 +38,17 @@ struct WalkArgs {
     WalkStoreView store;
     uint16_t *sig_out;   // [V][S] or null
     uint64_t *hash_out;  // [V] or null
+    // composition over token prefixes (null / 0: plain walks of all tokens)
+    const int32_t *parent;      // [V] id of a token of at most kComposePrefix bytes that is a proper prefix, or -1
+    const uint8_t *parent_len;  // [V] its length
+    int32_t phase;              // 1: only tokens of at most kComposePrefix bytes; 2: only the longer ones
 };
+
+// Composition (paper Appendix A, Lemma 1: the relation is a monoid homomorphism, so
+// sig(tu) = sig(u) o sig(t)): a token may continue the walk of a shorter token that is a prefix of
+// it.  Prefixes of up to this many bytes are used; the short tokens are walked in a first launch,
+// the others, starting from their prefix's kept vector, in a second.
+constexpr int kComposePrefix = 3;
 
 constexpr int kStateWords = 65536 / 32;  // presence bitmap over every uint16 value
 constexpr int kAccCap = 4096;            // ranks whose multiplier sums are reduced in LDS
@@ -185,12 +195,23 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_ke
             if (first_wave) {
                 const int64_t t = tcur + lane;
                 int64_t beg = 0, len = -1;
+                int32_t parent = -1, parent_len = 0;
                 if (t < t_end) {
                     beg = a.tok_off[t];
                     len = a.tok_off[t + 1] - beg;
                     if (len < 0) len = 0;  // offsets must not decrease; stay in bounds if they do
+                    if (a.phase == 2 && a.parent) {
+                        parent = a.parent[t];
+                        parent_len = a.parent_len[t];
+                    }
                 }
-                batch_fill(B, a.T, a.tok_bytes, beg, len, a.wcap, 1, 1);
+                // a token that belongs to the other launch keeps its slot, with no walks: its
+                // outputs are not touched
+                const bool other_launch = (a.phase == 1 && len > kComposePrefix) ||
+                                          (a.phase == 2 && len <= kComposePrefix);
+                const int kk = batch_fill(B, a.T, a.tok_bytes, beg, other_launch ? -1 : len, a.wcap, 1, 1,
+                                          parent, parent_len);
+                if (lane < kk) B.aux[lane] = (len >= 0 && !other_launch) ? 1 : 0;
             }
             __syncthreads();
             const int k = (int)min((int64_t)B.k, t_end - tcur);
@@ -199,11 +220,14 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_ke
             // the walk vectors are also kept for the class builder: token t at t * stride
             const uint32_t stride = walk_store_stride(S);
             uint16_t *keep = a.store.header ? a.store.wvec + (size_t)tcur * stride : nullptr;
-            if (a.hash_out) batch_walk<true>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
-            else batch_walk<false>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride);
+            // launch 2 of a composed call: slots with a parent start from its kept vector
+            const uint16_t *kept = (a.phase == 2 && a.parent && a.store.header) ? a.store.wvec : nullptr;
+            if (a.hash_out) batch_walk<true>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride, kept);
+            else batch_walk<false>(a.T, tab, S, a.tok_bytes, B, ldsb, w, keep, stride, kept);
             __syncthreads();
-            if (a.hash_out && (int)threadIdx.x < k) a.hash_out[tcur + threadIdx.x] = B.hash[threadIdx.x];
-            if (a.store.header && (int)threadIdx.x < k) {
+            if (a.hash_out && (int)threadIdx.x < k && B.aux[threadIdx.x])
+                a.hash_out[tcur + threadIdx.x] = B.hash[threadIdx.x];
+            if (a.store.header && (int)threadIdx.x < k && B.aux[threadIdx.x]) {
                 // image row of the kept vector (the walk wrote the vector and its zero padding)
                 const uint32_t m = threadIdx.x;
                 a.store.wrow[tcur + m] = (uint16_t)B.row[m];
@@ -228,7 +252,7 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_ke
 #pragma unroll
                         for (int u = 0; u < kAhead; ++u) {
                             const uint32_t x = x0 + u * blockDim.x;
-                            if (x < items) {
+                            if (x < items && B.aux[x / s8]) {
                                 const uint32_t m = x / s8, q0 = (x - m * s8) * 8;
                                 const uint16_t *wm = w + B.wstart[m];
                                 uint4 o;
@@ -248,6 +272,7 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_ke
                     const uint32_t items = (uint32_t)k * (uint32_t)S;
                     for (uint32_t x = threadIdx.x; x < items; x += blockDim.x) {
                         const uint32_t m = x / (uint32_t)S, q = x - m * (uint32_t)S;
+                        if (!B.aux[m]) continue;
                         a.sig_out[(size_t)(tcur + m) * S + q] =
                             w[B.wstart[m] + a.T.idx[(size_t)B.row[m] * S + q]];
                     }
@@ -256,6 +281,96 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_ke
             tcur += k;
         }
     }
+}
+
+// ---- composition over token prefixes: which short token is a prefix of which long one ----------
+// Tokens of 2 .. kComposePrefix bytes go into an open-addressing table keyed by their bytes
+// (length and bytes fit a 32-bit key, so a key match is a byte-string match); every longer token
+// then looks its own prefixes up, longest first.
+constexpr unsigned long long kPrefixEmpty = ~0ull;
+
+struct ComposeArgs {
+    const uint8_t *tok_bytes;
+    const int64_t *tok_off;
+    int32_t V;
+    unsigned long long *slots;  // [capacity]: (key << 32) | token id, or kPrefixEmpty
+    uint32_t capacity_mask;     // capacity - 1, capacity a power of two
+    int32_t *parent;            // [V]
+    uint8_t *parent_len;        // [V]
+};
+
+__device__ __forceinline__ uint32_t prefix_key(const uint8_t *p, int len) {
+    uint32_t key = (uint32_t)len << 24;
+    for (int k = 0; k < len; ++k) key |= (uint32_t)p[k] << (8 * (2 - k));
+    return key;
+}
+__device__ __forceinline__ uint32_t prefix_slot(uint32_t key, uint32_t mask) {
+    return (key * 2654435761u >> 7) & mask;
+}
+
+__global__ void prefix_clear_kernel(unsigned long long *slots, uint32_t capacity) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < capacity; i += gridDim.x * blockDim.x)
+        slots[i] = kPrefixEmpty;
+}
+
+// a thread per token; the short ones claim a slot (the first of several equal byte strings wins)
+__global__ void prefix_insert_kernel(ComposeArgs a) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.V) return;
+    const int64_t beg = a.tok_off[t], len = a.tok_off[t + 1] - beg;
+    a.parent[t] = -1;
+    a.parent_len[t] = 0;
+    if (len < 2 || len > kComposePrefix) return;
+    const uint32_t key = prefix_key(a.tok_bytes + beg, (int)len);
+    const unsigned long long mine = ((unsigned long long)key << 32) | (uint32_t)t;
+    uint32_t s = prefix_slot(key, a.capacity_mask);
+    for (uint32_t probes = 0; probes <= a.capacity_mask; ++probes, s = (s + 1) & a.capacity_mask) {
+        const unsigned long long old = atomicCAS(&a.slots[s], kPrefixEmpty, mine);
+        if (old == kPrefixEmpty || (uint32_t)(old >> 32) == key) return;  // claimed, or already there
+    }
+}
+
+// a thread per token; the long ones look their prefixes up
+__global__ void prefix_find_kernel(ComposeArgs a) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.V) return;
+    const int64_t beg = a.tok_off[t], len = a.tok_off[t + 1] - beg;
+    if (len <= kComposePrefix) return;
+    for (int k = kComposePrefix; k >= 2; --k) {
+        const uint32_t key = prefix_key(a.tok_bytes + beg, k);
+        uint32_t s = prefix_slot(key, a.capacity_mask);
+        for (uint32_t probes = 0; probes <= a.capacity_mask; ++probes, s = (s + 1) & a.capacity_mask) {
+            const unsigned long long e = a.slots[s];
+            if (e == kPrefixEmpty) break;
+            if ((uint32_t)(e >> 32) == key) {
+                a.parent[t] = (int32_t)(uint32_t)e;
+                a.parent_len[t] = (uint8_t)k;
+                return;
+            }
+        }
+    }
+}
+
+// the composition's own part of the workspace, behind the signature workspace
+struct ComposeWorkspace {
+    unsigned long long *slots;
+    uint32_t capacity;
+    int32_t *parent;
+    uint8_t *parent_len;
+    size_t bytes;
+};
+
+ComposeWorkspace carve_compose_ws(void *ws, int32_t V) {
+    Carver c(ws);
+    ComposeWorkspace w;
+    uint32_t cap = 1024;
+    while (cap < 2u * (uint32_t)V) cap <<= 1;
+    w.capacity = cap;
+    w.slots = c.take<unsigned long long>(cap);
+    w.parent = c.take<int32_t>((size_t)V);
+    w.parent_len = c.take<uint8_t>((size_t)V);
+    w.bytes = c.used;
+    return w;
 }
 
 constexpr size_t kLdsTableLimit = 128 * 1024;  // S <= 256
@@ -342,10 +457,26 @@ namespace {
 
 // Shared by both entry points: `ws` holds at least sig_workspace_bytes(store_V, S) bytes;
 // store_V = V keeps the walk vectors for the class builder, store_V = 0 keeps nothing.
+// `compose_ws` (or null): the composition's part of the workspace; the tokens are then walked
+// in two launches, the longer ones starting from the kept vector of a short token that is a
+// prefix of theirs (needs store_V = V).
 int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, const uint16_t *table,
                    int32_t S, uint16_t *sig_out, uint64_t *hash_out, uint64_t hash_seed, void *ws,
-                   int32_t store_V, hipStream_t stream) {
+                   int32_t store_V, hipStream_t stream, void *compose_ws = nullptr) {
     WalkArgs a{};
+    if (compose_ws) {
+        const ComposeWorkspace cw = carve_compose_ws(compose_ws, V);
+        ComposeArgs ca{tok_bytes, tok_off, V, cw.slots, cw.capacity - 1, cw.parent, cw.parent_len};
+        hipLaunchKernelGGL(prefix_clear_kernel, dim3((unsigned)std::min<int64_t>(1024, ceil_div(cw.capacity, 256))),
+                           dim3(256), 0, stream, cw.slots, cw.capacity);
+        CFGZIP_TRY(check_launch());
+        hipLaunchKernelGGL(prefix_insert_kernel, dim3((unsigned)ceil_div(V, 256)), dim3(256), 0, stream, ca);
+        CFGZIP_TRY(check_launch());
+        hipLaunchKernelGGL(prefix_find_kernel, dim3((unsigned)ceil_div(V, 256)), dim3(256), 0, stream, ca);
+        CFGZIP_TRY(check_launch());
+        a.parent = cw.parent;
+        a.parent_len = cw.parent_len;
+    }
     a.tok_bytes = tok_bytes;
     a.tok_off = tok_off;
     a.V = V;
@@ -371,7 +502,11 @@ int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, 
         // loading the table costs a workgroup about as much as walking a few batches
         const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(2, (150 * 1024) / (dyn + 8192)));
         const int64_t grid = std::min<int64_t>(ceil_div(n_chunks, 2), (int64_t)n_cu * per_cu);
-        hipLaunchKernelGGL(kern, dim3((unsigned)std::max<int64_t>(1, grid)), dim3(1024), dyn, stream, a);
+        for (int phase = compose_ws ? 1 : 0; phase <= (compose_ws ? 2 : 0); ++phase) {
+            a.phase = phase;
+            hipLaunchKernelGGL(kern, dim3((unsigned)std::max<int64_t>(1, grid)), dim3(1024), dyn, stream, a);
+            CFGZIP_TRY(check_launch());
+        }
     } else {
         const size_t dyn = sig_out ? (size_t)a.wcap * 2 : 0;
         if (!sig_out) a.wcap = 0x3FFFFFFF;  // no LDS buffer bounds a batch's walks
@@ -383,9 +518,13 @@ int run_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V, 
         // one workgroup per chunk: the hardware hands out chunks as workgroups retire, which
         // balances chunks of very different cost
         const int64_t grid = std::min<int64_t>(n_chunks, 0x7FFFFFFF);
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kWalkThreads), dyn, stream, a);
+        for (int phase = compose_ws ? 1 : 0; phase <= (compose_ws ? 2 : 0); ++phase) {
+            a.phase = phase;
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kWalkThreads), dyn, stream, a);
+            CFGZIP_TRY(check_launch());
+        }
     }
-    return check_launch();
+    return CFGZIP_OK;
 }
 
 int check_signature_args(const int64_t *tok_off, int32_t V, const uint16_t *table, int32_t S,
@@ -441,6 +580,23 @@ extern "C" int cfgzip_signatures(const uint8_t *tok_bytes, const int64_t *tok_of
     // tok_bytes may be null only if every token is empty; the kernels never read it then.
     return run_signatures(tok_bytes, tok_off, V, table, S, sig_out, hash_out, hash_seed, ws, V,
                           static_cast<hipStream_t>(stream_));
+}
+
+extern "C" size_t cfgzip_signatures_composed_workspace_bytes(int32_t V, int32_t S) {
+    if (V <= 0 || S <= 0 || S > 65536) return 0;
+    return sig_workspace_bytes(V, S) + carve_compose_ws(nullptr, V).bytes;
+}
+
+extern "C" int cfgzip_signatures_composed(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
+                                          const uint16_t *table, int32_t S, uint16_t *sig_out,
+                                          uint64_t *hash_out, uint64_t hash_seed, void *ws,
+                                          size_t ws_bytes, void *stream_) {
+    CFGZIP_TRY(check_signature_args(tok_off, V, table, S, sig_out, hash_out));
+    const size_t sig_bytes = sig_workspace_bytes(V, S);
+    if (!ws || !aligned_to(ws, 256) || ws_bytes < sig_bytes + carve_compose_ws(nullptr, V).bytes)
+        return CFGZIP_E_WORKSPACE;
+    return run_signatures(tok_bytes, tok_off, V, table, S, sig_out, hash_out, hash_seed, ws, V,
+                          static_cast<hipStream_t>(stream_), static_cast<char *>(ws) + sig_bytes);
 }
 
 extern "C" int cfgzip_signatures_static(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,

@@ -122,6 +122,10 @@ struct Batch {
     int32_t len[kBatchTokens];
     int32_t row[kBatchTokens];  // image row: first byte, or 256 for an empty byte string
     int32_t aux[kBatchTokens];  // free for the kernel that fills the batch
+    // composition (sig(tu) = sig(u) o sig(t)): a slot may start from the kept walk vector of a
+    // token that is a proper prefix of its own byte string instead of from the image states
+    int32_t parent[kBatchTokens];  // that token's id, or -1
+    int32_t skip[kBatchTokens];    // bytes the start vector has already read: the prefix's length, else 1
     int64_t beg[kBatchTokens];  // offset of the first byte in tok_bytes
     unsigned long long hash[kBatchTokens];
 };
@@ -142,9 +146,10 @@ __device__ __forceinline__ int batch_find(const int32_t *starts, int k, int i) {
 // bytes in kByteCap; at least `min_lanes` lanes are accepted (their walks always fit, see
 // walk_cap_for; if their bytes do not, the batch reads bytes from global memory).  Returns
 // the number of accepted lanes, rounded down to a multiple of `group` (wave-uniform).
+// `parent` / `parent_len`: see Batch::parent (pass -1 / 0 for a plain walk).
 __device__ __forceinline__ int batch_fill(Batch &B, const Tables &T, const uint8_t *tok_bytes,
                                           int64_t beg, int64_t len64, int wcap, int min_lanes,
-                                          int group) {
+                                          int group, int32_t parent = -1, int32_t parent_len = 0) {
     const int lane = threadIdx.x & 63;
     const bool used = len64 >= 0;
     const int len = !used ? 0 : (len64 > 0x7FFFFFFF ? 0x7FFFFFFF : (int)len64);
@@ -170,6 +175,9 @@ __device__ __forceinline__ int batch_fill(Batch &B, const Tables &T, const uint8
         B.row[lane] = row;
         B.beg[lane] = beg;
         B.hash[lane] = 0ull;
+        const bool composed = parent >= 0 && parent_len >= 1 && parent_len < len;
+        B.parent[lane] = composed ? parent : -1;
+        B.skip[lane] = composed ? parent_len : 1;
     }
     if (lane == k - 1) {
         B.wstart[k] = incl_n;
@@ -203,11 +211,13 @@ __device__ __forceinline__ void batch_stage_bytes(const Batch &B, const uint8_t 
 // sum_j wsum[row][j] * w[j] to B.hash[m] (order-free).  `keep` (or null) is where slot 0's
 // walk vector is kept, slot m's follows keep_stride entries on (keep_stride a multiple of
 // kWalkGroup; a vector longer than that is cut off).
+// `kept` (or null): kept walk vectors of finished tokens, kept_stride entries apart, from which
+// the slots with a parent start.
 template <bool LDS_BYTES, bool HASH>
 __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t *tab, int S,
                                                 const uint8_t *__restrict__ tok_bytes, Batch &B,
                                                 const uint8_t *ldsb, uint16_t *w, uint16_t *keep,
-                                                uint32_t keep_stride) {
+                                                uint32_t keep_stride, const uint16_t *kept = nullptr) {
     // every table index fits 32 bits: 257 rows of at most 65536 entries
     const uint32_t nt = blockDim.x, k = B.k, gtotal = B.gtotal, Su = (uint32_t)S;
     for (uint32_t g = threadIdx.x; g < gtotal; g += nt) {
@@ -216,17 +226,26 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
         const uint32_t n = (uint32_t)B.cnt[m];
         const uint32_t e0 = (uint32_t)B.row[m] * Su + j0;
         uint32_t cur[kWalkGroup];
+        // (a vector longer than what is kept of it cannot be started from)
+        const int32_t par = (kept && n <= keep_stride) ? B.parent[m] : -1;
+        const uint32_t skip = par >= 0 ? (uint32_t)B.skip[m] : 1u;
+        if (par >= 0) {  // the prefix's end states are this token's start states
+            const uint16_t *from = kept + (size_t)par * keep_stride + j0;
 #pragma unroll
-        for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)T.img[e0 + u] : 0u;
+            for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)from[u] : 0u;
+        } else {
+#pragma unroll
+            for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)T.img[e0 + u] : 0u;
+        }
         // the hash multipliers are asked for now and used after the walk: off the critical path
         uint64_t mult[kWalkGroup];
         if (HASH) {
 #pragma unroll
             for (int u = 0; u < kWalkGroup; ++u) mult[u] = j0 + u < n ? T.wsum[e0 + u] : 0ull;
         }
-        const uint32_t rem = B.len[m] > 0 ? (uint32_t)B.len[m] - 1u : 0u;
-        const uint32_t lsrc = (uint32_t)B.boff[m] + 1u;                               // byte 1 in ldsb
-        const uint8_t *gsrc = LDS_BYTES ? tok_bytes : tok_bytes + B.beg[m] + 1;       // or in memory
+        const uint32_t rem = B.len[m] > 0 ? (uint32_t)B.len[m] - skip : 0u;
+        const uint32_t lsrc = (uint32_t)B.boff[m] + skip;                             // first byte to read, in ldsb
+        const uint8_t *gsrc = LDS_BYTES ? tok_bytes : tok_bytes + B.beg[m] + skip;    // or in memory
         uint32_t nextb = 0;
         if (rem > 0) nextb = LDS_BYTES ? ldsb[lsrc] : gsrc[0];
         for (uint32_t p = 0; p < rem; ++p) {
@@ -260,9 +279,9 @@ template <bool HASH>
 __device__ __forceinline__ void batch_walk(const Tables &T, const uint16_t *tab, int S,
                                            const uint8_t *__restrict__ tok_bytes, Batch &B,
                                            const uint8_t *ldsb, uint16_t *w, uint16_t *keep = nullptr,
-                                           uint32_t keep_stride = 0) {
-    if (B.bytes_in_lds) batch_walk_impl<true, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
-    else batch_walk_impl<false, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride);
+                                           uint32_t keep_stride = 0, const uint16_t *kept = nullptr) {
+    if (B.bytes_in_lds) batch_walk_impl<true, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride, kept);
+    else batch_walk_impl<false, HASH>(T, tab, S, tok_bytes, B, ldsb, w, keep, keep_stride, kept);
 }
 
 }  // namespace cfgzip

@@ -215,6 +215,53 @@ def test_build_random_automaton_every_token_its_own_class(lib):
     _check_build(lib, vocab, table, stored=False)
 
 
+def _prefix_heavy_vocab(rng, V, alphabet=b"ab{ 1"):
+    """Short strings over a tiny alphabet: nearly every token of four bytes or more has a
+    two- or three-byte token as a prefix."""
+    alpha = np.frombuffer(alphabet, dtype=np.uint8)
+    toks = [bytes(alpha[rng.integers(0, len(alpha), size=int(rng.integers(0, 9)))]) for _ in range(V)]
+    toks += [b"", b"a", b"ab", b"abb", b"abba", b"abbab" * 3, b"ab" * 40, bytes(200)]
+    return vocab_from_tokens(toks)
+
+
+@pytest.mark.parametrize("S", [7, 24, 256, 300, 1024])
+def test_signatures_by_composition(lib, S):
+    """cfgzip_signatures_composed (Appendix A, Lemma 1) against the oracle and against the plain
+    call: signatures, hashes, and the kept walk vectors as the class builder reads them."""
+    from gpu_util import vocab_dev, hash_np
+    print(f"case composition S={S}", flush=True)
+    rng = np.random.default_rng(3000 + S)
+    raw = lib.load_library()
+    for vocab, table in ((_prefix_heavy_vocab(rng, 3000), _structured_table(rng, S, n_narrow=256)),
+                         (_prefix_heavy_vocab(rng, 700), rng.integers(0, S, size=(S, 256)).astype(np.uint16)),
+                         (_random_vocab(rng, 900, 9, n_bytes=4), _structured_table(rng, S, n_narrow=2))):
+        tb, to, tt = vocab_dev(vocab, table)
+        want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+        want_hash = oracle.signature_hash(want_sig, lib.DEFAULT_HASH_SEED)
+        want_c, want_r = oracle.build_classes(want_sig, vocab.tok_off)
+        ws = torch.empty(raw.cfgzip_signatures_composed_workspace_bytes(vocab.V, S), dtype=torch.uint8, device="cuda")
+        sig, h = lib.cfgzip_signatures(tb, to, tt, workspace=ws, composed=True)
+        assert (sig.cpu().numpy() == want_sig).all(), "signatures"
+        assert (hash_np(h) == want_hash).all(), "hash"
+        c, r, C, _ = lib.cfgzip_build_classes(tb, to, tt, None, h, signatures_workspace=ws)
+        assert C == len(want_r) and (c.cpu().numpy() == want_c).all() and (r.cpu().numpy() == want_r).all()
+        _, h2 = lib.cfgzip_signatures(tb, to, tt, want_sig=False, workspace=ws, composed=True)
+        assert (hash_np(h2) == want_hash).all(), "hash (on the fly)"
+        sig3, _ = lib.cfgzip_signatures(tb, to, tt, want_hash=False, workspace=ws, composed=True)
+        assert (sig3.cpu().numpy() == want_sig).all(), "signatures (no hash)"
+
+
+def test_signatures_by_composition_config3(lib):
+    from gpu_util import vocab_dev, hash_np
+    cfg = si.make_config(3)
+    vocab, table = cfg["vocab"], cfg["table"]
+    tb, to, tt = vocab_dev(vocab, table)
+    want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+    sig, h = lib.cfgzip_signatures(tb, to, tt, composed=True)
+    assert (sig.cpu().numpy() == want_sig).all()
+    assert (hash_np(h) == oracle.signature_hash(want_sig, lib.DEFAULT_HASH_SEED)).all()
+
+
 def test_random_automaton_at_scale(lib):
     """An automaton without structure at the size of the measured ones: every byte leaves about
     0.63 S distinct states, the image walk saves nothing, the walk vectors the signature call
