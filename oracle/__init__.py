@@ -220,6 +220,51 @@ def nfa_signatures(tok_bytes, tok_off, nfa) -> np.ndarray:
     return out
 
 
+def nfa_live_states(nfa, accept) -> np.ndarray:
+    """uint8 [S]: 1 iff an accepting state can be reached from the state (nfa uint32 [256, S, W])."""
+    nfa = _c(nfa, np.uint32)
+    accept = _c(accept, np.uint8)
+    S = nfa.shape[1]
+    live = np.empty(S, dtype=np.uint8)
+    _load().oracle_nfa_live_states(_p(nfa), ctypes.c_int32(S), _p(accept), _p(live))
+    return live
+
+
+def nfa_state_masks(rel_rep, live) -> np.ndarray:
+    """int32 [S, W(C)]: bit k of row q = the representative of class k leads from q to a live
+    state (rel_rep uint32 [C, S, W(S)])."""
+    rel_rep = _c(rel_rep, np.uint32)
+    live = _c(live, np.uint8)
+    C, S = rel_rep.shape[0], rel_rep.shape[1]
+    out = np.empty((S, (C + 31) // 32), dtype=np.int32)
+    _load().oracle_nfa_state_masks(_p(rel_rep), ctypes.c_int32(C), ctypes.c_int32(S), _p(live), _p(out))
+    return out
+
+
+def nfa_class_masks(state_mask, C, sets) -> np.ndarray:
+    """int32 [B, W(C)]: union of the mask rows of the states in each set (sets uint32 [B, W(S)])."""
+    state_mask = _c(state_mask, np.int32)
+    sets = _c(sets, np.uint32)
+    S, B = state_mask.shape[0], sets.shape[0]
+    out = np.empty((B, (C + 31) // 32), dtype=np.int32)
+    _load().oracle_nfa_class_masks(_p(state_mask), ctypes.c_int32(S), ctypes.c_int32(C), _p(sets),
+                                   ctypes.c_int32(B), _p(out))
+    return out
+
+
+def nfa_advance_states(rel_rep, class_of_token, tok, sets) -> np.ndarray:
+    """The state sets after each sequence consumed the representative of its token's class."""
+    rel_rep = _c(rel_rep, np.uint32)
+    c = _c(class_of_token, np.int32)
+    tok = _c(tok, np.int32)
+    out = _c(sets, np.uint32).copy()
+    C, S = rel_rep.shape[0], rel_rep.shape[1]
+    _load().oracle_nfa_advance_states(_p(rel_rep), ctypes.c_int32(C), ctypes.c_int32(S), _p(c),
+                                      ctypes.c_int32(c.shape[0]), _p(tok), ctypes.c_int32(tok.shape[0]),
+                                      _p(out))
+    return out
+
+
 def splitmix64_stream(seed: int, n: int) -> np.ndarray:
     state = ctypes.c_uint64(seed)
     lib = _load()

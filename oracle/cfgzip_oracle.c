@@ -46,6 +46,13 @@
  *                         (several productions q -> a q' per state and byte): the
  *                         displacement of t is the relation {(q, q') : q' reachable from q
  *                         on bytes(t)}, kept as one bit row per start state.
+ *   oracle_nfa_live_states, oracle_nfa_state_masks, oracle_nfa_class_masks,
+ *   oracle_nfa_advance_states
+ *                         The engine side (Section 2.2, Section 3.1 "Inference") when the
+ *                         automaton is not deterministic: the engine's state is a SET of
+ *                         automaton states; a class is allowed iff its representative leads
+ *                         from some state of the set to a live state; the set advances to
+ *                         everything the representative reaches from it.
  *   oracle_hash           The library's signature hash (not in the paper; a
  *                         device of this implementation) written from its
  *                         formula:  H(t) = sum_q a_q * sig[t][q]  mod 2^64 with
@@ -329,6 +336,85 @@ void oracle_nfa_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int
         free(cur);
         free(nxt);
     }
+}
+
+/* ---- engine side for a non-deterministic byte automaton ------------------------------- */
+
+static int bit_of(const uint32_t *row, int32_t i) { return (row[i >> 5] >> (i & 31)) & 1u; }
+
+/* live[q] = 1 iff an accepting state can be reached from q (q itself counts). */
+void oracle_nfa_live_states(const uint32_t *nfa /* [256][S][W] */, int32_t S,
+                            const uint8_t *accept /* [S] */, uint8_t *live /* [S] */) {
+    const int32_t W = (S + 31) / 32;
+    for (int32_t q = 0; q < S; ++q) live[q] = accept[q] ? 1 : 0;
+    int changed = 1;
+    while (changed) {
+        changed = 0;
+        for (int32_t q = 0; q < S; ++q) {
+            if (live[q]) continue;
+            for (int b = 0; b < 256 && !live[q]; ++b)
+                for (int32_t x = 0; x < S; ++x)
+                    if (live[x] && bit_of(nfa + ((size_t)b * S + q) * W, x)) {
+                        live[q] = 1;
+                        changed = 1;
+                        break;
+                    }
+        }
+    }
+}
+
+/* state_mask[q] bit k = 1 iff the representative of class k leads from q to some live state:
+ * exists q' with (q, q') in rel_rep[k] and live[q']. */
+void oracle_nfa_state_masks(const uint32_t *rel_rep /* [C][S][W] */, int32_t C, int32_t S,
+                            const uint8_t *live /* [S] */, int32_t *state_mask /* [S][W(C)] */) {
+    const int32_t W = (S + 31) / 32;
+    const int64_t Wc = ((int64_t)C + 31) / 32;
+    for (int32_t q = 0; q < S; ++q) {
+        int32_t *row = state_mask + q * Wc;
+        for (int64_t w = 0; w < Wc; ++w) row[w] = 0;
+        for (int32_t k = 0; k < C; ++k) {
+            const uint32_t *reach = rel_rep + ((size_t)k * S + q) * W;
+            int ok = 0;
+            for (int32_t x = 0; x < S && !ok; ++x) ok = bit_of(reach, x) && live[x];
+            if (ok) row[k >> 5] = (int32_t)((uint32_t)row[k >> 5] | (1u << (k & 31)));
+        }
+    }
+}
+
+/* cls_bits[b] = union of state_mask[q] over the states q of sets[b]. */
+void oracle_nfa_class_masks(const int32_t *state_mask /* [S][W(C)] */, int32_t S, int32_t C,
+                            const uint32_t *sets /* [B][W(S)] */, int32_t B,
+                            int32_t *cls_bits /* [B][W(C)] */) {
+    const int32_t W = (S + 31) / 32;
+    const int64_t Wc = ((int64_t)C + 31) / 32;
+    for (int32_t b = 0; b < B; ++b) {
+        for (int64_t w = 0; w < Wc; ++w) cls_bits[b * Wc + w] = 0;
+        for (int32_t q = 0; q < S; ++q)
+            if (bit_of(sets + (size_t)b * W, q))
+                for (int64_t w = 0; w < Wc; ++w)
+                    cls_bits[b * Wc + w] = (int32_t)((uint32_t)cls_bits[b * Wc + w] | (uint32_t)state_mask[q * Wc + w]);
+    }
+}
+
+/* sets[b] <- everything the representative of tok[b]'s class reaches from a state of sets[b];
+ * a token id or class id out of range leaves the empty set. */
+void oracle_nfa_advance_states(const uint32_t *rel_rep /* [C][S][W] */, int32_t C, int32_t S,
+                               const int32_t *class_of_token /* [V] */, int32_t V,
+                               const int32_t *tok /* [B] */, int32_t B, uint32_t *sets /* [B][W] */) {
+    const int32_t W = (S + 31) / 32;
+    uint32_t *next = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)W);
+    for (int32_t b = 0; b < B; ++b) {
+        uint32_t *set = sets + (size_t)b * W;
+        for (int32_t w = 0; w < W; ++w) next[w] = 0;
+        const int32_t t = tok[b];
+        const int32_t k = (t < 0 || t >= V) ? -1 : class_of_token[t];
+        if (k >= 0 && k < C)
+            for (int32_t q = 0; q < S; ++q)
+                if (bit_of(set, q))
+                    for (int32_t w = 0; w < W; ++w) next[w] |= rel_rep[((size_t)k * S + q) * W + w];
+        for (int32_t w = 0; w < W; ++w) set[w] = next[w];
+    }
+    free(next);
 }
 
 /* Byte strings of the representatives, class after class: rep_off[k] .. rep_off[k+1] delimit
