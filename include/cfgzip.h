@@ -391,7 +391,8 @@ int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32
  *
  *   nfa       int32 [256][S][W(S)]  bit q' of row nfa[b][q] <=> q' may follow q on byte b
  *                                   (pad bits must be 0); 16-byte aligned, as is rel_out
- *   S         1 .. 256
+ *   S         1 .. 1024 (up to 256 states a thread keeps its state set in registers, beyond
+ *             that in LDS)
  *   rel_out   int32 [V][S][W(S)]    bit q' of row rel_out[t][q] <=> (q, q') in R_t; pad bits 0
  *   hash_out  uint64 [V] or NULL    the hash of cfgzip_signatures taken over the relation read
  *                                   as 2 * S * W(S) 16-bit entries (low half of a word first)
@@ -402,6 +403,29 @@ int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok_off, int32
 int cfgzip_nfa_signatures(const uint8_t *tok_bytes, const int64_t *tok_off, int32_t V,
                           const int32_t *nfa, int32_t S, int32_t *rel_out, uint64_t *hash_out,
                           uint64_t hash_seed, void *stream);
+
+/*
+ * Engine side for a non-deterministic byte automaton (paper Section 2.2 and Section 3.1
+ * "Inference", as cfgzip_state_masks / cfgzip_class_masks / cfgzip_advance_states above): the
+ * engine's state per sequence is a SET of automaton states, a bit row int32 [W(S)].
+ *   rel_rep   int32 [C][S][W(S)]  relations of the C representatives (cfgzip_nfa_signatures on the
+ *                                 representatives' byte strings, or rows of its output)
+ *   live      uint8 [S]           1 iff an accepting state can be reached from the state
+ * cfgzip_nfa_state_masks (once per grammar):
+ *     state_mask[q] bit k = some state that r[k] reaches from q is live      int32 [S][W(C)]
+ * cfgzip_nfa_class_masks (per step):
+ *     cls_bits[b] = union of state_mask[q] over the states q of state_sets[b]  int32 [B][W(C)]
+ * cfgzip_nfa_advance_states (per step), in place:
+ *     state_sets[b] <- union over q in state_sets[b] of rel_rep[class_of_token[tok[b]]][q];
+ *     a token id or class id out of range leaves the empty set (which allows nothing)
+ */
+int cfgzip_nfa_state_masks(const int32_t *rel_rep, int32_t C, int32_t S, const uint8_t *live,
+                           int32_t *state_mask, void *stream);
+int cfgzip_nfa_class_masks(const int32_t *state_mask, int32_t S, int32_t C,
+                           const int32_t *state_sets, int32_t B, int32_t *cls_bits, void *stream);
+int cfgzip_nfa_advance_states(const int32_t *rel_rep, int32_t C, int32_t S,
+                              const int32_t *class_of_token, int32_t V, const int32_t *tok, int32_t B,
+                              int32_t *state_sets, void *stream);
 
 #ifdef __cplusplus
 }

@@ -23,7 +23,10 @@ from .binding import (  # noqa: F401
     cfgzip_engine_step,
     cfgzip_expand_mask,
     cfgzip_map_to_rep,
+    cfgzip_nfa_advance_states,
+    cfgzip_nfa_class_masks,
     cfgzip_nfa_signatures,
+    cfgzip_nfa_state_masks,
     cfgzip_representative_vocabulary,
     cfgzip_signatures,
     cfgzip_signatures_static,

@@ -92,6 +92,12 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_representative_vocabulary.argtypes = [vp, vp, i32, vp, i32, vp, vp, i64, vp]
     lib.cfgzip_nfa_signatures.restype = ctypes.c_int
     lib.cfgzip_nfa_signatures.argtypes = [vp, vp, i32, vp, i32, vp, vp, u64, vp]
+    lib.cfgzip_nfa_state_masks.restype = ctypes.c_int
+    lib.cfgzip_nfa_state_masks.argtypes = [vp, i32, i32, vp, vp, vp]
+    lib.cfgzip_nfa_class_masks.restype = ctypes.c_int
+    lib.cfgzip_nfa_class_masks.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+    lib.cfgzip_nfa_advance_states.restype = ctypes.c_int
+    lib.cfgzip_nfa_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
     lib.cfgzip_displacements_workspace_bytes.restype = sz
     lib.cfgzip_displacements_workspace_bytes.argtypes = [i32, i32]
     lib.cfgzip_stack_adjacency.restype = ctypes.c_int
@@ -461,6 +467,48 @@ def cfgzip_nfa_signatures(tok_bytes: torch.Tensor, tok_off: torch.Tensor, nfa: t
         ctypes.c_uint64(hash_seed & 0xFFFFFFFFFFFFFFFF), _stream(stream))
     _check("cfgzip_nfa_signatures", rc)
     return rel, hashes
+
+
+def cfgzip_nfa_state_masks(rel_rep: torch.Tensor, live: torch.Tensor, *, stream=None) -> torch.Tensor:
+    """int32 [S, W(C)] from relations int32 [C, S, W(S)] and live uint8 [S]."""
+    lib = load_library()
+    C, S, W = rel_rep.shape
+    if W != words_for(S) or live.numel() != S:
+        raise ValueError("rel_rep must be [C, S, W(S)] and live [S]")
+    out = torch.empty((S, words_for(C)), dtype=torch.int32, device=rel_rep.device)
+    rc = lib.cfgzip_nfa_state_masks(_dev(rel_rep, torch.int32, "rel_rep"), C, S, _dev(live, torch.uint8, "live"),
+                                    out.data_ptr(), _stream(stream))
+    _check("cfgzip_nfa_state_masks", rc)
+    return out
+
+
+def cfgzip_nfa_class_masks(state_mask: torch.Tensor, C: int, state_sets: torch.Tensor, *,
+                           stream=None) -> torch.Tensor:
+    """int32 [B, W(C)]: union of the mask rows of the states in each set (state_sets int32 [B, W(S)])."""
+    lib = load_library()
+    S = state_mask.shape[0]
+    B = state_sets.shape[0]
+    if state_sets.shape[1] != words_for(S) or state_mask.shape[1] != words_for(C):
+        raise ValueError("state_sets must be [B, W(S)] and state_mask [S, W(C)]")
+    out = torch.empty((B, words_for(C)), dtype=torch.int32, device=state_sets.device)
+    rc = lib.cfgzip_nfa_class_masks(_dev(state_mask, torch.int32, "state_mask"), S, int(C),
+                                    _dev(state_sets, torch.int32, "state_sets"), B, out.data_ptr(),
+                                    _stream(stream))
+    _check("cfgzip_nfa_class_masks", rc)
+    return out
+
+
+def cfgzip_nfa_advance_states(rel_rep: torch.Tensor, class_of_token: torch.Tensor, tok: torch.Tensor,
+                              state_sets: torch.Tensor, *, stream=None) -> torch.Tensor:
+    """state_sets (int32 [B, W(S)]) advanced in place on the representatives of tok's classes."""
+    lib = load_library()
+    C, S, _W = rel_rep.shape
+    rc = lib.cfgzip_nfa_advance_states(_dev(rel_rep, torch.int32, "rel_rep"), C, S,
+                                       _dev(class_of_token, torch.int32, "class_of_token"),
+                                       class_of_token.numel(), _dev(tok, torch.int32, "tok"), tok.numel(),
+                                       _dev(state_sets, torch.int32, "state_sets"), _stream(stream))
+    _check("cfgzip_nfa_advance_states", rc)
+    return state_sets
 
 
 def cfgzip_representative_vocabulary(tok_bytes: torch.Tensor, tok_off: torch.Tensor,

@@ -128,10 +128,132 @@ __global__ void rep_bytes_kernel(const uint8_t *__restrict__ tok_bytes,
     for (int64_t j = 0; j < n && dst + j < capacity; ++j) rep_bytes[dst + j] = tok_bytes[src + j];
 }
 
+// ---- the same engine over a non-deterministic byte automaton: the state is a set of states ----
+//   state_mask[q] bit k = some state that the representative of class k reaches from q is live
+//   cls_bits[b]         = union of state_mask[q] over the states q of sets[b]
+//   sets[b]            <- union over q in sets[b] of rel_rep[c[tok[b]]][q]
+
+// A thread per (state q, word of 32 classes): 32 relation rows tested against the live bitmap.
+__global__ __launch_bounds__(kThreads) void nfa_state_masks_kernel(const uint32_t *__restrict__ rel_rep,
+                                                                   int C, int S, int W,
+                                                                   const uint8_t *__restrict__ live,
+                                                                   int32_t *__restrict__ state_mask,
+                                                                   int Wc) {
+    __shared__ uint32_t live_bits[kStateWords];
+    for (int w = threadIdx.x; w < kStateWords; w += kThreads) {
+        uint32_t bits = 0;
+        for (int j = 0; j < 32; ++j) {
+            const int q = w * 32 + j;
+            if (q < S && live[q]) bits |= 1u << j;
+        }
+        live_bits[w] = bits;
+    }
+    __syncthreads();
+    const int64_t item = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (item >= (int64_t)S * Wc) return;
+    const int q = (int)(item / Wc), wi = (int)(item % Wc);
+    uint32_t word = 0;
+    for (int j = 0; j < 32; ++j) {
+        const int k = wi * 32 + j;
+        if (k >= C) break;
+        const uint32_t *row = rel_rep + ((size_t)k * S + q) * W;
+        uint32_t hit = 0;
+        for (int w = 0; w < W; ++w) hit |= row[w] & live_bits[w];
+        if (hit) word |= 1u << j;
+    }
+    state_mask[(size_t)q * Wc + wi] = (int32_t)word;
+}
+
+// A workgroup per sequence; a thread per word of the class mask goes through the set's members.
+__global__ __launch_bounds__(kThreads) void nfa_class_masks_kernel(const int32_t *__restrict__ state_mask,
+                                                                   int S, int W, int Wc,
+                                                                   const uint32_t *__restrict__ sets,
+                                                                   int32_t *__restrict__ cls_bits) {
+    const int b = blockIdx.x;
+    const uint32_t *set = sets + (size_t)b * W;
+    for (int wc = threadIdx.x; wc < Wc; wc += kThreads) {
+        uint32_t acc = 0;
+        for (int w = 0; w < W; ++w) {
+            uint32_t bits = set[w];  // the same for every thread
+            while (bits) {
+                const int q = w * 32 + __ffs(bits) - 1;
+                bits &= bits - 1;
+                if (q < S) acc |= (uint32_t)state_mask[(size_t)q * Wc + wc];
+            }
+        }
+        cls_bits[(size_t)b * Wc + wc] = (int32_t)acc;
+    }
+}
+
+// A workgroup per sequence; the old set is read whole before any word of the new one is written.
+__global__ __launch_bounds__(kThreads) void nfa_advance_kernel(const uint32_t *__restrict__ rel_rep, int C,
+                                                               int S, int W,
+                                                               const int32_t *__restrict__ class_of_token,
+                                                               int V, const int32_t *__restrict__ tok,
+                                                               uint32_t *sets) {
+    __shared__ uint32_t old_set[kStateWords];
+    const int b = blockIdx.x;
+    uint32_t *set = sets + (size_t)b * W;
+    for (int w = threadIdx.x; w < W; w += kThreads) old_set[w] = set[w];
+    __syncthreads();
+    const int32_t t = tok[b];
+    const int32_t k = (t < 0 || t >= V) ? -1 : class_of_token[t];
+    for (int wo = threadIdx.x; wo < W; wo += kThreads) {
+        uint32_t acc = 0;
+        if (k >= 0 && k < C) {
+            for (int w = 0; w < W; ++w) {
+                uint32_t bits = old_set[w];
+                while (bits) {
+                    const int q = w * 32 + __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    if (q < S) acc |= rel_rep[((size_t)k * S + q) * W + wo];
+                }
+            }
+        }
+        set[wo] = acc;
+    }
+}
+
 }  // namespace
 }  // namespace cfgzip
 
 using namespace cfgzip;
+
+extern "C" int cfgzip_nfa_state_masks(const int32_t *rel_rep, int32_t C, int32_t S, const uint8_t *live,
+                                      int32_t *state_mask, void *stream) {
+    if (!rel_rep || !live || !state_mask || C <= 0 || S <= 0 || S > 65536) return CFGZIP_E_INVALID;
+    if (!aligned_to(rel_rep, 4) || !aligned_to(state_mask, 4)) return CFGZIP_E_INVALID;
+    const int Wc = (int)words_for(C), W = (int)words_for(S);
+    const int64_t items = (int64_t)S * Wc;
+    hipLaunchKernelGGL(nfa_state_masks_kernel, dim3((unsigned)ceil_div(items, kThreads)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(rel_rep), C, S, W,
+                       live, state_mask, Wc);
+    return check_launch();
+}
+
+extern "C" int cfgzip_nfa_class_masks(const int32_t *state_mask, int32_t S, int32_t C,
+                                      const int32_t *state_sets, int32_t B, int32_t *cls_bits,
+                                      void *stream) {
+    if (!state_mask || !state_sets || !cls_bits || S <= 0 || S > 65536 || C <= 0 || B <= 0)
+        return CFGZIP_E_INVALID;
+    if (!aligned_to(state_mask, 4) || !aligned_to(state_sets, 4) || !aligned_to(cls_bits, 4))
+        return CFGZIP_E_INVALID;
+    hipLaunchKernelGGL(nfa_class_masks_kernel, dim3(B), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       state_mask, S, (int)words_for(S), (int)words_for(C),
+                       reinterpret_cast<const uint32_t *>(state_sets), cls_bits);
+    return check_launch();
+}
+
+extern "C" int cfgzip_nfa_advance_states(const int32_t *rel_rep, int32_t C, int32_t S,
+                                         const int32_t *class_of_token, int32_t V, const int32_t *tok,
+                                         int32_t B, int32_t *state_sets, void *stream) {
+    if (!rel_rep || !class_of_token || !tok || !state_sets) return CFGZIP_E_INVALID;
+    if (C <= 0 || S <= 0 || S > 65536 || V <= 0 || B <= 0) return CFGZIP_E_INVALID;
+    hipLaunchKernelGGL(nfa_advance_kernel, dim3(B), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<const uint32_t *>(rel_rep), C, S, (int)words_for(S), class_of_token, V,
+                       tok, reinterpret_cast<uint32_t *>(state_sets));
+    return check_launch();
+}
 
 extern "C" int cfgzip_representative_vocabulary(const uint8_t *tok_bytes, const int64_t *tok_off,
                                                 int32_t V, const int32_t *rep_of_class, int32_t C,

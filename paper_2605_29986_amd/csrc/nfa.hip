@@ -6,7 +6,8 @@
 // A thread owns one (token, start state) pair and carries the set of current states as W words
 // in registers.  Per byte it ORs together the successor rows of the set's members, visiting set
 // bits only, so the cost follows the number of live states (one or a few for a lexer), not S;
-// a set that has become empty stops early.  The 64-bit hash is the same multilinear form as for
+// a set that has become empty stops early.  Automata of more than 256 states (up to 1,024) keep
+// the sets in LDS instead.  The 64-bit hash is the same multilinear form as for
 // the byte walk, over the relation read as 16-bit entries, so any split over threads gives the
 // same bits.
 
@@ -19,7 +20,8 @@ namespace cfgzip {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxNfaStates = 256;
+constexpr int kMaxRegisterStates = 256;  // up to here a thread keeps its set in registers
+constexpr int kMaxNfaStates = 1024;
 constexpr int kStagedBytes = 64;  // token bytes read once into LDS; longer tokens go on from global
 
 struct NfaArgs {
@@ -123,6 +125,68 @@ __global__ __launch_bounds__(kThreads) void nfa_walk_kernel(NfaArgs a) {
     }
 }
 
+// More than 256 states: the sets no longer fit in registers.  A workgroup takes 256 start states
+// of one token; a thread keeps its current and next set in LDS, word w of thread t at [w][t] (so
+// the threads of a wave hit different banks), and per byte ORs the successor rows of the set's
+// members into the next set.  The hash is accumulated per token with one atomic per workgroup
+// (hash_out is cleared by a launch before).
+__global__ __launch_bounds__(kThreads) void nfa_walk_lds_kernel(NfaArgs a, int W, int q_blocks) {
+    extern __shared__ uint32_t sets[];  // [2][W][kThreads]
+    __shared__ unsigned long long hash_sum;
+    const int t = blockIdx.x / q_blocks;
+    const int q = (blockIdx.x % q_blocks) * kThreads + threadIdx.x;
+    uint32_t *cur = sets + threadIdx.x, *nxt = sets + (size_t)W * kThreads + threadIdx.x;
+    if (threadIdx.x == 0) hash_sum = 0;
+    __syncthreads();
+    uint64_t h = 0;
+    if (q < a.S) {
+        for (int w = 0; w < W; ++w) cur[(size_t)w * kThreads] = (q >> 5) == w ? 1u << (q & 31) : 0u;
+        const int64_t b0 = a.tok_off[t], b1 = a.tok_off[t + 1];
+        const size_t matrix = (size_t)a.S * W;
+        for (int64_t p = b0; p < b1; ++p) {
+            const uint32_t *step = a.nfa + (size_t)a.tok_bytes[p] * matrix;
+            for (int w = 0; w < W; ++w) nxt[(size_t)w * kThreads] = 0;
+            for (int w = 0; w < W; ++w) {
+                uint32_t bits = cur[(size_t)w * kThreads];
+                while (bits) {
+                    const int x = w * 32 + __ffs(bits) - 1;
+                    bits &= bits - 1;
+                    const uint32_t *row = step + (size_t)x * W;
+                    for (int k = 0; k < W; ++k) nxt[(size_t)k * kThreads] |= row[k];
+                }
+            }
+            nxt[(size_t)(W - 1) * kThreads] &= a.last_word_mask;  // a stray pad bit must not become a state number
+            uint32_t any = 0;
+            for (int w = 0; w < W; ++w) any |= nxt[(size_t)w * kThreads];
+            uint32_t *tmp = cur;
+            cur = nxt;
+            nxt = tmp;
+            if (!any) break;  // no state left: the row stays empty
+        }
+        uint32_t *out = a.rel + ((size_t)t * a.S + q) * W;
+        for (int w = 0; w < W; ++w) {
+            const uint32_t v = cur[(size_t)w * kThreads];
+            out[w] = v;
+            if (a.hash && v) {
+                const uint32_t e = 2u * (uint32_t)(q * W + w);
+                if (v & 0xFFFFu) h += (splitmix64_at(a.seed, e) | 1ull) * (uint64_t)(v & 0xFFFFu);
+                if (v >> 16) h += (splitmix64_at(a.seed, e + 1u) | 1ull) * (uint64_t)(v >> 16);
+            }
+        }
+    }
+    if (a.hash) {
+        if (h) atomicAdd(&hash_sum, (unsigned long long)h);
+        __syncthreads();
+        if (threadIdx.x == 0 && hash_sum)
+            atomicAdd(reinterpret_cast<unsigned long long *>(a.hash + t), hash_sum);
+    }
+}
+
+__global__ void clear_u64_kernel(uint64_t *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
 template <int W>
 int launch_nfa(const NfaArgs &a, hipStream_t stream) {
     const int per_block = kThreads / a.threads_per_token;
@@ -157,6 +221,22 @@ extern "C" int cfgzip_nfa_signatures(const uint8_t *tok_bytes, const int64_t *to
     while (a.threads_per_token < S) a.threads_per_token *= 2;
     a.last_word_mask = (S & 31) ? (1u << (S & 31)) - 1u : 0xFFFFFFFFu;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (S > kMaxRegisterStates) {
+        const int W = (S + 31) / 32, q_blocks = (S + kThreads - 1) / kThreads;
+        if ((int64_t)V * q_blocks > 0x7FFFFFFF) return CFGZIP_E_INVALID;
+        if (hash_out) {
+            hipLaunchKernelGGL(clear_u64_kernel, dim3((unsigned)ceil_div(V, kThreads)), dim3(kThreads), 0,
+                               stream, hash_out, V);
+            CFGZIP_TRY(check_launch());
+        }
+        const size_t dyn = (size_t)2 * W * kThreads * sizeof(uint32_t);
+        if (dyn > 48 * 1024)
+            CFGZIP_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(nfa_walk_lds_kernel),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn)));
+        hipLaunchKernelGGL(nfa_walk_lds_kernel, dim3((unsigned)(V * q_blocks)), dim3(kThreads), dyn, stream,
+                           a, W, q_blocks);
+        return check_launch();
+    }
     switch ((S + 31) / 32) {
         case 1: return launch_nfa<1>(a, stream);
         case 2: return launch_nfa<2>(a, stream);

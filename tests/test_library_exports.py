@@ -71,7 +71,7 @@ def test_widening_rows_queries_and_argument_checks(raw):
     # sizes are checked before any pointer is used
     buf = ctypes.create_string_buffer(4096)
     p = ctypes.cast(buf, ctypes.c_void_p)
-    assert raw.cfgzip_nfa_signatures(p, p, 1, p, 257, p, None, u64, None) == -1
+    assert raw.cfgzip_nfa_signatures(p, p, 1, p, 1025, p, None, u64, None) == -1
     assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, 2, 1, 5000, p, 256, p, None, u64, p, sz, None) == -1
     assert raw.cfgzip_displacements(p, p, 1, p, p, p, p, -1, 1, 5, p, 256, p, None, u64, p, sz, None) == -1
     assert raw.cfgzip_displacements(p, p, 1, p, p, p, None, 2, 1, 5, p, 256, p, None, u64, p, sz, None) == -1
