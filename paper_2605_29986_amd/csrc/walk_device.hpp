@@ -36,7 +36,10 @@ constexpr int kImageRows = 257;     // 256 first bytes + the "empty token" row
 constexpr int kBatchTokens = 64;    // tokens a workgroup walks together (one per lane of a wave)
 constexpr int kByteCap = 4096;      // token bytes staged in LDS per batch
 constexpr int kMinWalkCap = 8192;   // walks (entries of w) held in LDS per batch, at least
-constexpr int kWalkGroup = 8;       // walks of one token that a thread carries together
+// Walks of one token that a thread carries together.  Fewer walks per thread put more lanes on one
+// token, so a wave's table reads fall into fewer columns (measured on 4,096 states: 8 -> 147 us,
+// 4 -> 130 us, 2 -> 130 us, 1 -> 153 us per signature call).
+constexpr int kWalkGroup = 4;
 
 struct Tables {
     const uint16_t *Tt;
@@ -206,7 +209,7 @@ __device__ __forceinline__ void batch_stage_bytes(const Batch &B, const uint8_t 
 // Walks every (slot, image state) pair of the batch: w[wstart[m] + j] = state reached from
 // img[row][j] on bytes 1.. of slot m (0 in the padding).  A walk is a chain of dependent table
 // reads, so a thread carries a group of kWalkGroup walks of ONE slot: they share the bytes,
-// have the same length, and give eight independent reads per step; the next byte is fetched
+// have the same length, and give kWalkGroup independent reads per step; the next byte is fetched
 // while the current reads are outstanding.  With HASH, adds the group's part of
 // sum_j wsum[row][j] * w[j] to B.hash[m] (order-free).  `keep` (or null) is where slot 0's
 // walk vector is kept, slot m's follows keep_stride entries on (keep_stride a multiple of
@@ -270,6 +273,10 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
             uint16_t *kd = keep + (size_t)m * keep_stride + j0;
 #pragma unroll
             for (int u = 0; u < kWalkGroup; ++u) kd[u] = (uint16_t)cur[u];
+            // a kept vector is compared 8 entries at a time: the token's last group also zeroes
+            // what lies between its own end and the next multiple of 8 (keep_stride is one)
+            if (kWalkGroup < 8 && j0 + kWalkGroup >= n)
+                for (uint32_t j = j0 + kWalkGroup; j < ((n + 7u) & ~7u) && j < keep_stride; ++j) kd[j - j0] = 0;
         }
         if (HASH) atomicAdd(&B.hash[m], (unsigned long long)term);
     }
