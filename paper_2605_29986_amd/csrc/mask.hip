@@ -23,6 +23,7 @@ constexpr int kCols = 8;                       // columns (tokens) per thread
 constexpr int kTileCols = kThreads * kCols;    // 2048 columns per workgroup
 constexpr int kUnroll = 2;                     // rows in flight per thread
 constexpr int kRowsStream = 4;                 // rows per workgroup when logits are streamed
+constexpr int kRowsStreamFusedBf16 = 2;        // the same for bf16 logits masked from class bits (measured best of 1, 2, 3, 4, 8)
 constexpr int kRowsExpand = 16;                // rows per workgroup for mask expansion alone
 constexpr int kMaxRowsPerBlock = 16;           // the larger of the two
 
@@ -349,6 +350,8 @@ int run_mask(void *logits, int logits_kind, int32_t B, int32_t V, int64_t row_st
     // Measured on MI355X at batch 256 x 128,256 bf16: small row chunks (many workgroups, two
     // rows in flight per thread) stream fastest; the class ids of a tile are re-read from L2.
     int rows = logits_kind == LOGITS_NONE ? kRowsExpand : kRowsStream;
+    // (the engine step's staging phase wants the larger chunk: it is paid per workgroup)
+    if (logits_kind == LOGITS_BF16 && from_class && !engine) rows = kRowsStreamFusedBf16;
     if (from_class) {
         if (row_bytes > kMaxLds) return CFGZIP_E_INVALID;  // one class-mask row must fit in LDS
         while (rows > 1 && rows * row_bytes > 64 * 1024) rows /= 2;
