@@ -236,7 +236,7 @@ def bench_displacement(lib_mod, raw, torch, repeats: int, cpu_sample: int, gramm
     tb = torch.from_numpy(vocab.tok_bytes).cuda()
     to = torch.from_numpy(vocab.tok_off).cuda()
     gd = [torch.from_numpy(x).cuda() for x in g.arrays()]
-    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(V, g.N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(V, g.N, g.P), dtype=torch.uint8, device="cuda")
     # rows long enough for every set of these workloads (no token left in a class of its own for
     # want of room); the shortest row length is timed beside it
     ROW = 1024

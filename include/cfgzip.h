@@ -361,7 +361,7 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
  *     hash_out    uint64 [V]
  *     status_out  int32 [V] or NULL: CFGZIP_DISP_OK, CFGZIP_DISP_OVERFLOW, or
  *                 CFGZIP_DISP_BAD_GRAMMAR for every token (rows and hashes then 0)
- *     ws          cfgzip_displacements_workspace_bytes(V, N) bytes, 256-byte aligned
+ *     ws          cfgzip_displacements_workspace_bytes(V, N, P) bytes, 256-byte aligned
  *                 (cfgzip_stack_adjacency alone: V = 0)
  * Grouping: cfgzip_build_classes(tok_bytes, tok_off, V, NULL, row_len, rows, hash, NULL, ..).
  */
@@ -369,7 +369,7 @@ int cfgzip_advance_states(const uint16_t *sig_rep, int32_t C, int32_t S,
 #define CFGZIP_DISP_OK 0
 #define CFGZIP_DISP_OVERFLOW 1
 #define CFGZIP_DISP_BAD_GRAMMAR 2
-size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N);
+size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N, int32_t P);
 int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
                            const int32_t *prod_body_off, const uint16_t *prod_body,
                            int32_t body_total, int32_t P, int32_t N,

@@ -99,7 +99,7 @@ def load_library() -> ctypes.CDLL:
     lib.cfgzip_nfa_advance_states.restype = ctypes.c_int
     lib.cfgzip_nfa_advance_states.argtypes = [vp, i32, i32, vp, i32, vp, i32, vp, vp]
     lib.cfgzip_displacements_workspace_bytes.restype = sz
-    lib.cfgzip_displacements_workspace_bytes.argtypes = [i32, i32]
+    lib.cfgzip_displacements_workspace_bytes.argtypes = [i32, i32, i32]
     lib.cfgzip_stack_adjacency.restype = ctypes.c_int
     lib.cfgzip_stack_adjacency.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, sz, vp]
     lib.cfgzip_displacements.restype = ctypes.c_int
@@ -414,7 +414,7 @@ def cfgzip_stack_adjacency(prod_head: torch.Tensor, prod_byte: torch.Tensor,
     adj = torch.empty((N, words_for(N)), dtype=torch.int32, device=dev)
     invalid = torch.empty((1,), dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(0, N), dev)
+        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(0, N, prod_head.numel()), dev)
     h, b, off, bd, P = _grammar_args(prod_head, prod_byte, prod_body_off, prod_body)
     total = prod_body.numel() if body_total is None else int(body_total)
     rc = lib.cfgzip_stack_adjacency(h, b, off, bd, total, P, N, adj.data_ptr(), invalid.data_ptr(),
@@ -436,7 +436,7 @@ def cfgzip_displacements(tok_bytes: torch.Tensor, tok_off: torch.Tensor, prod_he
     hashes = torch.empty((V,), dtype=torch.int64, device=dev)
     status = torch.empty((V,), dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(V, N), dev)
+        workspace = _workspace(lib.cfgzip_displacements_workspace_bytes(V, N, prod_head.numel()), dev)
     h, b, off, bd, P = _grammar_args(prod_head, prod_byte, prod_body_off, prod_body)
     total = prod_body.numel() if body_total is None else int(body_total)
     rc = lib.cfgzip_displacements(

@@ -94,12 +94,13 @@ struct GrammarWorkspace {
     uint32_t *reach[2]; // [N][W]: reachability over "right-most body symbol" edges
     uint32_t *adj;      // [N][W]: bit Y of row Z <=> (Y, Z) stack-adjacent
     int32_t *pair_first;  // [256][N]: 1 + index of the first production with (terminal, head), 0 = none
+    uint4 *prod_short;    // [P]: first four body symbols (16 bits each), body length, body offset: one load per production
     int32_t *retry_list[2];  // [V] each: ids of the tokens handed on
     size_t clear_words; // words from hdr to the end that start at zero
     size_t bytes;
 };
 
-GrammarWorkspace carve_grammar_ws(void *ws, int N, int V) {
+GrammarWorkspace carve_grammar_ws(void *ws, int N, int V, int P) {
     GrammarWorkspace g{};
     const size_t W = (size_t)ceil_div(N, 32);
     size_t off = 0;
@@ -116,6 +117,7 @@ GrammarWorkspace carve_grammar_ws(void *ws, int N, int V) {
     g.pair_first = reinterpret_cast<int32_t *>(take((size_t)256 * N * 4));
     g.clear_words = off / 4;
     g.reach[1] = reinterpret_cast<uint32_t *>(take((size_t)N * W * 4));  // fully written
+    g.prod_short = reinterpret_cast<uint4 *>(take((size_t)P * sizeof(uint4)));  // fully written for a valid grammar
     g.retry_list[0] = reinterpret_cast<int32_t *>(take((size_t)V * 4));
     g.retry_list[1] = reinterpret_cast<int32_t *>(take((size_t)V * 4));
     g.bytes = off;
@@ -172,6 +174,11 @@ __global__ void grammar_index_kernel(Grammar g, GrammarWorkspace w) {
         for (int x = b + 1; x <= 256; ++x) w.byte_off[x] = g.P;
     const int A = g.head[i];
     if (i == 0 || g.byte[i - 1] != b || g.head[i - 1] != A) w.pair_first[(size_t)b * g.N + A] = i + 1;
+    {
+        uint32_t sym[4] = {0, 0, 0, 0};
+        for (int k = 0; k < min(len, 4); ++k) sym[k] = g.body[off + k];
+        w.prod_short[i] = make_uint4(sym[0] | (sym[1] << 16), sym[2] | (sym[3] << 16), (uint32_t)len, (uint32_t)off);
+    }
     if (len == 0) {
         atomicOr(&w.unary[A >> 5], 1u << (A & 31));
     } else {
@@ -253,6 +260,7 @@ struct DisplacementArgs {
     GrammarHeader *hdr;
     const int32_t *byte_off;
     const int32_t *pair_first;
+    const uint4 *prod_short;
     const uint32_t *adj;
     const uint8_t *tok_bytes;
     const int64_t *tok_off;
@@ -421,12 +429,17 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
         }
         __syncthreads();
         auto head_of = [&](int i) -> int { return staged ? L.sp_head[i - lo] : g.head[i]; };
-        auto len_of = [&](int i) -> int {
-            return staged ? L.sp_off[i - lo + 1] - L.sp_off[i - lo] : g.body_off[i + 1] - g.body_off[i];
+        // a production's body: staged symbols in LDS, or the packed record (its first four symbols,
+        // length and offset in one 16-byte load) with the symbol array behind it for longer bodies
+        auto body_of = [&](int i) -> uint4 {
+            if (staged) return make_uint4(0, 0, (uint32_t)(L.sp_off[i - lo + 1] - L.sp_off[i - lo]), L.sp_off[i - lo]);
+            return a.prod_short[i];
         };
-        // where the body of production i starts: an index into the staged symbols or into g.body
-        auto body_start = [&](int i) -> int { return staged ? L.sp_off[i - lo] : g.body_off[i]; };
-        auto body_sym = [&](int start, int k) -> int { return staged ? L.sp_body[start + k] : g.body[start + k]; };
+        auto body_sym = [&](const uint4 &b, int k) -> int {
+            if (staged) return L.sp_body[b.w + k];
+            if (k < 4) return (int)(((k < 2 ? b.x : b.y) >> (16 * (k & 1))) & 0xFFFFu);
+            return g.body[b.w + k];
+        };
 
         // pops: a lane per configuration (few productions per (terminal, head))
         for (int c = lane; c < n; c += 64) {
@@ -437,8 +450,8 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
             const int first = a.pair_first[(size_t)ch * g.N + top] - 1;
             if (first < 0) continue;
             for (int i = first; i < hi && head_of(i) == top; ++i) {
-                const int len = len_of(i);
-                const int body = body_start(i);
+                const uint4 body = body_of(i);
+                const int len = (int)body.z;
                 const int slot = atomicAdd(&L.n_emit, 1);
                 if (no - 1 + len > MAX_OUT) {
                     L.crossed = 1;
@@ -470,8 +483,8 @@ __device__ void token_displacement(const DisplacementArgs &a, int t,
                     const uint32_t bits = (STAGE && adj_in_lds) ? L.adj[w] : a.adj[w];
                     if (!((bits >> (prev & 31)) & 1u)) continue;
                 }
-                const int len = len_of(i);
-                const int body = body_start(i);
+                const uint4 body = body_of(i);
+                const int len = (int)body.z;
                 const int slot = atomicAdd(&L.n_emit, 1);
                 if (ni + 1 > MAX_IN || len > MAX_OUT) {
                     L.crossed = 1;
@@ -677,9 +690,9 @@ int check_grammar_args(const uint16_t *prod_head, const uint8_t *prod_byte, cons
 
 using namespace cfgzip;
 
-extern "C" size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N) {
-    if (V < 0 || N <= 0 || N > kMaxSymbols) return 0;
-    return carve_grammar_ws(nullptr, N, V).bytes;
+extern "C" size_t cfgzip_displacements_workspace_bytes(int32_t V, int32_t N, int32_t P) {
+    if (V < 0 || N <= 0 || N > kMaxSymbols || P <= 0) return 0;
+    return carve_grammar_ws(nullptr, N, V, P).bytes;
 }
 
 extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *prod_byte,
@@ -689,7 +702,7 @@ extern "C" int cfgzip_stack_adjacency(const uint16_t *prod_head, const uint8_t *
     CFGZIP_TRY(check_grammar_args(prod_head, prod_byte, prod_body_off, prod_body, body_total, P, N));
     if (!adj_out || !aligned_to(adj_out, 4) || !aligned_to(invalid_out, 4)) return CFGZIP_E_INVALID;
     if (!ws || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
-    GrammarWorkspace w = carve_grammar_ws(ws, N, 0);
+    GrammarWorkspace w = carve_grammar_ws(ws, N, 0, P);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     Grammar g{prod_head, prod_byte, prod_body_off, prod_body, P, N, (int)ceil_div(N, 32), body_total};
@@ -720,7 +733,7 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
         !aligned_to(status_out, 4))
         return CFGZIP_E_INVALID;
     if (!ws || !aligned_to(ws, 256)) return CFGZIP_E_WORKSPACE;
-    GrammarWorkspace w = carve_grammar_ws(ws, N, V);
+    GrammarWorkspace w = carve_grammar_ws(ws, N, V, P);
     if (ws_bytes < w.bytes) return CFGZIP_E_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     Grammar g{prod_head, prod_byte, prod_body_off, prod_body, P, N, (int)ceil_div(N, 32), body_total};
@@ -730,6 +743,7 @@ extern "C" int cfgzip_displacements(const uint8_t *tok_bytes, const int64_t *tok
     a.hdr = w.hdr;
     a.byte_off = w.byte_off;
     a.pair_first = w.pair_first;
+    a.prod_short = w.prod_short;
     a.adj = w.adj;
     a.tok_bytes = tok_bytes;
     a.tok_off = tok_off;

@@ -424,7 +424,7 @@ def test_status_pointer_is_optional(lib):
     raw = lib.load_library()
     rows2 = torch.zeros_like(rows)
     hashes2 = torch.zeros_like(hashes)
-    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(vocab.V, g.N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(raw.cfgzip_displacements_workspace_bytes(vocab.V, g.N, g.P), dtype=torch.uint8, device="cuda")
     rc = raw.cfgzip_displacements(tb.data_ptr(), to.data_ptr(), vocab.V, gd[0].data_ptr(), gd[1].data_ptr(),
                                   gd[2].data_ptr(), gd[3].data_ptr(), g.body.size, g.P, g.N, rows2.data_ptr(), 256,
                                   hashes2.data_ptr(), None, ctypes.c_uint64(SEED), ws.data_ptr(), ws.numel(),

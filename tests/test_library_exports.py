@@ -58,11 +58,11 @@ def test_widening_rows_queries_and_argument_checks(raw):
         assert fn in names
     q = raw.cfgzip_displacements_workspace_bytes
     q.restype = ctypes.c_size_t
-    assert q(0, 4097) == 0 and q(-1, 10) == 0 and q(0, 0) == 0
-    small, large = q(0, 27), q(128256, 27)
+    assert q(0, 4097, 5) == 0 and q(-1, 10, 5) == 0 and q(0, 0, 5) == 0 and q(0, 10, 0) == 0
+    small, large = q(0, 27, 480), q(128256, 27, 480)
     assert small >= 256 * 27 * 4 + 257 * 4          # the (terminal, head) index and the byte offsets
     assert large >= small + 128256 * 4              # plus the list of tokens for the second pass
-    assert q(0, 4096) >= 3 * 4096 * 128 * 4 + 256 * 4096 * 4   # three bit matrices and the index
+    assert q(0, 4096, 9000) >= 3 * 4096 * 128 * 4 + 256 * 4096 * 4 + 9000 * 16   # three bit matrices and the index
     u64, sz = ctypes.c_uint64(0), ctypes.c_size_t(0)
     assert raw.cfgzip_displacements(None, None, 1, None, None, None, None, 0, 1, 1, None, 256, None, None, u64,
                                     None, sz, None) == -1
