@@ -39,7 +39,7 @@ constexpr int kThreads = 256;             // link, minima and marking kernels: o
 constexpr int kItems = 8;
 constexpr int kTile = kThreads * kItems;  // items per workgroup in the scan kernels
 constexpr int kSortThreads = 1024;
-constexpr int kSortItems = 8;
+constexpr int kSortItems = 2;  // measured: 8 -> 156 us, 4 -> 133, 3 -> 128, 2 -> 130, 1 -> 151 per build of 152 K tokens (2 is best on the smaller ones)
 constexpr int kSortTile = kSortThreads * kSortItems;  // keys per workgroup in the sort
 constexpr int kRadixBits = 10;
 constexpr int kBins = 1 << kRadixBits;
@@ -380,7 +380,7 @@ __device__ __forceinline__ int walk_store_state(const StoreSource &s) {
 // Image row of a token as the store has it (256: the empty token, whose signature is the
 // identity and whose vector is not kept).
 __device__ __forceinline__ uint32_t store_row(const StoreSource &s, int32_t tok) {
-    return min((uint32_t)s.store.wrow[tok], 256u);
+    return min(walk_row_of(s.store.wrow[tok]), 256u);
 }
 
 // Two tokens with the same image row `row` < 256: idx[row] is onto, so their signatures are
@@ -389,10 +389,9 @@ __device__ __forceinline__ uint32_t store_row(const StoreSource &s, int32_t tok)
 __device__ __forceinline__ bool store_same_row_differ(const StoreSource &s, int32_t ta, int32_t tb,
                                                       uint32_t row) {
     const uint32_t stride = walk_store_stride(s.S);
-    const uint32_t cnt = min((uint32_t)s.T.nimg[row], stride);
     const uint4 *wa = reinterpret_cast<const uint4 *>(s.store.wvec + (size_t)ta * stride);
     const uint4 *wb = reinterpret_cast<const uint4 *>(s.store.wvec + (size_t)tb * stride);
-    const uint32_t n16 = (cnt + 7u) / 8u;
+    const uint32_t n16 = min(walk_units_of(s.store.wrow[ta]), stride / 8u);  // the same for both: one row
     bool diff = false;
     constexpr int kAhead = 4;  // independent 16-byte loads in flight per side
     for (uint32_t k0 = 0; k0 < n16; k0 += kAhead) {
@@ -423,7 +422,9 @@ __device__ __forceinline__ bool store_other_row_differ(const StoreSource &s, int
     const uint32_t stride = walk_store_stride(S);
     const bool ida = ra == 256u, idb = rb == 256u;
     if (ida && idb) return false;
-    const uint32_t na = min((uint32_t)s.T.nimg[ra], stride), nb = min((uint32_t)s.T.nimg[rb], stride);
+    // positions in a kept vector are below the row's image size, which is at most the stride in a
+    // store that has not overflowed; the bound keeps a corrupt index inside the staged vector
+    const uint32_t na = stride, nb = stride;
     {
         // lanes 0..31 copy vector a, lanes 32..63 vector b, 16 bytes each (stride <= 256 entries)
         const uint32_t half = lane & 31;
@@ -589,7 +590,7 @@ struct LinkArgs {
     uint64_t *rep_key;
     Counters *ctr;
     StoreSource store;    // SRC_STORE
-    int32_t *other_list;  // SRC_STORE: sorted positions whose link crosses two image rows
+    int4 *other_list;     // SRC_STORE: (sorted position, its token, its left neighbour's token, the two image rows) of the links that cross two image rows
     const uint16_t *sig;  // SRC_ROWS: [V][S]
     int S;
 };
@@ -607,6 +608,51 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     const int tile0 = blockIdx.x * kThreads;
     const int n = a.n;
     const uint64_t *keys = a.keys;
+    const int i = tile0 + threadIdx.x;
+    const bool in = i < n;
+    bool start = false;
+    int32_t ta = 0, tb = 0;
+    int64_t len = 0;
+    if (in) {
+        start = i == 0 || hash_part(keys[i]) != hash_part(keys[i - 1]);
+        ta = a.vals[i];
+        tb = i > 0 ? a.vals[i - 1] : ta;
+        len = a.tok_off[ta + 1] - a.tok_off[ta];
+    }
+
+    // SRC_STORE: is the store this call's?  The same answer in every workgroup.
+    int store_state = 0;
+    if (SRC == SRC_STORE) {
+        store_state = walk_store_state(a.store);
+        if (store_state && blockIdx.x == 0 && threadIdx.x == 0) a.ctr->store_state = store_state;
+    }
+    const bool verify = in && !start && SRC != SRC_NONE && store_state == 0;
+    // Links inside one image row: the two walk vectors are compared by eight lanes together,
+    // 16 bytes each per round, so that a wave's reads fall into whole cache lines; the wave takes
+    // its 64 positions eight at a time and keeps all eight pairs' reads in flight.  The first
+    // round is asked for before the rows are known (every token has a slot of `stride` entries;
+    // what turns out not to be wanted is not looked at), so that it overlaps the row reads and
+    // the search below.
+    const uint32_t stride = SRC == SRC_STORE ? walk_store_stride(a.S) : 8u;
+    const uint32_t sub = lane & 7, group = lane >> 3;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    uint16_t wa_row = 0, wb_row = 0;
+    uint4 x0[8], y0[8];
+    if (SRC == SRC_STORE) {
+        if (verify) {
+            wa_row = a.store.store.wrow[ta];
+            wb_row = a.store.store.wrow[tb];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int owner = k * 8 + (int)group;
+            const bool want = __shfl((int)verify, owner, 64) != 0 && sub < stride / 8u;
+            const int32_t pa = __shfl(ta, owner, 64), pb = __shfl(tb, owner, 64);
+            x0[k] = want ? reinterpret_cast<const uint4 *>(a.store.store.wvec + (size_t)pa * stride)[sub] : zero;
+            y0[k] = want ? reinterpret_cast<const uint4 *>(a.store.store.wvec + (size_t)pb * stride)[sub] : zero;
+        }
+    }
+
     // where the segment that reaches into this tile starts (64-ary search by the first wave)
     if (wave == 0) {
         int lo = tile0;
@@ -631,17 +677,6 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
         }
         if (lane == 0) carry_s = lo;
     }
-    const int i = tile0 + threadIdx.x;
-    const bool in = i < n;
-    bool start = false;
-    int32_t ta = 0, tb = 0;
-    int64_t len = 0;
-    if (in) {
-        start = i == 0 || hash_part(keys[i]) != hash_part(keys[i - 1]);
-        ta = a.vals[i];
-        tb = i > 0 ? a.vals[i - 1] : ta;
-        len = a.tok_off[ta + 1] - a.tok_off[ta];
-    }
     int32_t inc = start ? i : -1;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -650,30 +685,34 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     }
     if (lane == 63) wave_tot[wave] = inc;
 
-    // SRC_STORE: is the store this call's?  The same answer in every workgroup.
-    int store_state = 0;
-    if (SRC == SRC_STORE) {
-        store_state = walk_store_state(a.store);
-        if (store_state && blockIdx.x == 0 && threadIdx.x == 0) a.ctr->store_state = store_state;
-    }
-    const bool verify = in && !start && SRC != SRC_NONE && store_state == 0;
+    __syncthreads();
+    int32_t seg = carry_s;
+    for (int w = 0; w < wave; ++w) seg = max(seg, wave_tot[w]);
+    seg = max(seg, inc);
+
+    // the per-segment minima go out now: their atomics are under way while the vectors are compared
+    wave_class_minima(in, seg, ta, len, a.min_id, a.rep_key, ends);
+    __syncthreads();
+    flush_wave_ends(ends, 2 * (kThreads / 64), a.min_id, a.rep_key);
+
     bool differs = false;
     uint32_t ra = 0, rb = 0;
     if (SRC == SRC_STORE) {
         if (verify) {
-            ra = store_row(a.store, ta);
-            rb = store_row(a.store, tb);
+            ra = min(walk_row_of(wa_row), 256u);
+            rb = min(walk_row_of(wb_row), 256u);
         }
-        // Links inside one image row: the two walk vectors are compared by eight lanes together,
-        // 16 bytes each per round, so that a wave's reads fall into whole cache lines; the wave
-        // takes its 64 positions eight at a time and keeps all eight pairs' reads in flight.
-        const uint32_t stride = walk_store_stride(a.S);
         const bool same = verify && ra == rb && ra != 256u;
-        const uint32_t n16 = same ? (min((uint32_t)a.store.T.nimg[ra], stride) + 7u) / 8u : 0u;
-        const uint32_t sub = lane & 7, group = lane >> 3;
-        const uint4 zero = make_uint4(0, 0, 0, 0);
+        const uint32_t n16 = same ? min(walk_units_of(wa_row), stride / 8u) : 0u;
         uint32_t dmask = 0;  // bit k: this lane saw a difference in the pair of position 8 k + group
-        for (uint32_t r = 0; r < kWalkStoreMaxStride / 64; ++r) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t pn = __shfl(n16, k * 8 + (int)group, 64);
+            if (sub < pn && ((x0[k].x != y0[k].x) | (x0[k].y != y0[k].y) | (x0[k].z != y0[k].z) |
+                             (x0[k].w != y0[k].w)))
+                dmask |= 1u << k;
+        }
+        for (uint32_t r = 1; r < kWalkStoreMaxStride / 64; ++r) {
             if (__ballot(n16 > 8u * r) == 0ull) break;  // nobody's vector is that long
             uint4 x[8], y[8];
 #pragma unroll
@@ -698,11 +737,6 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
             if ((lane >> 3) == k) differs = differs || ((dm >> (8 * (lane & 7))) & 0xFFull) != 0ull;
         }
     }
-    __syncthreads();
-    int32_t seg = carry_s;
-    for (int w = 0; w < wave; ++w) seg = max(seg, wave_tot[w]);
-    seg = max(seg, inc);
-
     bool listed = false;
     if (SRC == SRC_STORE) {
         // Links between different image rows cost a pass over all S states each and bunch up
@@ -714,7 +748,8 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
             int32_t at = 0;
             if (lane == 0) at = atomicAdd(&a.ctr->other_rows, (int)__popcll(lm));
             at = __shfl(at, 0, 64);
-            if (listed) a.other_list[at + __popcll(lm & ((1ull << lane) - 1ull))] = i;
+            if (listed)
+                a.other_list[at + __popcll(lm & ((1ull << lane) - 1ull))] = make_int4(i, ta, tb, (int)(ra | (rb << 16)));
         }
     } else if (SRC == SRC_ROWS) {
         // a wave takes its own positions four at a time: more row reads in flight
@@ -774,9 +809,6 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     }
     const uint64_t dm = __ballot(differs);
     if (dm && lane == 0) atomicAdd(&a.ctr->unresolved, (int)__popcll(dm));
-    wave_class_minima(in, seg, ta, len, a.min_id, a.rep_key, ends);
-    __syncthreads();
-    flush_wave_ends(ends, 2 * (kThreads / 64), a.min_id, a.rep_key);
 }
 
 // ---------------------------------------------------------------- verification of arbitrary pairs
@@ -1111,9 +1143,8 @@ struct MarkArgs {
     const int32_t *min_id;
     uint32_t *head_bits;
     // listed links (null list: none)
-    const int32_t *other_list;
+    const int4 *other_list;
     StoreSource store;
-    const int32_t *vals;
     int32_t *resolved, *mismatch;
     Counters *ctr;
 };
@@ -1133,11 +1164,11 @@ __global__ __launch_bounds__(kThreads) void mark_heads_kernel(MarkArgs a) {
     const int count = min(a.ctr->other_rows, a.n);
     const int waves = ((int)gridDim.x - a.mark_blocks) * (kThreads / 64);
     for (int e = ((int)blockIdx.x - a.mark_blocks) * (kThreads / 64) + wave; e < count; e += waves) {
-        const int i = a.other_list[e];
+        const int4 link = a.other_list[e];
+        const int i = link.x;
         if (i <= 0 || i >= a.n) continue;  // never listed; stay in bounds
-        const int32_t ta = a.vals[i], tb = a.vals[i - 1];
-        const bool d = store_other_row_differ(a.store, ta, tb, store_row(a.store, ta),
-                                              store_row(a.store, tb), staged[wave][0], staged[wave][1]);
+        const bool d = store_other_row_differ(a.store, link.y, link.z, (uint32_t)link.w & 0xFFFFu,
+                                              (uint32_t)link.w >> 16, staged[wave][0], staged[wave][1]);
         settle(d, i, a.resolved, a.mismatch, a.ctr);
     }
 }
@@ -1238,6 +1269,7 @@ struct BuildWorkspace {
     uint32_t *hist;
     int32_t *seg_head, *head_pos, *resolved, *mismatch, *next_head, *cand, *chain_start, *anchor;
     int32_t *min_id, *word_prefix, *tile_tmp;
+    int4 *other_list;
     uint32_t *head_bits;
     uint64_t *rep_key;
     uint16_t *verify_w;  // walk vectors of the re-walk verification when they do not fit in LDS
@@ -1269,6 +1301,7 @@ BuildWorkspace carve_build_ws(void *ws, int32_t V, int32_t S) {
     w.chain_start = c.take<int32_t>(n);
     w.anchor = c.take<int32_t>(n);
     w.min_id = c.take<int32_t>(n);
+    w.other_list = c.take<int4>(n);
     w.word_prefix = c.take<int32_t>(n_words);
     w.head_bits = c.take<uint32_t>(n_words);
     w.tile_tmp = c.take<int32_t>(nt);
@@ -1438,7 +1471,7 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         la.rep_key = w.rep_key;
         la.ctr = w.ctr;
         la.store = store_src;
-        la.other_list = w.cand;  // free until the collision rounds, which start after a host wait
+        la.other_list = w.other_list;
         la.sig = sig;
         la.S = S;
         if (source == FROM_STORE) hipLaunchKernelGGL(link_kernel<SRC_STORE>, grid_for(n), dim3(kThreads), 0, stream, la);
@@ -1489,9 +1522,8 @@ extern "C" int cfgzip_build_classes(const uint8_t *tok_bytes, const int64_t *tok
         ma.head_bits = w.head_bits;
         int verify_blocks = 0;
         if (settle_listed && source == FROM_STORE) {
-            ma.other_list = w.cand;
+            ma.other_list = w.other_list;
             ma.store = store_src;
-            ma.vals = vals;
             ma.resolved = w.resolved;
             ma.mismatch = w.mismatch;
             ma.ctr = w.ctr;

@@ -230,7 +230,7 @@ __global__ __launch_bounds__(LDS_TABLE ? 1024 : kWalkThreads) void signatures_ke
             if (a.store.header && (int)threadIdx.x < k && B.aux[threadIdx.x]) {
                 // image row of the kept vector (the walk wrote the vector and its zero padding)
                 const uint32_t m = threadIdx.x;
-                a.store.wrow[tcur + m] = (uint16_t)B.row[m];
+                a.store.wrow[tcur + m] = pack_walk_row((uint32_t)B.row[m], (uint32_t)B.cnt[m], stride);
                 // (the empty token's identity vector is never looked at: its row says it all)
                 if ((uint32_t)B.cnt[m] > stride && B.row[m] != 256) a.store.header->overflow = 1;
             }

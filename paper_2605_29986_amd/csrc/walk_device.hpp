@@ -70,9 +70,16 @@ __host__ __device__ inline uint32_t walk_store_stride(int32_t S) {
 
 struct WalkStoreView {
     WalkStore *header;  // null: nothing is kept
-    uint16_t *wrow;     // [V]
+    uint16_t *wrow;     // [V]: image row (9 bits) and, above it, how many 16-byte units of the vector are in use
     uint16_t *wvec;     // [V][stride]
 };
+// wrow entry: the comparison of two kept vectors then needs no look-up of the row's image size
+__host__ __device__ inline uint16_t pack_walk_row(uint32_t row, uint32_t count, uint32_t stride) {
+    const uint32_t kept = row >= 256u ? 0u : (count < stride ? count : stride);  // the empty token keeps nothing
+    return (uint16_t)((row < 256u ? row : 256u) | (((kept + 7u) / 8u) << 9));
+}
+__host__ __device__ inline uint32_t walk_row_of(uint16_t packed) { return packed & 0x1FFu; }
+__host__ __device__ inline uint32_t walk_units_of(uint16_t packed) { return packed >> 9; }
 
 // Builds all tables in the signature workspace.  Host functions, defined in walk.hip.
 // V > 0 also lays out (and resets) the walk store for V tokens.
