@@ -47,6 +47,7 @@ static_assert(kSortThreads == kBins, "one thread per bin in the sort kernels");
 constexpr int kAggBits = 12;
 constexpr int kAggSlots = 1 << kAggBits;
 constexpr uint32_t kAggEmpty = 0xFFFFFFFFu;
+constexpr int kListedParts = 4;  // waves that share one listed cross-row link
 constexpr int kAssignThreads = 512;
 constexpr int kAssignItems = 4;
 constexpr int kAssignTile = kAssignThreads * kAssignItems;
@@ -413,15 +414,17 @@ __device__ __forceinline__ bool store_same_row_differ(const StoreSource &s, int3
 // a segment, or an empty token): sig[q] = w[idx[row][q]] has to be compared for every q; the
 // empty token's signature is sig[q] = q.  One wave; both vectors are staged in the wave's LDS
 // buffers la, lb (kWalkStoreMaxStride entries each).  Returns whether any entry differs
-// (wave-uniform).
+// (wave-uniform).  `part` of `parts`: the wave looks only at every parts-th stretch of 512 states,
+// starting with stretch `part` (several waves then share one pair; S a multiple of 8 only).
 __device__ __forceinline__ bool store_other_row_differ(const StoreSource &s, int32_t ta, int32_t tb,
                                                        uint32_t ra, uint32_t rb, uint16_t *la,
-                                                       uint16_t *lb) {
+                                                       uint16_t *lb, int part = 0, int parts = 1) {
     const int lane = threadIdx.x & 63;
     const int S = s.S;
     const uint32_t stride = walk_store_stride(S);
     const bool ida = ra == 256u, idb = rb == 256u;
     if (ida && idb) return false;
+    if (part * 512 >= S) return false;  // nothing of this pair falls to this wave
     // positions in a kept vector are below the row's image size, which is at most the stride in a
     // store that has not overflowed; the bound keeps a corrupt index inside the staged vector
     const uint32_t na = stride, nb = stride;
@@ -445,17 +448,17 @@ __device__ __forceinline__ bool store_other_row_differ(const StoreSource &s, int
         // 16 bytes of each index row per lane and step (the identity row is not read)
         const uint4 zero = make_uint4(0, 0, 0, 0);
         constexpr int kAhead = 2;
-        for (int q0 = lane * 8; q0 < S; q0 += 512 * kAhead) {
+        for (int q0 = lane * 8 + 512 * part; q0 < S; q0 += 512 * parts * kAhead) {
             uint4 xa[kAhead], xb[kAhead];
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
-                const int q = q0 + 512 * u;
+                const int q = q0 + 512 * parts * u;
                 xa[u] = (!ida && q < S) ? *reinterpret_cast<const uint4 *>(ia + q) : zero;
                 xb[u] = (!idb && q < S) ? *reinterpret_cast<const uint4 *>(ib + q) : zero;
             }
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
-                const int q = q0 + 512 * u;
+                const int q = q0 + 512 * parts * u;
                 if (q >= S) continue;
                 const uint32_t ja[8] = {xa[u].x & 0xFFFFu, xa[u].x >> 16, xa[u].y & 0xFFFFu, xa[u].y >> 16,
                                         xa[u].z & 0xFFFFu, xa[u].z >> 16, xa[u].w & 0xFFFFu, xa[u].w >> 16};
@@ -804,7 +807,8 @@ __global__ __launch_bounds__(kThreads) void link_kernel(LinkArgs a) {
     if (in) {
         a.seg_head[i] = seg;
         a.head_pos[i] = start ? i : i - 1;
-        a.resolved[i] = (start || (verify && !listed && !differs)) ? 1 : 0;
+        // (a listed link counts as settled until a wave of the next launch finds a difference)
+        a.resolved[i] = (start || (verify && !differs)) ? 1 : 0;
         a.mismatch[i] = differs ? 1 : 0;
     }
     const uint64_t dm = __ballot(differs);
@@ -1160,16 +1164,23 @@ __global__ __launch_bounds__(kThreads) void mark_heads_kernel(MarkArgs a) {
         return;
     }
     if (!a.other_list) return;
+    // kListedParts waves share a link when the signatures are long (S a multiple of 8 only)
     const int wave = threadIdx.x >> 6;
+    const int parts = (a.store.S % 8) == 0 ? kListedParts : 1;
     const int count = min(a.ctr->other_rows, a.n);
     const int waves = ((int)gridDim.x - a.mark_blocks) * (kThreads / 64);
-    for (int e = ((int)blockIdx.x - a.mark_blocks) * (kThreads / 64) + wave; e < count; e += waves) {
-        const int4 link = a.other_list[e];
+    for (int64_t e = ((int)blockIdx.x - a.mark_blocks) * (kThreads / 64) + wave; e < (int64_t)count * parts;
+         e += waves) {
+        const int4 link = a.other_list[e / parts];
         const int i = link.x;
         if (i <= 0 || i >= a.n) continue;  // never listed; stay in bounds
         const bool d = store_other_row_differ(a.store, link.y, link.z, (uint32_t)link.w & 0xFFFFu,
-                                              (uint32_t)link.w >> 16, staged[wave][0], staged[wave][1]);
-        settle(d, i, a.resolved, a.mismatch, a.ctr);
+                                              (uint32_t)link.w >> 16, staged[wave][0], staged[wave][1],
+                                              (int)(e % parts), parts);
+        if (d && (threadIdx.x & 63) == 0) {  // the first wave to find a difference counts it
+            a.resolved[i] = 0;
+            if (atomicExch(&a.mismatch[i], 1) == 0) atomicAdd(&a.ctr->unresolved, 1);
+        }
     }
 }
 
