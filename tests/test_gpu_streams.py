@@ -62,3 +62,47 @@ def test_whole_path_on_a_side_stream(cfg1):
     assert (status.cpu().numpy() == want_status).all() and int(invalid.item()) == 0
     assert (adj.cpu().numpy().view(np.uint32) ==
             D.adjacency_bits(D.stack_adjacency(g.productions()), g.N)).all()
+
+
+def test_class_builds_from_two_host_threads(cfg1, cfg2_small):
+    """Two host threads, each with a stream, workspaces and outputs of its own, build classes at
+    the same time (the call waits for its stream and keeps its counts in per-thread pinned
+    memory): both must match the oracle, call after call."""
+    import threading
+
+    import paper_2605_29986_amd as lib
+    from gpu_util import vocab_dev
+    lib.load_library()
+    jobs = []
+    for cfg in (cfg1, cfg2_small):
+        vocab, table = cfg["vocab"], cfg["table"]
+        want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+        jobs.append((vocab_dev(vocab, table), oracle.build_classes(want_sig, vocab.tok_off)))
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(k):
+        try:
+            (tb, to, tt), (want_c, want_r) = jobs[k]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(12):
+                    ws = torch.empty(lib.load_library().cfgzip_signatures_workspace_bytes(to.numel() - 1, tt.shape[0]),
+                                     dtype=torch.uint8, device="cuda")
+                    _sig, h = lib.cfgzip_signatures(tb, to, tt, want_sig=False, workspace=ws, stream=stream)
+                    c, r, C, coll = lib.cfgzip_build_classes(tb, to, tt, None, h, signatures_workspace=ws,
+                                                             stream=stream)
+                    if C != len(want_r) or coll != 0:
+                        errors.append((k, rep, "count", C, coll))
+                    if not (c.cpu().numpy() == want_c).all() or not (r.cpu().numpy() == want_r).all():
+                        errors.append((k, rep, "classes"))
+        except Exception as e:  # noqa: BLE001 - reported by the main thread
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads)
+    assert not errors, errors[:3]
