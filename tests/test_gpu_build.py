@@ -333,6 +333,18 @@ def test_million_token_vocabulary(lib):
     assert C2 == C and coll2 > 1000
 
 
+@pytest.mark.parametrize("V", [262_144, 262_145])
+def test_vocabulary_sizes_around_the_switch_to_wider_keys(lib, V):
+    """Up to 262,144 tokens the sort key holds 32 hash bits (four passes) and the ranking keeps its
+    bit vector in LDS; one token more and it is 40 bits (five passes) and scan kernels."""
+    print(f"case V={V}", flush=True)
+    cfg = si.make_config(1, V=V)
+    C, coll = _check_build(lib, cfg["vocab"], cfg["table"], use_store=True)
+    assert coll == 0 and C > 1000
+    _check_build(lib, cfg["vocab"], cfg["table"], stored=False, use_store=False,
+                 hash_override=lambda h: h & 0xFFFF)
+
+
 def test_signature_workspace_that_does_not_match_is_ignored(lib, cfg1, cfg2_small):
     """A workspace left by a call on another vocabulary / automaton, a zeroed one, and one
     whose compressed signatures overflowed (random automaton: ~0.63 S states per token, more
