@@ -352,6 +352,33 @@ def bench_nfa(lib_mod, raw, torch, repeats: int, cpu: bool):
     }
     log(f"nfa: V={V} S={S} C={C} relations {ms_rel:.3f} ms ({out['relation_store_GBps']} GB/s stored), "
         f"with classes {ms_all:.3f} ms, {out['walks_per_s']:.3e} walks/s")
+    # engine side over state sets: per-state class masks once, then per step the class masks of
+    # 256 state sets and their advance on the representatives of sampled tokens
+    rel_t, _h = res["rel"]
+    c_t, r_t = res["cls"][0], res["cls"][1]
+    rel_rep = rel_t[r_t.long()].contiguous()          # plumbing: rows of the representatives
+    rng = np.random.Generator(np.random.PCG64(cfg["seed"] + 600))
+    live = torch.from_numpy((rng.random(S) < 0.5).astype(np.uint8)).cuda()
+    state_mask = lib_mod.cfgzip_nfa_state_masks(rel_rep, live)
+    ms_sm = min(event_ms(lambda: lib_mod.cfgzip_nfa_state_masks(rel_rep, live), stream) for _ in range(repeats))
+    Bn = 256
+    members = np.zeros((Bn, W * 32), bool)
+    for b in range(Bn):
+        members[b, rng.integers(1, S, size=2)] = True
+    sets0 = torch.from_numpy(np.packbits(members, axis=1, bitorder="little").view(np.int32)).cuda()
+    tok_t = torch.from_numpy(rng.integers(0, V, size=Bn).astype(np.int32)).cuda()
+    sets = sets0.clone()
+
+    def engine_steps(n=100):
+        for _ in range(n):
+            lib_mod.cfgzip_nfa_class_masks(state_mask, C, sets)
+            lib_mod.cfgzip_nfa_advance_states(rel_rep, c_t, tok_t, sets)
+    engine_steps(5)
+    us_step = event_ms(engine_steps, stream) * 1e3 / 100
+    out["engine_over_state_sets"] = {"B": Bn, "ms_state_masks_once": round(ms_sm, 4),
+                                     "us_per_step_class_masks_plus_advance": round(us_step, 2)}
+    log(f"nfa engine: state masks [S={S}][C={C}] once {ms_sm * 1e3:.1f} us; class masks + advance of {Bn} state sets "
+        f"{us_step:.1f} us per step")
     if cpu:
         import oracle
         t0 = time.perf_counter()
