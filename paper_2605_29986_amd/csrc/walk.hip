@@ -3,13 +3,17 @@
 // image walk that keeps the work per token proportional to the number of
 // distinct states its first byte leaves, not to S).
 //
-// Per call:  transpose the table, build the per-first-byte image tables, then
+// Per call:  one kernel transposes the table and builds the per-first-byte image
+// tables (a workgroup per image row), then
 // one kernel in which a workgroup takes 64 consecutive tokens at a time, stages
 // their bytes in LDS, walks all (token, image state) pairs as one flat list of
 // independent lanes, reduces the hash in LDS and expands w through idx into the
 // stored signature rows with 16-byte stores.  Automata whose transposed table
 // fits next to that in LDS are walked from LDS, larger ones from the
-// L2-resident copy in the workspace.
+// L2-resident copy in the workspace.  Two variants of the call share these kernels:
+// cfgzip_signatures_composed (longer tokens continue the walk of a short token that is a
+// prefix of theirs; paper Appendix A, Lemma 1) and cfgzip_signatures_static (tables in
+// memory that belongs to the library, for callers that cannot allocate).
 
 #include <algorithm>
 #include <mutex>
