@@ -230,6 +230,7 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
                                                 uint32_t keep_stride, const uint16_t *kept = nullptr) {
     // every table index fits 32 bits: 257 rows of at most 65536 entries
     const uint32_t nt = blockDim.x, k = B.k, gtotal = B.gtotal, Su = (uint32_t)S;
+    const bool vec4 = (S % 4) == 0;
     for (uint32_t g = threadIdx.x; g < gtotal; g += nt) {
         const uint32_t m = (uint32_t)batch_find(B.gstart, (int)k, (int)g);
         const uint32_t j0 = (g - (uint32_t)B.gstart[m]) * kWalkGroup;
@@ -239,19 +240,34 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
         // (a vector longer than what is kept of it cannot be started from)
         const int32_t par = (kept && n <= keep_stride) ? B.parent[m] : -1;
         const uint32_t skip = par >= 0 ? (uint32_t)B.skip[m] : 1u;
+        // A group's four start states (and its four hash multipliers) lie next to each other: with
+        // S a multiple of 4 they are 8-byte (32-byte) aligned and come in one (two) loads.
+        static_assert(kWalkGroup == 4, "the vector forms below are written for groups of four");
         if (par >= 0) {  // the prefix's end states are this token's start states
-            const uint16_t *from = kept + (size_t)par * keep_stride + j0;
-#pragma unroll
-            for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)from[u] : 0u;
+            const uint2 v = *reinterpret_cast<const uint2 *>(kept + (size_t)par * keep_stride + j0);
+            cur[0] = v.x & 0xFFFFu, cur[1] = v.x >> 16, cur[2] = v.y & 0xFFFFu, cur[3] = v.y >> 16;
+        } else if (vec4) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(T.img + e0);
+            cur[0] = v.x & 0xFFFFu, cur[1] = v.x >> 16, cur[2] = v.y & 0xFFFFu, cur[3] = v.y >> 16;
         } else {
 #pragma unroll
             for (int u = 0; u < kWalkGroup; ++u) cur[u] = j0 + u < n ? (uint32_t)T.img[e0 + u] : 0u;
         }
+#pragma unroll
+        for (int u = 0; u < kWalkGroup; ++u)
+            if (j0 + u >= n) cur[u] = 0u;  // padding of the token's last group
         // the hash multipliers are asked for now and used after the walk: off the critical path
         uint64_t mult[kWalkGroup];
         if (HASH) {
+            if (vec4) {
+                const uint4 lo = *reinterpret_cast<const uint4 *>(T.wsum + e0);
+                const uint4 hi = *reinterpret_cast<const uint4 *>(T.wsum + e0 + 2);
+                mult[0] = lo.x | ((uint64_t)lo.y << 32), mult[1] = lo.z | ((uint64_t)lo.w << 32);
+                mult[2] = hi.x | ((uint64_t)hi.y << 32), mult[3] = hi.z | ((uint64_t)hi.w << 32);
+            } else {
 #pragma unroll
-            for (int u = 0; u < kWalkGroup; ++u) mult[u] = j0 + u < n ? T.wsum[e0 + u] : 0ull;
+                for (int u = 0; u < kWalkGroup; ++u) mult[u] = j0 + u < n ? T.wsum[e0 + u] : 0ull;
+            }
         }
         const uint32_t rem = B.len[m] > 0 ? (uint32_t)B.len[m] - skip : 0u;
         const uint32_t lsrc = (uint32_t)B.boff[m] + skip;                             // first byte to read, in ldsb
@@ -271,19 +287,17 @@ __device__ __forceinline__ void batch_walk_impl(const Tables &T, const uint16_t 
             if (j0 + u >= n) cur[u] = 0;  // padding
             else if (HASH) term += mult[u] * (uint64_t)cur[u];
         }
-        if (w) {  // null: the caller needs the end states only in the hash and in `keep`
-            uint16_t *dst = w + (uint32_t)B.wstart[m] + j0;
-#pragma unroll
-            for (int u = 0; u < kWalkGroup; ++u) dst[u] = (uint16_t)cur[u];
-        }
+        // the four end states as one 8-byte store each way (both regions are 8-byte aligned: a slot's
+        // region in w starts at a multiple of the group size, a kept vector at a multiple of 8 entries)
+        const uint2 packed = make_uint2(cur[0] | (cur[1] << 16), cur[2] | (cur[3] << 16));
+        if (w) *reinterpret_cast<uint2 *>(w + (uint32_t)B.wstart[m] + j0) = packed;  // null: only hash and `keep` are wanted
         if (keep && j0 < keep_stride) {
             uint16_t *kd = keep + (size_t)m * keep_stride + j0;
-#pragma unroll
-            for (int u = 0; u < kWalkGroup; ++u) kd[u] = (uint16_t)cur[u];
+            *reinterpret_cast<uint2 *>(kd) = packed;
             // a kept vector is compared 8 entries at a time: the token's last group also zeroes
             // what lies between its own end and the next multiple of 8 (keep_stride is one)
-            if (kWalkGroup < 8 && j0 + kWalkGroup >= n)
-                for (uint32_t j = j0 + kWalkGroup; j < ((n + 7u) & ~7u) && j < keep_stride; ++j) kd[j - j0] = 0;
+            if (j0 + kWalkGroup >= n && j0 + kWalkGroup < ((n + 7u) & ~7u) && j0 + kWalkGroup < keep_stride)
+                *reinterpret_cast<uint2 *>(kd + kWalkGroup) = make_uint2(0u, 0u);
         }
         if (HASH) atomicAdd(&B.hash[m], (unsigned long long)term);
     }
