@@ -368,7 +368,7 @@ ComposeWorkspace carve_compose_ws(void *ws, int32_t V) {
     Carver c(ws);
     ComposeWorkspace w;
     uint32_t cap = 1024;
-    while (cap < 2u * (uint32_t)V) cap <<= 1;
+    while (cap < (1u << 31) && cap < 2u * (uint32_t)V) cap <<= 1;  // (V < 2^31: the product cannot wrap)
     w.capacity = cap;
     w.slots = c.take<unsigned long long>(cap);
     w.parent = c.take<int32_t>((size_t)V);
