@@ -29,7 +29,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // table read from L2 (S > 256): threads per workgroup and tokens per chunk
 constexpr int kWalkThreads = 256;
-constexpr int kWalkChunkTokens = 64;
+constexpr int kWalkChunkTokens = 32;  // (measured 16, 24, 32, 40, 48, 64: 32 is best when rows are stored, flat otherwise)
 
 struct WalkArgs {
     const uint8_t *tok_bytes;
