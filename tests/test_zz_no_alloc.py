@@ -103,3 +103,56 @@ def test_static_entry_point_refuses_what_does_not_fit():
         lib.cfgzip_signatures_static(tb, to, tt, None, h)
     # bad arguments answer before any device work, as for the workspace entry point
     assert raw.cfgzip_signatures_static(None, None, 1, None, 5, None, None, ctypes.c_uint64(1), None) == -1
+
+
+def test_static_entry_point_and_decode_step_in_a_captured_graph():
+    """What the entry point is for: a HIP graph captures cfgzip_signatures_static and
+    cfgzip_decode_step (neither allocates); the graph is replayed several times, with eager work and
+    waits in between, and every replay is checked against the oracle."""
+    import oracle
+    import paper_2605_29986_amd as lib
+    from gpu_util import dev, hash_np, logits_dev, logits_bits
+    cfg = si.make_config(1)
+    vocab, table = cfg["vocab"], cfg["table"]
+    V, S = vocab.V, cfg["S"]
+    want_sig = oracle.signatures(vocab.tok_bytes, vocab.tok_off, table)
+    want_c, want_r = oracle.build_classes(want_sig, vocab.tok_off)
+    C, B = len(want_r), 8
+    d = si.make_decode_inputs(321, B, V, C, "bf16", sigma=2.0)
+    want_bits = oracle.expand_mask(d["cls_bits"], want_c, C)
+    want_logits = oracle.apply_mask(d["logits"], want_bits, "bf16")
+    want_rep = oracle.map_to_rep(d["tok"], want_c, want_r)
+
+    tb, to, tt = dev(vocab.tok_bytes), dev(vocab.tok_off), dev(table)
+    sig = torch.zeros((V, S), dtype=torch.uint16, device="cuda")
+    h = torch.zeros((V,), dtype=torch.int64, device="cuda")
+    pristine = logits_dev(d["logits"], "bf16")
+    logits = pristine.clone()
+    cls, c_d, r_d, tok = dev(d["cls_bits"]), dev(want_c), dev(want_r), dev(d["tok"])
+    tbits = torch.zeros((B, (V + 31) // 32), dtype=torch.int32, device="cuda")
+    rep = torch.zeros((B,), dtype=torch.int32, device="cuda")
+
+    def step():
+        lib.cfgzip_signatures_static(tb, to, tt, sig, h, hash_seed=SEED)
+        lib.cfgzip_decode_step(logits, cls, c_d, C, tok, r_d, tok_bits_out=tbits, rep_out=rep)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                      # first call on this device outside the capture: it looks the array up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay in range(4):
+        print(f"replay {replay}", flush=True)
+        logits.copy_(pristine)      # eager work between the replays
+        sig.zero_(), h.zero_(), tbits.zero_(), rep.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (sig.cpu().numpy() == want_sig).all(), replay
+        assert (hash_np(h) == oracle.signature_hash(want_sig, SEED)).all(), replay
+        assert (logits_bits(logits) == want_logits).all(), replay
+        assert (tbits.cpu().numpy() == want_bits).all() and (rep.cpu().numpy() == want_rep).all(), replay
